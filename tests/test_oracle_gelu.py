@@ -1,0 +1,131 @@
+"""Pins for the oracle's integer polynomial GELU (Section 4.3, Eq. 2, 3, 5)."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import prepare, ref
+
+ALL_I8 = np.arange(-128, 128, dtype=np.int8)
+# the paper's L-infinity error of each GELU approximation (its error table)
+LINF = {0: 0.0182, 1: 0.0093}
+
+
+def gelu_real(x):
+    return 0.5 * x * (1.0 + math.erf(x / math.sqrt(2.0)))
+
+
+def poly_gelu_real(x, variant):
+    p, a, b = prepare.POLY[variant]
+    z = x / math.sqrt(2.0)
+    l = math.copysign(1.0, z) * (a * (min(abs(z), -b) + b) ** p + 1.0) if z != 0 else 0.0
+    return 0.5 * x * (1.0 + l)
+
+
+def test_hand_worked_values(golden_dir):
+    with open(os.path.join(golden_dir, "gelu_values.txt")) as fh:
+        lines = [l.strip() for l in fh if l.strip() and not l.startswith("#")]
+    assert lines
+    for line in lines:
+        head, xs, ys = [[int(v) for v in part.split()] for part in line.split("|")]
+        variant, q_b, q_c, k, m, s, zp_in, zp_out, maxq = head
+        p = ref.GeluParams(variant, q_b, q_c, k, zp_in, maxq, 1, 0,
+                           ref.Dyadic(m, s, zp_out, -128, 127))
+        assert ref.gelu_i8(np.array(xs, np.int8), p).tolist() == ys
+        # the constants in the file are also what the derivation gives
+        d = prepare.gelu_prepare(2.0 ** -4, 2.0 ** -5, zp_in, zp_out, variant, maxq)
+        assert (d.q_b, d.q_c, d.k, d.post.m, d.post.s) == (q_b, q_c, k, m, s)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("log2_s", [-4, -5, -7, -10])
+@pytest.mark.parametrize("zp_in", [0, -17])
+def test_all_256_inputs_against_erf_gelu(variant, log2_s, zp_in):
+    s_in = 2.0 ** log2_s * 1.07
+    vals = [gelu_real(s_in * (q - zp_in)) for q in range(-128, 128)]
+    # output quantizer with headroom for the approximation error, so nothing clips
+    lo, hi = min(vals) - 0.03, max(vals) + 0.03
+    s_out = (hi - lo) / 255.0
+    zp_out = int(round(-128 - lo / s_out))
+    p = prepare.gelu_prepare(s_in, s_out, zp_in, zp_out, variant)
+    y = ref.gelu_i8(ALL_I8, p).astype(np.int64)
+    got = (y - zp_out) * s_out
+    want = np.array(vals)
+    # paper's L-inf of the polynomial + floor of q_b (moves the clip point by < S_e,
+    # slope of x/2 * L' stays below 0.4) + floor of q_c and the shift k + output rounding
+    # + 15-bit multiplier
+    tol = LINF[variant] + 0.4 * s_in + s_out * 0.5 + np.abs(want) * 2.0 ** -14 + 1e-4
+    assert np.all(np.abs(got - want) <= tol), np.abs(got - want).max()
+    # and much closer to the polynomial itself than to erf-GELU
+    poly = np.array([poly_gelu_real(s_in * (q - zp_in), variant) for q in range(-128, 128)])
+    tol2 = 0.4 * s_in + s_out * 0.5 + np.abs(poly) * 2.0 ** -14 + 1e-4
+    assert np.all(np.abs(got - poly) <= tol2), np.abs(got - poly).max()
+
+
+def test_error_shrinks_with_the_scale_to_the_papers_bound():
+    # fine scales: what remains is the polynomial's own error, which the paper bounds
+    for variant in (0, 1):
+        s_in = 2.0 ** -6       # inputs cover (-2, 2)
+        s_out = 2.0 ** -9
+        p = prepare.gelu_prepare(s_in, s_out, 0, 0, variant)
+        p.post.qmin, p.post.qmax = -128, 127
+        q = np.arange(-60, 61, dtype=np.int8)    # outputs stay unclipped: |GELU| < 0.25
+        q = q[np.abs([gelu_real(s_in * int(v)) for v in q]) < 0.24]
+        y = ref.gelu_i8(q, p).astype(np.float64) * s_out
+        want = np.array([gelu_real(s_in * int(v)) for v in q])
+        assert np.abs(y - want).max() <= LINF[variant] + 0.5 * s_out + 0.4 * s_in
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_closed_forms(variant):
+    s_in, s_out = 2.0 ** -4, 2.0 ** -5
+    p = prepare.gelu_prepare(s_in, s_out, 3, -20, variant)
+    y = ref.gelu_i8(ALL_I8, p).astype(np.int64)
+    q = ALL_I8.astype(np.int64) - 3
+    # x = 0 gives exactly the zero-point
+    assert y[q == 0][0] == -20
+    # beyond the clip point on the negative side 1 + L is exactly 0
+    assert np.all(y[q <= p.q_b] == -20)
+    # beyond it on the positive side GELU is the identity: y = zp + x * S_in / S_out
+    far = q >= -p.q_b
+    want = np.clip(np.rint(q[far] * s_in / s_out) - 20, -128, 127)
+    assert np.all(np.abs(y[far] - want) <= 1)
+
+
+def test_monotone_for_positive_inputs_and_sign_of_negative_lobe():
+    p = prepare.gelu_prepare(2.0 ** -5, 2.0 ** -6, 0, 0, 1)
+    y = ref.gelu_i8(ALL_I8, p).astype(np.int64)
+    assert np.all(np.diff(y[128:]) >= 0)
+    assert np.all(y[:128] <= 0) and y[:128].min() >= -round(0.17 / 2.0 ** -6) - 1
+
+
+def test_max_abs_q_clamp_and_i32_entry():
+    p = prepare.gelu_prepare(2.0 ** -6, 2.0 ** -4, 0, 0, 1, max_abs_q=1000)
+    x = np.array([-10 ** 9, -1001, -1000, -5, 0, 5, 1000, 1001, 2 ** 31 - 1], np.int32)
+    y = ref.gelu_i32(x, p)
+    yc = ref.gelu_i32(np.clip(x, -1000, 1000), p)
+    assert np.array_equal(y, yc)
+    # with a requantization in front: same as requantizing first
+    p2 = prepare.gelu_prepare(2.0 ** -6, 2.0 ** -4, 0, 0, 1, max_abs_q=1000)
+    p2.pre_m, p2.pre_s = 20000, 22
+    x2 = np.arange(-300000, 300000, 997, dtype=np.int32)
+    pre = np.floor(x2.astype(np.float64) * 20000 / 2 ** 22 + 0.5).astype(np.int32)
+    assert np.array_equal(ref.gelu_i32(x2, p2), ref.gelu_i32(pre, p))
+    # int8 entry equals int32 entry on the int8 range
+    p8 = prepare.gelu_prepare(2.0 ** -5, 2.0 ** -5, 4, -9, 0)
+    assert np.array_equal(ref.gelu_i8(ALL_I8, p8), ref.gelu_i32(ALL_I8.astype(np.int32), p8))
+
+
+def test_rejects_bad_params():
+    good = prepare.gelu_prepare(2.0 ** -5, 2.0 ** -5, 0, 0, 1)
+    x = np.zeros(4, np.int8)
+    ref.gelu_i8(x, good)
+    for field, val in (("variant", 2), ("q_b", 0), ("q_c", 0), ("k", 63), ("k", 0),
+                       ("max_abs_q", 0), ("q_b", -40000)):
+        bad = prepare.gelu_prepare(2.0 ** -5, 2.0 ** -5, 0, 0, 1)
+        setattr(bad, field, val)
+        if field == "k" and val == 0 and good.k == 0:
+            continue
+        with pytest.raises(ref.OracleError):
+            ref.gelu_i8(x, bad)
