@@ -1,0 +1,196 @@
+/*
+ * iptq.h - C ABI of the MI355X (gfx950) integer-only non-linear layers of IPTQ-ViT
+ * (arXiv 2511.15369): bit-shifting Softmax (Section 4.4), polynomial GELU (Section 4.3)
+ * and the dyadic multiply-then-shift requantization around both.
+ *
+ * General rules of every entry point
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; the library never
+ *     allocates, frees or retains them.  Parameter structs are HOST pointers and are
+ *     copied before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work: they return before the kernels finish and never synchronise.
+ *   - Return value: IPTQ_OK (0) or a negative IPTQ_ERR_* code.  All argument checks run
+ *     on the host before anything is enqueued: on an error other than IPTQ_ERR_HIP no
+ *     kernel was launched and the outputs are untouched.
+ *   - The library keeps no state; calls on different streams may overlap freely as long
+ *     as their output buffers do not.
+ *   - Arithmetic conventions: x >> k on a negative integer is floor(x / 2^k);
+ *     rshr_round(v, s) = (v + 2^(s-1)) >> s for s >= 1 and v for s == 0 (ties go up).
+ *   - The kernels contain integer instructions only (no floating point, no matrix cores).
+ */
+#ifndef IPTQ_H
+#define IPTQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IPTQ_OK 0
+#define IPTQ_ERR_NULL (-1)  /* a required pointer is NULL */
+#define IPTQ_ERR_SHAPE (-2) /* negative count, cols outside [1, IPTQ_COLS_MAX], rows >= 2^31 */
+#define IPTQ_ERR_PARAM (-3) /* a parameter is outside its documented domain */
+#define IPTQ_ERR_RANGE (-4) /* parameters are valid one by one but could overflow the fixed-width path */
+#define IPTQ_ERR_HIP (-5)   /* the HIP runtime refused the launch */
+#define IPTQ_ERR_ALIGN (-6) /* a pointer is not aligned to its element type */
+
+#define IPTQ_COLS_MAX 65536
+
+/* Softmax fractional-part approximation of 2^(S(-r)) (the per-layer choice of Section 4.2) */
+#define IPTQ_SOFTMAX_SHIFT_LINEAR 0     /* 1 + x/2            (Eq. 10) */
+#define IPTQ_SOFTMAX_EFFICIENT_BITEXP 1 /* 1 + (0.1011)b x    (Eq. 12-14) */
+/* GELU erf polynomial */
+#define IPTQ_GELU_POLY2 0            /* second order a(x+b)^2 + c form (Eq. 2) */
+#define IPTQ_GELU_POLY4_DATA_AWARE 1 /* quartic, a = -0.019913, b = -2.698088 (Eq. 3) */
+
+/* algo field: which kernel family serves the call (results are identical) */
+#define IPTQ_ALGO_AUTO 0
+#define IPTQ_ALGO_GENERIC 1 /* softmax: one wavefront per row, any cols; GELU: polynomial per element */
+
+/*
+ * y = clamp(rshr_round(x * m, s) + zp, qmin, qmax)
+ * |m| < 2^15, 0 <= s <= 62, qmin <= qmax inside the output type ([0,255] or [-128,127]).
+ */
+typedef struct {
+    int32_t m;
+    int32_t s;
+    int32_t zp;
+    int32_t qmin;
+    int32_t qmax;
+} iptq_dyadic_t;
+
+/*
+ * Integer softmax of one row x[0..cols) of int32 scores (Section 4.4):
+ *   0. x_j == INT32_MIN means "minus infinity" (masked) at every stage below;
+ *      otherwise x_j = sat32(x_j + bias_j) when a bias is given, then
+ *      x_j = sat32(rshr_round(x_j * pre_m, pre_s)) unless (pre_m, pre_s) == (1, 0)
+ *   1. d_j = max(x_j - max_j x_j, -2^30)                                  (Eq. 6)
+ *   2. Qp = d + (d >> 1) - (d >> 4)                                       (Eq. 7)
+ *   3. n = -Qp, q = n div i0, r = n mod i0                                (Eq. 8)
+ *   4. base = i0 + ((-r) >> 1)                       variant 0            (Eq. 10)
+ *      base = i0 + ((-r) >> 1) + ((-r) >> 3) + ((-r) >> 4)  variant 1     (Eq. 13-14)
+ *   5. Qexp_j = 0 if masked or q >= 32, else (base << n_shift) >> q       (Eq. 9)
+ *   6. f = floor(2^m_bits / sum_j Qexp_j)  (0 for an all-masked row)
+ *      p_j = (f * Qexp_j) >> (m_bits - (out_bits - 1))                    (Eq. 15)
+ *   7. out_j = clamp(rshr_round(p_j * post.m, post.s) + post.zp, post.qmin, post.qmax)
+ * Domain: variant in {0,1}; 16 <= i0 < 2^24; n_shift >= 0 with (i0 << n_shift) < 2^24;
+ * 2 <= out_bits <= 8; out_bits - 1 <= m_bits <= 31; cols * (i0 << n_shift) <= 2^m_bits
+ * (else IPTQ_ERR_RANGE); 1 <= pre_m < 2^15; 0 <= pre_s <= 62.
+ */
+typedef struct {
+    int32_t variant;
+    int32_t i0;      /* floor(1 / S_delta) (Eq. 14) */
+    int32_t n_shift; /* guard bits N; 0 is the literal Eq. 14 */
+    int32_t m_bits;  /* M of Eq. 15 */
+    int32_t out_bits; /* b of Eq. 15 */
+    int32_t pre_m;
+    int32_t pre_s;
+    iptq_dyadic_t post;
+    int32_t out_is_signed; /* 0: uint8_t output, 1: int8_t output */
+    int32_t algo;          /* IPTQ_ALGO_* */
+} iptq_softmax_params_t;
+
+/*
+ * Integer polynomial GELU of one value (Section 4.3, Eq. 3 and Eq. 5), p = 2 or 4:
+ *   0. (int32 entry only) in = sat32(rshr_round(in * pre_m, pre_s)) unless (1, 0)
+ *   1. q = clamp(in - zp_in, -max_abs_q, max_abs_q)
+ *   2. t = min(|q|, -q_b) + q_b            in [q_b, 0]
+ *   3. u = t^p + q_c                       (the square is reused for the quartic)
+ *   4. v = (sign(q) * u + q_c) >> k        (1 + L on the scale where 1 is q_c / 2^k)
+ *   5. w = q * v
+ *   6. y = clamp(rshr_round(w * post.m, post.s) + post.zp, post.qmin, post.qmax)
+ * Domain: q_b < 0 (|q_b| < 2^15 for p = 4, <= 2^30 for p = 2); q_c < 0; 0 <= k <= 62;
+ * max_abs_q >= 1; ((|q_b|^p + 2|q_c|) >> k) * max_abs_q < 2^31 and |q_b|^p < 2^61,
+ * |q_c| < 2^60 (else IPTQ_ERR_RANGE); for the int8 entry |zp_in| <= 128.
+ */
+typedef struct {
+    int32_t variant;
+    int32_t q_b;
+    int64_t q_c;
+    int32_t k;
+    int32_t zp_in;
+    int32_t max_abs_q;
+    int32_t pre_m;
+    int32_t pre_s;
+    iptq_dyadic_t post; /* int8 output: qmin >= -128, qmax <= 127 */
+    int32_t algo;       /* IPTQ_ALGO_AUTO: int8 input evaluates the polynomial once per input
+                           code into a 256-entry table per workgroup and gathers;
+                           IPTQ_ALGO_GENERIC: polynomial per element */
+} iptq_gelu_params_t;
+
+/* Library version (major * 10000 + minor * 100 + patch). */
+int iptq_version(void);
+
+/* Static text for a return code. */
+const char *iptq_strerror(int code);
+
+/*
+ * Requantization of an int32 tensor (the formula of iptq_dyadic_t).
+ * d_in: n int32 (device, 4-byte aligned); d_out: n uint8_t (out_is_signed == 0) or int8_t
+ * (== 1) (device); n >= 0 (0 is a successful no-op); p: host.
+ */
+int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t out_is_signed,
+                 const iptq_dyadic_t *p, void *stream);
+
+/*
+ * Integer softmax over every row of a row-major [rows, cols] int32 score matrix
+ * (Section 4.4, Eq. 6-15; steps listed at iptq_softmax_params_t).
+ * d_scores: rows * cols int32 (device); d_bias: NULL or a row-major
+ * [bias_period_rows, cols] int32 (device) added to row r from its row
+ * (r mod bias_period_rows) - the Swin relative-position bias with
+ * bias_period_rows = heads * window_tokens; d_out: rows * cols bytes (device), uint8_t or
+ * int8_t per p->out_is_signed, must not overlap d_scores.
+ * 0 <= rows < 2^31 (0 is a no-op), 1 <= cols <= IPTQ_COLS_MAX.
+ */
+int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias, int64_t bias_period_rows,
+                     void *d_out, int64_t rows, int32_t cols, const iptq_softmax_params_t *p,
+                     void *stream);
+
+/*
+ * Integer GELU (Section 4.3, Eq. 3 and 5; steps listed at iptq_gelu_params_t) of n int8
+ * activations.  d_out may equal d_in (in place); partial overlap is not allowed.
+ */
+int iptq_gelu_i8(const int8_t *d_in, int8_t *d_out, int64_t n, const iptq_gelu_params_t *p,
+                 void *stream);
+
+/* Same on int32 accumulators with the requantization (pre_m, pre_s) fused in front. */
+int iptq_gelu_i32(const int32_t *d_in, int8_t *d_out, int64_t n, const iptq_gelu_params_t *p,
+                  void *stream);
+
+/*
+ * Layer-batched forms for model sweeps: layer l reads d_scores + l * in_stride (elements)
+ * and writes d_out + l * out_stride (bytes) with p[l]; all layers share rows and cols (or n).
+ * Equivalent to n_layers single calls on `stream`; the per-layer variant choice of
+ * Section 4.2 is the `variant` field of each p[l].  No bias.
+ */
+int iptq_softmax_i32_layers(const int32_t *d_scores, int64_t in_stride, void *d_out,
+                            int64_t out_stride, int64_t rows, int32_t cols, int32_t n_layers,
+                            const iptq_softmax_params_t *p, void *stream);
+int iptq_gelu_i8_layers(const int8_t *d_in, int64_t in_stride, int8_t *d_out, int64_t out_stride,
+                        int64_t n, int32_t n_layers, const iptq_gelu_params_t *p, void *stream);
+
+/*
+ * Host-only helpers: real scales -> integer constants, once, before inference
+ * ("pre-quantized as a constant", Section 4.3; floor(1/S), Eq. 14).  IEEE double.
+ */
+
+/* ratio ~ m / 2^s with |m| in [2^14, 2^15) and the largest s <= 62 (see the .cpp for ties). */
+int iptq_make_dyadic(double ratio, int32_t *m, int32_t *s);
+
+/* i0 = floor(1/s_delta); n_shift = max(0, 15 - bitlen(i0)) lowered until
+ * cols * (i0 << n_shift) <= 2^30; m_bits = 30; out_bits = 8; identity pre/post
+ * (int8 output clips the code 128 to 127). */
+int iptq_softmax_prepare(double s_delta, int32_t cols, int32_t variant, int32_t out_is_signed,
+                         iptq_softmax_params_t *out);
+
+/* S_e = s_in / sqrt 2; q_b = floor(b / S_e); q_c = floor(1 / (a S_e^p));
+ * k = smallest shift keeping q * v inside int32 for |q| <= max_abs_q;
+ * post = dyadic(s_in * a * S_e^p * 2^k / 2 / s_out), zero-point zp_out, int8 clip. */
+int iptq_gelu_prepare(double s_in, double s_out, int32_t zp_in, int32_t zp_out, int32_t variant,
+                      int32_t max_abs_q, iptq_gelu_params_t *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IPTQ_H */

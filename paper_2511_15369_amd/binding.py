@@ -1,0 +1,203 @@
+"""ctypes binding of ``libiptq.so``: argument marshalling only.
+
+Every function has the name and the argument order of its C entry point
+(``include/iptq.h``).  Device tensors are torch tensors on the GPU; only their
+``data_ptr()`` crosses the boundary, together with the current torch stream.
+There is no CPU fallback: if the library is missing, loading raises.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libiptq.so")
+_lib = None
+
+ALGO_AUTO = 0
+ALGO_GENERIC = 1
+
+
+class IptqError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__("%s failed: %s (code %d)" % (what, strerror(code), code))
+
+
+class Dyadic(ctypes.Structure):
+    _fields_ = [("m", ctypes.c_int32), ("s", ctypes.c_int32), ("zp", ctypes.c_int32),
+                ("qmin", ctypes.c_int32), ("qmax", ctypes.c_int32)]
+
+
+class SoftmaxParams(ctypes.Structure):
+    _fields_ = [("variant", ctypes.c_int32), ("i0", ctypes.c_int32), ("n_shift", ctypes.c_int32),
+                ("m_bits", ctypes.c_int32), ("out_bits", ctypes.c_int32),
+                ("pre_m", ctypes.c_int32), ("pre_s", ctypes.c_int32),
+                ("post", Dyadic), ("out_is_signed", ctypes.c_int32), ("algo", ctypes.c_int32)]
+
+
+class GeluParams(ctypes.Structure):
+    _fields_ = [("variant", ctypes.c_int32), ("q_b", ctypes.c_int32), ("q_c", ctypes.c_int64),
+                ("k", ctypes.c_int32), ("zp_in", ctypes.c_int32), ("max_abs_q", ctypes.c_int32),
+                ("pre_m", ctypes.c_int32), ("pre_s", ctypes.c_int32), ("post", Dyadic),
+                ("algo", ctypes.c_int32)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load the shared library (built by ``python -m paper_2511_15369_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libiptq.so is not built: run `python -m paper_2511_15369_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    lib.iptq_version.restype = ctypes.c_int
+    lib.iptq_strerror.restype = ctypes.c_char_p
+    lib.iptq_strerror.argtypes = [ctypes.c_int]
+    lib.iptq_requant.argtypes = [vp, vp, i64, i32, ctypes.POINTER(Dyadic), vp]
+    lib.iptq_softmax_i32.argtypes = [vp, vp, i64, vp, i64, i32, ctypes.POINTER(SoftmaxParams), vp]
+    lib.iptq_gelu_i8.argtypes = [vp, vp, i64, ctypes.POINTER(GeluParams), vp]
+    lib.iptq_gelu_i32.argtypes = [vp, vp, i64, ctypes.POINTER(GeluParams), vp]
+    lib.iptq_softmax_i32_layers.argtypes = [vp, i64, vp, i64, i64, i32, i32,
+                                            ctypes.POINTER(SoftmaxParams), vp]
+    lib.iptq_gelu_i8_layers.argtypes = [vp, i64, vp, i64, i64, i32, ctypes.POINTER(GeluParams), vp]
+    lib.iptq_make_dyadic.argtypes = [ctypes.c_double, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.iptq_softmax_prepare.argtypes = [ctypes.c_double, i32, i32, i32,
+                                         ctypes.POINTER(SoftmaxParams)]
+    lib.iptq_gelu_prepare.argtypes = [ctypes.c_double, ctypes.c_double, i32, i32, i32, i32,
+                                      ctypes.POINTER(GeluParams)]
+    for name in ("iptq_requant", "iptq_softmax_i32", "iptq_gelu_i8", "iptq_gelu_i32",
+                 "iptq_softmax_i32_layers", "iptq_gelu_i8_layers", "iptq_make_dyadic",
+                 "iptq_softmax_prepare", "iptq_gelu_prepare"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def version() -> int:
+    return int(load().iptq_version())
+
+
+def strerror(code: int) -> str:
+    return load().iptq_strerror(int(code)).decode()
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise IptqError(rc, what)
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dptr(t) -> Optional[int]:
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _need(t, dtype, what):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous %s tensor on the GPU" % (what, dtype))
+
+
+# ----------------------------------------------------------------------------- host helpers
+def make_dyadic(ratio: float):
+    m, s = ctypes.c_int32(), ctypes.c_int32()
+    _check(load().iptq_make_dyadic(ratio, ctypes.byref(m), ctypes.byref(s)), "iptq_make_dyadic")
+    return m.value, s.value
+
+
+def softmax_prepare(s_delta: float, cols: int, variant: int, out_is_signed: int = 0) -> SoftmaxParams:
+    p = SoftmaxParams()
+    _check(load().iptq_softmax_prepare(s_delta, cols, variant, out_is_signed, ctypes.byref(p)),
+           "iptq_softmax_prepare")
+    return p
+
+
+def gelu_prepare(s_in: float, s_out: float, zp_in: int, zp_out: int, variant: int,
+                 max_abs_q: int = 255) -> GeluParams:
+    p = GeluParams()
+    _check(load().iptq_gelu_prepare(s_in, s_out, zp_in, zp_out, variant, max_abs_q,
+                                    ctypes.byref(p)), "iptq_gelu_prepare")
+    return p
+
+
+# ----------------------------------------------------------------------------- device calls
+def requant(d_in, d_out, n: int, out_is_signed: int, p: Dyadic):
+    import torch
+    _need(d_in, torch.int32, "d_in")
+    _need(d_out, torch.int8 if out_is_signed else torch.uint8, "d_out")
+    assert d_in.numel() >= n and d_out.numel() >= n
+    _check(load().iptq_requant(_dptr(d_in), _dptr(d_out), n, out_is_signed, ctypes.byref(p),
+                               _stream()), "iptq_requant")
+
+
+def softmax_i32(d_scores, d_bias, bias_period_rows: int, d_out, rows: int, cols: int,
+                p: SoftmaxParams):
+    import torch
+    _need(d_scores, torch.int32, "d_scores")
+    _need(d_out, torch.int8 if p.out_is_signed else torch.uint8, "d_out")
+    assert d_scores.numel() >= rows * cols and d_out.numel() >= rows * cols
+    if d_bias is not None:
+        _need(d_bias, torch.int32, "d_bias")
+        assert d_bias.numel() >= bias_period_rows * cols
+    _check(load().iptq_softmax_i32(_dptr(d_scores), _dptr(d_bias), bias_period_rows, _dptr(d_out),
+                                   rows, cols, ctypes.byref(p), _stream()), "iptq_softmax_i32")
+
+
+def gelu_i8(d_in, d_out, n: int, p: GeluParams):
+    import torch
+    _need(d_in, torch.int8, "d_in")
+    _need(d_out, torch.int8, "d_out")
+    assert d_in.numel() >= n and d_out.numel() >= n
+    _check(load().iptq_gelu_i8(_dptr(d_in), _dptr(d_out), n, ctypes.byref(p), _stream()),
+           "iptq_gelu_i8")
+
+
+def gelu_i32(d_in, d_out, n: int, p: GeluParams):
+    import torch
+    _need(d_in, torch.int32, "d_in")
+    _need(d_out, torch.int8, "d_out")
+    assert d_in.numel() >= n and d_out.numel() >= n
+    _check(load().iptq_gelu_i32(_dptr(d_in), _dptr(d_out), n, ctypes.byref(p), _stream()),
+           "iptq_gelu_i32")
+
+
+def softmax_i32_layers(d_scores, in_stride: int, d_out, out_stride: int, rows: int, cols: int,
+                       n_layers: int, params: Sequence[SoftmaxParams]):
+    import torch
+    _need(d_scores, torch.int32, "d_scores")
+    assert len(params) == n_layers
+    signed = params[0].out_is_signed if n_layers else 0
+    _need(d_out, torch.int8 if signed else torch.uint8, "d_out")
+    if n_layers:
+        assert d_scores.numel() >= (n_layers - 1) * in_stride + rows * cols
+        assert d_out.numel() >= (n_layers - 1) * out_stride + rows * cols
+    arr = (SoftmaxParams * max(n_layers, 1))(*params)
+    _check(load().iptq_softmax_i32_layers(_dptr(d_scores), in_stride, _dptr(d_out), out_stride,
+                                          rows, cols, n_layers, arr, _stream()),
+           "iptq_softmax_i32_layers")
+
+
+def gelu_i8_layers(d_in, in_stride: int, d_out, out_stride: int, n: int, n_layers: int,
+                   params: Sequence[GeluParams]):
+    import torch
+    _need(d_in, torch.int8, "d_in")
+    _need(d_out, torch.int8, "d_out")
+    assert len(params) == n_layers
+    if n_layers:
+        assert d_in.numel() >= (n_layers - 1) * in_stride + n
+        assert d_out.numel() >= (n_layers - 1) * out_stride + n
+    arr = (GeluParams * max(n_layers, 1))(*params)
+    _check(load().iptq_gelu_i8_layers(_dptr(d_in), in_stride, _dptr(d_out), out_stride, n,
+                                      n_layers, arr, _stream()), "iptq_gelu_i8_layers")

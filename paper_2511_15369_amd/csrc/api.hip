@@ -1,0 +1,145 @@
+// C ABI of the library: argument checks (host only), then one or two kernel launches on
+// the caller's stream.  Declarations and contracts: include/iptq.h.
+#include <hip/hip_runtime.h>
+
+#include "../../include/iptq.h"
+#include "device_common.h"
+#include "kernels.h"
+#include "plan.h"
+
+using namespace iptq;
+
+static int hip_rc(hipError_t e) { return e == hipSuccess ? IPTQ_OK : IPTQ_ERR_HIP; }
+
+static bool overlap(const void *a, int64_t na, const void *b, int64_t nb)
+{
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
+}
+
+extern "C" int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t out_is_signed,
+                            const iptq_dyadic_t *p, void *stream)
+{
+    if (!p) return IPTQ_ERR_NULL;
+    if (n < 0) return IPTQ_ERR_SHAPE;
+    DyadicDev dev;
+    int rc = plan_requant(p, out_is_signed, &dev);
+    if (rc != IPTQ_OK) return rc;
+    if (n == 0) return IPTQ_OK;
+    if (!d_in || !d_out) return IPTQ_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(d_in) & 3) return IPTQ_ERR_ALIGN;
+    if (overlap(d_in, n * 4, d_out, n)) return IPTQ_ERR_PARAM;
+    return hip_rc(requant_dispatch(d_in, d_out, n, dev, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias,
+                                int64_t bias_period_rows, void *d_out, int64_t rows, int32_t cols,
+                                const iptq_softmax_params_t *p, void *stream)
+{
+    if (!p) return IPTQ_ERR_NULL;
+    SoftmaxDev dev;
+    int rc = plan_softmax(p, rows, cols, d_bias != nullptr, bias_period_rows, &dev);
+    if (rc != IPTQ_OK) return rc;
+    if (rows == 0) return IPTQ_OK;
+    if (!d_scores || !d_out) return IPTQ_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(d_scores) & 3) || (reinterpret_cast<uintptr_t>(d_bias) & 3))
+        return IPTQ_ERR_ALIGN;
+    if (overlap(d_scores, rows * cols * 4, d_out, rows * cols)) return IPTQ_ERR_PARAM;
+    return hip_rc(softmax_dispatch(d_scores, d_bias, static_cast<uint8_t *>(d_out), rows, cols,
+                                   p->out_bits, p->algo == IPTQ_ALGO_GENERIC, dev,
+                                   static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int iptq_gelu_i8(const int8_t *d_in, int8_t *d_out, int64_t n,
+                            const iptq_gelu_params_t *p, void *stream)
+{
+    if (!p) return IPTQ_ERR_NULL;
+    if (n < 0) return IPTQ_ERR_SHAPE;
+    GeluDev dev;
+    int rc = plan_gelu(p, 1, &dev);
+    if (rc != IPTQ_OK) return rc;
+    if (n == 0) return IPTQ_OK;
+    if (!d_in || !d_out) return IPTQ_ERR_NULL;
+    if (d_in != d_out && overlap(d_in, n, d_out, n)) return IPTQ_ERR_PARAM;
+    return hip_rc(gelu_i8_dispatch(d_in, d_out, n, p->algo == IPTQ_ALGO_GENERIC, dev,
+                                   static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int iptq_gelu_i32(const int32_t *d_in, int8_t *d_out, int64_t n,
+                             const iptq_gelu_params_t *p, void *stream)
+{
+    if (!p) return IPTQ_ERR_NULL;
+    if (n < 0) return IPTQ_ERR_SHAPE;
+    GeluDev dev;
+    int rc = plan_gelu(p, 0, &dev);
+    if (rc != IPTQ_OK) return rc;
+    if (n == 0) return IPTQ_OK;
+    if (!d_in || !d_out) return IPTQ_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(d_in) & 3) return IPTQ_ERR_ALIGN;
+    if (overlap(d_in, n * 4, d_out, n)) return IPTQ_ERR_PARAM;
+    return hip_rc(gelu_i32_dispatch(d_in, d_out, n, dev, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int iptq_softmax_i32_layers(const int32_t *d_scores, int64_t in_stride, void *d_out,
+                                       int64_t out_stride, int64_t rows, int32_t cols,
+                                       int32_t n_layers, const iptq_softmax_params_t *p,
+                                       void *stream)
+{
+    if (!p) return IPTQ_ERR_NULL;
+    if (n_layers < 0 || in_stride < 0 || out_stride < 0) return IPTQ_ERR_SHAPE;
+    // validate every layer before the first launch
+    for (int32_t l = 0; l < n_layers; ++l) {
+        SoftmaxDev dev;
+        int rc = plan_softmax(&p[l], rows, cols, 0, 0, &dev);
+        if (rc != IPTQ_OK) return rc;
+    }
+    if (n_layers > 1 && rows > 0 && (in_stride < rows * cols || out_stride < rows * cols))
+        return IPTQ_ERR_SHAPE;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        int rc = iptq_softmax_i32(d_scores ? d_scores + l * in_stride : nullptr, nullptr, 0,
+                                  d_out ? static_cast<uint8_t *>(d_out) + l * out_stride : nullptr,
+                                  rows, cols, &p[l], stream);
+        if (rc != IPTQ_OK) return rc;
+    }
+    return IPTQ_OK;
+}
+
+extern "C" int iptq_gelu_i8_layers(const int8_t *d_in, int64_t in_stride, int8_t *d_out,
+                                   int64_t out_stride, int64_t n, int32_t n_layers,
+                                   const iptq_gelu_params_t *p, void *stream)
+{
+    if (!p) return IPTQ_ERR_NULL;
+    if (n_layers < 0 || in_stride < 0 || out_stride < 0 || n < 0) return IPTQ_ERR_SHAPE;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        GeluDev dev;
+        int rc = plan_gelu(&p[l], 1, &dev);
+        if (rc != IPTQ_OK) return rc;
+    }
+    if (n_layers > 1 && (in_stride < n || out_stride < n)) return IPTQ_ERR_SHAPE;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        int rc = iptq_gelu_i8(d_in ? d_in + l * in_stride : nullptr,
+                              d_out ? d_out + l * out_stride : nullptr, n, &p[l], stream);
+        if (rc != IPTQ_OK) return rc;
+    }
+    return IPTQ_OK;
+}
+
+// ---- host-side test hooks (not part of the public header): the same source the kernels
+// run, compiled for the host, so that integer helpers can be checked exhaustively without
+// a GPU.
+extern "C" uint32_t iptq_debug_floor_pow2_div(int32_t m_bits, uint32_t sigma)
+{
+    return floor_pow2_div(m_bits, sigma);
+}
+
+extern "C" int iptq_debug_softmax_plan(const iptq_softmax_params_t *p, int64_t rows, int32_t cols,
+                                       int32_t has_bias, int64_t bias_period_rows, int64_t *out8)
+{
+    SoftmaxDev dev;
+    int rc = plan_softmax(p, rows, cols, has_bias, bias_period_rows, &dev);
+    if (rc != IPTQ_OK || !out8) return rc;
+    out8[0] = dev.magic; out8[1] = dev.magic_sh; out8[2] = dev.d_clamp; out8[3] = dev.i0n;
+    out8[4] = dev.p_shift; out8[5] = dev.period_magic; out8[6] = dev.period_sh;
+    out8[7] = neg_qp_of(dev.d_clamp);
+    return rc;
+}

@@ -1,0 +1,176 @@
+// Integer-only device helpers shared by the gfx950 kernels.  Nothing in this file may
+// compile to a floating-point instruction: no '/' or '%' on run-time values (the compiler
+// lowers those through v_rcp_f32), no float types.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define IPTQ_DEV __device__ __forceinline__
+#define IPTQ_HD __host__ __device__ inline
+
+namespace iptq {
+
+constexpr int32_t kI32Min = (int32_t)0x80000000;
+
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Streaming accesses: every byte is touched once, so the loads and stores carry the
+// non-temporal hint and do not displace reusable lines (the bias table) from the caches.
+#ifndef IPTQ_NONTEMPORAL
+#define IPTQ_NONTEMPORAL 1
+#endif
+template <typename T>
+__device__ __forceinline__ T stream_load(const T *p)
+{
+#if IPTQ_NONTEMPORAL
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
+}
+template <typename T>
+__device__ __forceinline__ void stream_store(T v, T *p)
+{
+#if IPTQ_NONTEMPORAL
+    __builtin_nontemporal_store(v, p);
+#else
+    *p = v;
+#endif
+}
+
+IPTQ_HD uint32_t mulhi_u32(uint32_t a, uint32_t b)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __umulhi(a, b);
+#else
+    return (uint32_t)(((uint64_t)a * b) >> 32);
+#endif
+}
+
+IPTQ_HD int clz_u32(uint32_t v)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __clz((int)v);
+#else
+    return v ? __builtin_clz(v) : 32;
+#endif
+}
+
+// floor(2^m_bits / sigma) for 1 <= sigma <= 2^m_bits, 1 <= m_bits <= 31, without a divide
+// instruction: normalise sigma to y in [2^31, 2^32), run three Newton steps on the Q31
+// reciprocal (each keeps the estimate at or below the true value), scale back and finish
+// with an exact remainder correction.  sigma == 0 returns 0.
+IPTQ_HD uint32_t floor_pow2_div(int m_bits, uint32_t sigma)
+{
+    if (sigma == 0) return 0;
+    const int k = clz_u32(sigma);
+    const uint32_t y = sigma << k;                    // Y = y / 2^32 in [0.5, 1)
+    // X0 = 48/17 - 32/17 Y in Q30, then to Q31: relative error below 1/17, X0 < 1/Y
+    uint32_t r = (3031741620u - mulhi_u32(y, 2021161080u)) << 1;
+    for (int it = 0; it < 3; ++it) {
+        const uint32_t t = mulhi_u32(y, r);           // Y X in Q31, at most 2^31
+        const uint32_t u = 0u - t;                    // (2 - Y X) in Q31
+        r = mulhi_u32(r, u) << 1;                     // X (2 - Y X) in Q31, rounded down
+    }
+    // 2^m / sigma = (2^63 / y) * 2^(m + k - 63), r ~ 2^63 / y
+    const int sh = 63 - m_bits - k;                   // 1 <= sh <= 32
+    uint32_t f = sh >= 32 ? 0u : (r >> sh);
+    uint32_t rem = (1u << m_bits) - f * sigma;        // exact: f <= true quotient
+    while (rem >= sigma) { rem -= sigma; ++f; }
+    return f;
+}
+
+// clamp(rshr_round(x * m, s) + zp, qmin, qmax) for |x| < 2^31, |m| < 2^15, 0 <= s <= 62.
+// NARROW (s >= 16): the shifted value fits 32 bits.
+template <bool NARROW>
+IPTQ_DEV int32_t requant_dev(int32_t x, int32_t m, int32_t s, int32_t zp, int32_t qmin, int32_t qmax)
+{
+    const int64_t rnd = s > 0 ? ((int64_t)1 << (s - 1)) : 0;
+    const int64_t v = (int64_t)x * (int64_t)m + rnd;
+    if (NARROW) {
+        const int32_t r = (int32_t)(v >> s) + zp;
+        return min(max(r, qmin), qmax);
+    } else {
+        int64_t r = (v >> s) + (int64_t)zp;
+        r = r < (int64_t)qmin ? (int64_t)qmin : r;
+        r = r > (int64_t)qmax ? (int64_t)qmax : r;
+        return (int32_t)r;
+    }
+}
+
+// sat32(rshr_round(x * m, s)), 1 <= m < 2^15, 0 <= s <= 62
+IPTQ_DEV int32_t pre_requant_dev(int32_t x, int32_t m, int32_t s)
+{
+    const int64_t rnd = s > 0 ? ((int64_t)1 << (s - 1)) : 0;
+    int64_t v = ((int64_t)x * (int64_t)m + rnd) >> s;
+    v = v < (int64_t)INT32_MIN ? (int64_t)INT32_MIN : v;
+    v = v > (int64_t)INT32_MAX ? (int64_t)INT32_MAX : v;
+    return (int32_t)v;
+}
+
+IPTQ_DEV int32_t sat_add_i32(int32_t a, int32_t b)
+{
+    return __builtin_elementwise_add_sat(a, b);
+}
+
+// ---- cross-lane exchange on the DPP path (no LDS traffic) -----------------------------
+// DPP control words: quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E,
+// row_half_mirror = 0x141, row_mirror = 0x140.
+template <int CTRL>
+IPTQ_DEV int32_t dpp_i32(int32_t v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+
+// All-reduce over aligned groups of K lanes (K in {1,2,4,8,16}); every lane gets the result.
+template <int K>
+IPTQ_DEV int32_t group_max_i32(int32_t v)
+{
+    if (K >= 2) v = max(v, dpp_i32<0xB1>(v));
+    if (K >= 4) v = max(v, dpp_i32<0x4E>(v));
+    if (K >= 8) v = max(v, dpp_i32<0x141>(v));
+    if (K >= 16) v = max(v, dpp_i32<0x140>(v));
+    return v;
+}
+
+template <int K>
+IPTQ_DEV uint32_t group_sum_u32(uint32_t v)
+{
+    if (K >= 2) v += (uint32_t)dpp_i32<0xB1>((int32_t)v);
+    if (K >= 4) v += (uint32_t)dpp_i32<0x4E>((int32_t)v);
+    if (K >= 8) v += (uint32_t)dpp_i32<0x141>((int32_t)v);
+    if (K >= 16) v += (uint32_t)dpp_i32<0x140>((int32_t)v);
+    return v;
+}
+
+// Full 64-lane all-reduce: the 16-lane DPP rows first, then across rows through the
+// permute network.
+IPTQ_DEV int32_t wave_max_i32(int32_t v)
+{
+    v = group_max_i32<16>(v);
+    v = max(v, __shfl_xor(v, 16));
+    v = max(v, __shfl_xor(v, 32));
+    return v;
+}
+
+IPTQ_DEV uint32_t wave_sum_u32(uint32_t v)
+{
+    v = group_sum_u32<16>(v);
+    v += (uint32_t)__shfl_xor((int32_t)v, 16);
+    v += (uint32_t)__shfl_xor((int32_t)v, 32);
+    return v;
+}
+
+// Orders this wavefront's LDS accesses: what its lanes wrote before is visible to its
+// lanes after.  LDS executes a wavefront's instructions in issue order, so this only has
+// to stop the compiler from moving accesses across it.
+IPTQ_DEV void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+}  // namespace iptq

@@ -1,0 +1,256 @@
+// Element-wise integer kernels for gfx950: polynomial GELU (Section 4.3, Eq. 3 and 5) and
+// the dyadic requantization.  All of them stream: each 16-byte chunk is read once and
+// written once with dwordx4 accesses.
+#include <hip/hip_runtime.h>
+
+#include "device_common.h"
+#include "plan.h"
+
+namespace iptq {
+
+// One GELU value.  `in` is the already requantized input code.
+//   q = clamp(in - zp, +-max_abs_q); t = min(|q|, -q_b) + q_b; t^p (square reused);
+//   v = (sign(q) (t^p + q_c) + q_c) >> k; w = q v; y = requant(w).
+// For q >= 0 the numerator is t^p + 2 q_c; for q < 0 it is -t^p, and
+// floor(-a / 2^k) == ~floor((a - 1) / 2^k), so both signs share one 64-bit add and shift.
+template <bool NARROW>
+IPTQ_DEV int32_t gelu_eval_dev(int32_t in, const GeluDev &P)
+{
+    int32_t q = in - P.zp_in;                       // |in|, |zp| small enough on both entries
+    q = min(max(q, -P.max_abs_q), P.max_abs_q);
+    const int32_t aq = max(q, -q);
+    const int32_t t = min(aq, -P.q_b) + P.q_b;      // Eq. 3: clip at -b, add b
+    const int64_t t2 = (int64_t)t * (int64_t)t;     // < 2^30 for the quartic, < 2^60 otherwise
+    const int64_t tp = P.quartic ? (int64_t)((uint64_t)(uint32_t)t2 * (uint64_t)(uint32_t)t2) : t2;
+    const bool neg = q < 0;
+    const int64_t addend = neg ? (int64_t)-1 : 2 * P.q_c;
+    const int64_t z = (tp + addend) >> P.k;
+    const int32_t v = neg ? ~(int32_t)z : (int32_t)z;
+    const int32_t w = q * v;                        // Eq. 5: x (1 + L); 1/2 is in the scale
+    return requant_dev<NARROW>(w, P.post_m, P.post_s, P.post_zp, P.qmin, P.qmax);
+}
+
+IPTQ_DEV int32_t gelu_eval_any(int32_t in, const GeluDev &P)
+{
+    return P.post_s >= 16 ? gelu_eval_dev<true>(in, P) : gelu_eval_dev<false>(in, P);
+}
+
+IPTQ_DEV uint32_t pack4(int32_t a, int32_t b, int32_t c, int32_t d)
+{
+    return ((uint32_t)a & 0xffu) | (((uint32_t)b & 0xffu) << 8) | (((uint32_t)c & 0xffu) << 16) |
+           ((uint32_t)d << 24);
+}
+
+IPTQ_DEV int32_t sbyte(uint32_t w, int i) { return (int32_t)(int8_t)(w >> (8 * i)); }
+
+// ---------------------------------------------------------------------------------------
+// int8 -> int8 through a per-workgroup table: the polynomial is evaluated once for each of
+// the 256 input codes with the exact integer formula, then every element is one byte
+// gather from LDS.  n16 = number of whole 16-byte chunks; the last (n & 15) bytes are done
+// by workgroup 0.  in and out must be 16-byte aligned; they may be the same buffer.
+__global__ void __launch_bounds__(256)
+gelu_i8_table_kernel(const uint8_t *in, uint8_t *out, int64_t n, GeluDev P)
+{
+    __shared__ uint8_t table[256];
+    table[threadIdx.x] = (uint8_t)gelu_eval_any((int32_t)(int8_t)threadIdx.x, P);
+    __syncthreads();
+
+    const int64_t n16 = n >> 4;
+    const u32x4 *in4 = reinterpret_cast<const u32x4 *>(in);
+    u32x4 *out4 = reinterpret_cast<u32x4 *>(out);
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+        const u32x4 v = stream_load(in4 + i);
+        u32x4 r;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t w = v[d];
+            const uint32_t y0 = table[w & 0xffu];
+            const uint32_t y1 = table[(w >> 8) & 0xffu];
+            const uint32_t y2 = table[(w >> 16) & 0xffu];
+            const uint32_t y3 = table[w >> 24];
+            r[d] = y0 | (y1 << 8) | (y2 << 16) | (y3 << 24);
+        }
+        stream_store(r, out4 + i);
+    }
+    if (blockIdx.x == 0) {
+        const int64_t i = (n16 << 4) + threadIdx.x;
+        if (threadIdx.x < 16 && i < n) out[i] = table[in[i]];
+    }
+}
+
+// int8 -> int8, polynomial evaluated per element (no table).
+__global__ void __launch_bounds__(256)
+gelu_i8_direct_kernel(const uint8_t *in, uint8_t *out, int64_t n, GeluDev P)
+{
+    const int64_t n16 = n >> 4;
+    const u32x4 *in4 = reinterpret_cast<const u32x4 *>(in);
+    u32x4 *out4 = reinterpret_cast<u32x4 *>(out);
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const bool narrow = P.post_s >= 16;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+        const u32x4 v = stream_load(in4 + i);
+        u32x4 r;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t w = v[d];
+            if (narrow)
+                r[d] = pack4(gelu_eval_dev<true>(sbyte(w, 0), P), gelu_eval_dev<true>(sbyte(w, 1), P),
+                             gelu_eval_dev<true>(sbyte(w, 2), P), gelu_eval_dev<true>(sbyte(w, 3), P));
+            else
+                r[d] = pack4(gelu_eval_dev<false>(sbyte(w, 0), P), gelu_eval_dev<false>(sbyte(w, 1), P),
+                             gelu_eval_dev<false>(sbyte(w, 2), P), gelu_eval_dev<false>(sbyte(w, 3), P));
+        }
+        stream_store(r, out4 + i);
+    }
+    if (blockIdx.x == 0) {
+        const int64_t i = (n16 << 4) + threadIdx.x;
+        if (threadIdx.x < 16 && i < n) out[i] = (uint8_t)gelu_eval_any((int32_t)(int8_t)in[i], P);
+    }
+}
+
+// Unaligned or tiny int8 tensors: one element per thread.
+__global__ void __launch_bounds__(256)
+gelu_i8_bytes_kernel(const uint8_t *in, uint8_t *out, int64_t n, GeluDev P)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
+        out[i] = (uint8_t)gelu_eval_any((int32_t)(int8_t)in[i], P);
+}
+
+// int32 accumulators -> int8 with the requantization in front.  A thread owns 16
+// consecutive elements: four dwordx4 loads, one dwordx4 store.
+template <bool ALIGNED>
+__global__ void __launch_bounds__(256)
+gelu_i32_kernel(const int32_t *in, uint8_t *out, int64_t n, GeluDev P)
+{
+    const bool has_pre = !(P.pre_m == 1 && P.pre_s == 0);
+    GeluDev Q = P;
+    Q.zp_in = 0;
+    auto one = [&](int32_t x) -> int32_t {
+        if (has_pre) x = pre_requant_dev(x, P.pre_m, P.pre_s);
+        // in - zp_in may leave 32 bits; clamping the 64-bit difference to +-max_abs_q first
+        // gives the same q as the definition
+        const int64_t c = (int64_t)x - (int64_t)P.zp_in;
+        const int64_t lim = (int64_t)P.max_abs_q;
+        const int32_t q = (int32_t)(c < -lim ? -lim : (c > lim ? lim : c));
+        return gelu_eval_any(q, Q);
+    };
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    if (ALIGNED) {
+        const int64_t n16 = n >> 4;
+        const i32x4 *in4 = reinterpret_cast<const i32x4 *>(in);
+        u32x4 *out4 = reinterpret_cast<u32x4 *>(out);
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+            u32x4 r;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const i32x4 v = stream_load(in4 + 4 * i + d);
+                r[d] = pack4(one(v.x), one(v.y), one(v.z), one(v.w));
+            }
+            stream_store(r, out4 + i);
+        }
+        if (blockIdx.x == 0) {
+            const int64_t i = (n16 << 4) + threadIdx.x;
+            if (threadIdx.x < 16 && i < n) out[i] = (uint8_t)one(in[i]);
+        }
+    } else {
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
+            out[i] = (uint8_t)one(in[i]);
+    }
+}
+
+// int32 -> int8 / uint8 requantization, same access pattern.
+template <bool ALIGNED>
+__global__ void __launch_bounds__(256)
+requant_kernel(const int32_t *in, uint8_t *out, int64_t n, DyadicDev P)
+{
+    auto one = [&](int32_t x) -> int32_t {
+        return P.s >= 16 ? requant_dev<true>(x, P.m, P.s, P.zp, P.qmin, P.qmax)
+                         : requant_dev<false>(x, P.m, P.s, P.zp, P.qmin, P.qmax);
+    };
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    if (ALIGNED) {
+        const int64_t n16 = n >> 4;
+        const i32x4 *in4 = reinterpret_cast<const i32x4 *>(in);
+        u32x4 *out4 = reinterpret_cast<u32x4 *>(out);
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+            u32x4 r;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const i32x4 v = stream_load(in4 + 4 * i + d);
+                r[d] = pack4(one(v.x), one(v.y), one(v.z), one(v.w));
+            }
+            stream_store(r, out4 + i);
+        }
+        if (blockIdx.x == 0) {
+            const int64_t i = (n16 << 4) + threadIdx.x;
+            if (threadIdx.x < 16 && i < n) out[i] = (uint8_t)one(in[i]);
+        }
+    } else {
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
+            out[i] = (uint8_t)one(in[i]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Host-side dispatch.  Grid: enough workgroups to fill 256 compute units several times
+// over, capped by the amount of work.
+
+static unsigned grid_for(int64_t work_items, int per_block)
+{
+    int64_t g = (work_items + per_block - 1) / per_block;
+    const int64_t cap = 256 * 16;
+    if (g > cap) g = cap;
+    if (g < 1) g = 1;
+    return (unsigned)g;
+}
+
+hipError_t gelu_i8_dispatch(const int8_t *in, int8_t *out, int64_t n, bool force_direct,
+                            const GeluDev &P, hipStream_t stream)
+{
+    const uint8_t *uin = reinterpret_cast<const uint8_t *>(in);
+    uint8_t *uout = reinterpret_cast<uint8_t *>(out);
+    const bool aligned = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+    if (!aligned) {
+        hipLaunchKernelGGL(gelu_i8_bytes_kernel, dim3(grid_for(n, 256)), dim3(256), 0, stream, uin,
+                           uout, n, P);
+    } else if (force_direct) {
+        hipLaunchKernelGGL(gelu_i8_direct_kernel, dim3(grid_for(n >> 4, 256)), dim3(256), 0, stream,
+                           uin, uout, n, P);
+    } else {
+        hipLaunchKernelGGL(gelu_i8_table_kernel, dim3(grid_for(n >> 4, 256)), dim3(256), 0, stream,
+                           uin, uout, n, P);
+    }
+    return hipGetLastError();
+}
+
+hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,
+                             hipStream_t stream)
+{
+    uint8_t *uout = reinterpret_cast<uint8_t *>(out);
+    const bool aligned = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+    if (aligned)
+        hipLaunchKernelGGL(gelu_i32_kernel<true>, dim3(grid_for(n >> 4, 256)), dim3(256), 0, stream, in,
+                           uout, n, P);
+    else
+        hipLaunchKernelGGL(gelu_i32_kernel<false>, dim3(grid_for(n, 256)), dim3(256), 0, stream, in,
+                           uout, n, P);
+    return hipGetLastError();
+}
+
+hipError_t requant_dispatch(const int32_t *in, void *out, int64_t n, const DyadicDev &P,
+                            hipStream_t stream)
+{
+    uint8_t *uout = reinterpret_cast<uint8_t *>(out);
+    const bool aligned = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+    if (aligned)
+        hipLaunchKernelGGL(requant_kernel<true>, dim3(grid_for(n >> 4, 256)), dim3(256), 0, stream, in,
+                           uout, n, P);
+    else
+        hipLaunchKernelGGL(requant_kernel<false>, dim3(grid_for(n, 256)), dim3(256), 0, stream, in, uout,
+                           n, P);
+    return hipGetLastError();
+}
+
+}  // namespace iptq

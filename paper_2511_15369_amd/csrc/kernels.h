@@ -1,0 +1,21 @@
+// Launch entry points of the kernel translation units (host side).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "plan.h"
+
+namespace iptq {
+
+hipError_t softmax_dispatch(const int32_t *scores, const int32_t *bias, uint8_t *out, int64_t rows,
+                            int32_t cols, int out_bits, bool force_generic, const SoftmaxDev &P,
+                            hipStream_t stream);
+hipError_t gelu_i8_dispatch(const int8_t *in, int8_t *out, int64_t n, bool force_direct,
+                            const GeluDev &P, hipStream_t stream);
+hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,
+                             hipStream_t stream);
+hipError_t requant_dispatch(const int32_t *in, void *out, int64_t n, const DyadicDev &P,
+                            hipStream_t stream);
+
+}  // namespace iptq

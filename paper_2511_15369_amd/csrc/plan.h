@@ -1,0 +1,61 @@
+// Host-side plans: validated call parameters turned into the integer constants the
+// kernels take by value.  Everything here is plain C++ (no HIP types) so that the checks
+// can be exercised without a GPU.
+#pragma once
+
+#include <stdint.h>
+
+#include "../../include/iptq.h"
+
+namespace iptq {
+
+// Constants of one softmax launch (Section 4.4).  All derived on the host.
+struct SoftmaxDev {
+    int32_t i0;         // floor(1 / S_delta)
+    int32_t i0n;        // i0 << N: the integer image of 1.0
+    int32_t n_shift;    // N
+    uint32_t magic;     // q = mulhi(n, magic) >> magic_sh == n div i0 for 0 <= n <= n_max
+    int32_t magic_sh;
+    int32_t d_clamp;    // D: deltas below -D have Qexp == 0 and are clamped to -D
+    int32_t m_bits;     // M
+    int32_t p_shift;    // M - (b - 1)
+    int32_t pre_m, pre_s;
+    int32_t post_m, post_s, post_zp, qmin, qmax;
+    int32_t variant;
+    // bias addressing: row index modulo the period by multiply-high
+    int32_t bias_period_rows;
+    uint32_t period_magic;
+    int32_t period_sh;
+};
+
+// Constants of one GELU launch (Section 4.3).
+struct GeluDev {
+    int32_t quartic;    // 1: p = 4, 0: p = 2
+    int32_t q_b;
+    int64_t q_c;
+    int32_t k;
+    int32_t zp_in;
+    int32_t max_abs_q;
+    int32_t pre_m, pre_s;
+    int32_t post_m, post_s, post_zp, qmin, qmax;
+};
+
+struct DyadicDev {
+    int32_t m, s, zp, qmin, qmax;
+};
+
+// Unsigned division by a constant through multiply-high: for every 0 <= n < 2^nbits,
+// (mulhi32(n, magic) >> sh) == n / d.  Requires 1 <= d < 2^nbits and nbits <= 31.
+// Returns false if no 32-bit magic exists for that range (cannot happen for nbits <= 31).
+bool make_magic_u32(uint32_t d, int nbits, uint32_t *magic, int32_t *sh);
+
+// n(d) = -Qp for delta = -d: d + ceil(d/2) - ceil(d/16) (Eq. 7 with floor shifts).
+int64_t neg_qp_of(int64_t d);
+
+int check_dyadic(const iptq_dyadic_t *p, int out_is_signed);
+int plan_requant(const iptq_dyadic_t *p, int out_is_signed, DyadicDev *out);
+int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int has_bias,
+                 int64_t bias_period_rows, SoftmaxDev *out);
+int plan_gelu(const iptq_gelu_params_t *p, int is_i8_entry, GeluDev *out);
+
+}  // namespace iptq

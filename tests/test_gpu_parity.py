@@ -1,0 +1,280 @@
+"""GPU parity: the HIP path against the CPU oracle, bit for bit, through the C ABI.
+
+Every comparison is exact equality (integer work).  Inputs come from the seeded
+generators; sizes here are what the oracle finishes in seconds, chosen to span several
+wavefront slabs plus a ragged tail.  Full benchmark sizes are in test_gpu_fullsize.py.
+"""
+import numpy as np
+import pytest
+
+import workloads
+from oracle import prepare, ref
+from tests.helpers import (gpu_gelu_i8, gpu_gelu_i32, gpu_requant, gpu_softmax, lib_gelu,
+                           lib_softmax)
+
+pytestmark = pytest.mark.gpu
+INT32_MIN = -(2 ** 31)
+
+# (config, unit, reduced batch): a few thousand rows each, never a multiple of the slab
+SOFTMAX_CASES = [("deit_t", 0, 1), ("vit_s", 3, 3), ("vit_b", 7, 2), ("swin_b", 0, 1),
+                 ("swin_b", 1, 2), ("swin_b", 3, 5), ("swin_s_det", 0, 1)]
+
+
+def _trim(case, drop):
+    """Drop a few rows so that the row count is ragged with respect to every slab size."""
+    rows = case.scores.shape[0] - drop
+    return case.scores[:rows]
+
+
+@pytest.mark.parametrize("name,unit,batch", SOFTMAX_CASES)
+@pytest.mark.parametrize("variant", [0, 1])
+def test_softmax_configs(name, unit, batch, variant):
+    case = workloads.softmax_case(name, unit, batch=batch)
+    scores = _trim(case, 5)
+    for signed in (0, 1):
+        p = prepare.softmax_prepare(case.s_delta, scores.shape[1], variant, signed)
+        want = ref.softmax_i32(scores, p, case.bias, case.bias_period_rows)
+        got = gpu_softmax(scores, p, case.bias, case.bias_period_rows)
+        assert got.dtype == want.dtype
+        assert np.array_equal(got, want), (name, unit, variant, signed)
+    # the generic kernel family gives the same bytes
+    p = prepare.softmax_prepare(case.s_delta, scores.shape[1], variant, 0)
+    want = ref.softmax_i32(scores, p, case.bias, case.bias_period_rows)
+    got = gpu_softmax(scores, p, case.bias, case.bias_period_rows, algo=1)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("cols", [197, 49])
+@pytest.mark.parametrize("variant", [0, 1])
+def test_softmax_soft_rows_all_scales(cols, variant):
+    # scores scaled so that S_delta * sigma is about 0.5 .. 4: many non-zero probabilities
+    rng = np.random.default_rng(100 + cols + variant)
+    for log2s in (-4, -5.3, -7, -8.6, -10):
+        s_delta = 2.0 ** log2s
+        spread = float(rng.choice([0.5, 1.5, 4.0])) / s_delta
+        rows = int(rng.integers(130, 400))
+        scores = np.rint(rng.standard_normal((rows, cols)) * spread).astype(np.int32)
+        p = prepare.softmax_prepare(s_delta, cols, variant)
+        want = ref.softmax_i32(scores, p)
+        assert want.any()
+        assert np.array_equal(gpu_softmax(scores, p), want), (log2s, rows)
+
+
+@pytest.mark.parametrize("cols", [197, 49])
+def test_softmax_mask_and_extreme_rows(cols):
+    rng = np.random.default_rng(7)
+    rows = 150
+    scores = np.rint(rng.standard_normal((rows, cols)) * 600).astype(np.int32)
+    scores[3, :] = INT32_MIN                               # fully masked row
+    scores[4, ::2] = INT32_MIN                             # half masked
+    scores[5, :] = INT32_MIN
+    scores[5, 7] = INT32_MIN + 1                           # one live entry next to the sentinel
+    scores[6, :] = INT32_MIN + 1 + rng.integers(0, 50, cols)   # whole row near INT32_MIN
+    scores[6, 1::3] = INT32_MIN
+    scores[7, :] = 2 ** 31 - 1 - rng.integers(0, 50, cols)     # whole row near INT32_MAX
+    scores[8, :] = rng.integers(INT32_MIN, 2 ** 31, cols)      # full-range garbage
+    scores[9, :] = 0
+    scores[9, 0] = 2 ** 31 - 1
+    scores[9, 1] = INT32_MIN + 1
+    scores[70, :] = INT32_MIN                              # a masked row in a later slab
+    scores[71, 5:] = INT32_MIN
+    big = [(2 ** 20, 3, 31), (2 ** 23 - 1, 0, 31)] if cols == 197 else [(2 ** 20, 3, 30), (2 ** 24 - 1, 0, 30)]
+    for variant in (0, 1):
+        for i0, n, m_bits in [(16, 0, 30), (128, 7, 30), (1000, 5, 30)] + big:
+            p = ref.SoftmaxParams(variant=variant, i0=i0, n_shift=n, m_bits=m_bits)
+            want = ref.softmax_i32(scores, p)
+            assert np.array_equal(gpu_softmax(scores, p), want), (variant, i0, n)
+            assert np.array_equal(gpu_softmax(scores, p, algo=1), want), (variant, i0, n)
+
+
+@pytest.mark.parametrize("cols", [1, 2, 3, 4, 5, 16, 63, 64, 65, 128, 196, 198, 577, 1025, 4099])
+def test_softmax_any_row_length(cols):
+    rng = np.random.default_rng(cols)
+    rows = 37
+    scores = np.rint(rng.standard_normal((rows, cols)) * 300).astype(np.int32)
+    scores[2, : max(1, cols // 3)] = INT32_MIN
+    for variant in (0, 1):
+        p = prepare.softmax_prepare(2.0 ** -7.3, cols, variant)
+        want = ref.softmax_i32(scores, p)
+        assert np.array_equal(gpu_softmax(scores, p), want)
+
+
+def test_softmax_max_cols():
+    cols = 65536
+    rng = np.random.default_rng(3)
+    scores = np.rint(rng.standard_normal((3, cols)) * 50).astype(np.int32)
+    p = prepare.softmax_prepare(2.0 ** -5, cols, 1)
+    assert p.n_shift < 15 - p.i0.bit_length() + 1
+    assert np.array_equal(gpu_softmax(scores, p), ref.softmax_i32(scores, p))
+
+
+@pytest.mark.parametrize("cols,rows", [(197, 16), (197, 15), (197, 33), (49, 64), (49, 63), (49, 130)])
+def test_softmax_pre_post_outbits_bias(cols, rows):
+    rng = np.random.default_rng(rows * cols)
+    scores = np.rint(rng.standard_normal((rows, cols)) * 9000).astype(np.int32)
+    scores[1, 3] = INT32_MIN
+    bias = np.rint(rng.standard_normal((7, cols)) * 500).astype(np.int32)
+    bias[0, 0] = 2 ** 31 - 1
+    bias[1, 1] = INT32_MIN
+    big_bias = np.rint(rng.standard_normal((96, cols)) * 500).astype(np.int32)   # 96 * cols % 4 == 0
+    variants = [
+        ref.SoftmaxParams(variant=1, i0=128, n_shift=7, pre_m=20000, pre_s=18),
+        ref.SoftmaxParams(variant=0, i0=64, n_shift=8, pre_m=3, pre_s=0),
+        ref.SoftmaxParams(variant=1, i0=300, n_shift=6, post=ref.Dyadic(3, 1, 10, 0, 255)),
+        ref.SoftmaxParams(variant=0, i0=300, n_shift=6, post=ref.Dyadic(-255, 7, 100, -128, 127),
+                          out_is_signed=1),
+        ref.SoftmaxParams(variant=1, i0=300, n_shift=6, post=ref.Dyadic(1, 0, 0, 0, 100)),
+        ref.SoftmaxParams(variant=1, i0=300, n_shift=6, post=ref.Dyadic(32767, 62, -3, -128, 127),
+                          out_is_signed=1),
+        ref.SoftmaxParams(variant=0, i0=50, n_shift=3, out_bits=4, m_bits=20),
+        ref.SoftmaxParams(variant=1, i0=50, n_shift=3, out_bits=2, m_bits=31),
+    ]
+    for p in variants:
+        for b, period in ((None, 0), (bias, 7), (big_bias, 96), (bias[:1], 1)):
+            want = ref.softmax_i32(scores, p, b, period)
+            assert np.array_equal(gpu_softmax(scores, p, b, period), want)
+
+
+def test_softmax_empty_and_layers_entry():
+    import torch
+    import paper_2511_15369_amd as ip
+    p = lib_softmax(prepare.softmax_prepare(2.0 ** -7, 197, 1))
+    d_in = torch.zeros(16, dtype=torch.int32, device="cuda")
+    d_out = torch.full((16,), 7, dtype=torch.uint8, device="cuda")
+    ip.softmax_i32(d_in, None, 0, d_out, 0, 197, p)
+    torch.cuda.synchronize()
+    assert (d_out == 7).all()
+    # three layers with different scales and variants in one call
+    rng = np.random.default_rng(4)
+    rows, cols, layers = 50, 197, 3
+    x = np.rint(rng.standard_normal((layers, rows, cols)) * 2000).astype(np.int32)
+    ps = [prepare.softmax_prepare(2.0 ** -(5 + l), cols, l % 2) for l in range(layers)]
+    d_x = torch.from_numpy(x).cuda()
+    d_y = torch.zeros((layers, rows, cols), dtype=torch.uint8, device="cuda")
+    ip.softmax_i32_layers(d_x, rows * cols, d_y, rows * cols, rows, cols, layers,
+                          [lib_softmax(q) for q in ps])
+    torch.cuda.synchronize()
+    y = d_y.cpu().numpy()
+    for l in range(layers):
+        assert np.array_equal(y[l], ref.softmax_i32(x[l], ps[l]))
+
+
+def test_softmax_is_deterministic():
+    case = workloads.softmax_case("vit_s", 0, batch=2)
+    p = prepare.softmax_prepare(2.0 ** -9, 197, 1)
+    a = gpu_softmax(case.scores, p)
+    b = gpu_softmax(case.scores, p)
+    assert np.array_equal(a, b)
+
+
+# --------------------------------------------------------------------------------- GELU
+GELU_CASES = [("deit_t", 0, 1), ("vit_s", 5, 1), ("vit_b", 2, 1), ("swin_b", 0, 1),
+              ("swin_b", 3, 2), ("swin_s_det", 0, 1)]
+
+
+@pytest.mark.parametrize("name,unit,batch", GELU_CASES)
+@pytest.mark.parametrize("variant", [0, 1])
+def test_gelu_i8_configs(name, unit, batch, variant):
+    case = workloads.gelu_case(name, unit, batch=batch)
+    x = case.x.reshape(-1)[: min(case.x.size, 3_000_000) - 5]
+    p = prepare.gelu_prepare(case.s_in, case.s_out, case.zp_in, case.zp_out, variant)
+    want = ref.gelu_i8(x, p)
+    assert np.array_equal(gpu_gelu_i8(x, p), want)
+    assert np.array_equal(gpu_gelu_i8(x, p, algo=1), want)
+    assert np.array_equal(gpu_gelu_i8(x, p, inplace=True), want)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_gelu_all_codes_all_scales(variant):
+    allx = np.tile(np.arange(-128, 128, dtype=np.int8), 5)[:-3]
+    rng = np.random.default_rng(variant)
+    for _ in range(25):
+        s_in = float(2.0 ** rng.uniform(-12, -3))
+        s_out = float(2.0 ** rng.uniform(-12, -3))
+        zi, zo = int(rng.integers(-128, 129)), int(rng.integers(-128, 128))
+        p = prepare.gelu_prepare(s_in, s_out, zi, zo, variant)
+        want = ref.gelu_i8(allx, p)
+        assert np.array_equal(gpu_gelu_i8(allx, p), want), (s_in, s_out, zi, zo)
+        assert np.array_equal(gpu_gelu_i8(allx, p, algo=1), want), (s_in, s_out, zi, zo)
+    # a requantization with a small shift (wide path) and a positive multiplier
+    p = prepare.gelu_prepare(2.0 ** -4, 2.0 ** -5, 0, 0, variant, 128)
+    p.post = ref.Dyadic(-3, 18, 5, -100, 90)
+    assert np.array_equal(gpu_gelu_i8(allx, p), ref.gelu_i8(allx, p))
+    p.post = ref.Dyadic(-1, 3, 0, -128, 127)
+    assert np.array_equal(gpu_gelu_i8(allx, p, algo=1), ref.gelu_i8(allx, p))
+
+
+@pytest.mark.parametrize("n", [0, 1, 15, 16, 17, 255, 4097, 100003])
+def test_gelu_i8_sizes_and_unaligned(n):
+    import torch
+    import paper_2511_15369_amd as ip
+    rng = np.random.default_rng(n)
+    p = prepare.gelu_prepare(2.0 ** -5.5, 2.0 ** -6, 3, -11, 1)
+    x = rng.integers(-128, 128, size=n + 8, dtype=np.int8)
+    d_x = torch.from_numpy(x).cuda()
+    for off in (0, 1, 5):
+        d_out = torch.full((n + 8,), 0x5A, dtype=torch.int8, device="cuda")
+        ip.gelu_i8(d_x[off:], d_out[off:], n, lib_gelu(p))
+        torch.cuda.synchronize()
+        got = d_out.cpu().numpy()
+        assert np.array_equal(got[off:off + n], ref.gelu_i8(x[off:off + n], p))
+        assert (got[:off] == 0x5A).all() and (got[off + n:] == 0x5A).all()
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_gelu_i32(variant):
+    rng = np.random.default_rng(50 + variant)
+    n = 70001
+    x = np.rint(rng.standard_normal(n) * 40000).astype(np.int32)
+    x[:6] = [INT32_MIN, 2 ** 31 - 1, 0, -1, 1, 123456789]
+    p = prepare.gelu_prepare(2.0 ** -7, 2.0 ** -4, 5, -20, variant, max_abs_q=2000)
+    assert np.array_equal(gpu_gelu_i32(x, p), ref.gelu_i32(x, p))
+    p.pre_m, p.pre_s = 23000, 21
+    assert np.array_equal(gpu_gelu_i32(x, p), ref.gelu_i32(x, p))
+    p.pre_m, p.pre_s = 32767, 0                            # saturating pre-requantization
+    assert np.array_equal(gpu_gelu_i32(x, p), ref.gelu_i32(x, p))
+    p.zp_in = 2 ** 31 - 1
+    assert np.array_equal(gpu_gelu_i32(x, p), ref.gelu_i32(x, p))
+    # a second-order case with a large |q_b| (square does not fit 32 bits)
+    if variant == 0:
+        p2 = prepare.gelu_prepare(2.0 ** -22, 2.0 ** -15, 0, 0, 0, max_abs_q=200000)
+        assert -p2.q_b > 2 ** 17
+        x2 = np.rint(rng.standard_normal(n) * 300000).astype(np.int32)
+        assert np.array_equal(gpu_gelu_i32(x2, p2), ref.gelu_i32(x2, p2))
+
+
+def test_gelu_layers_entry():
+    import torch
+    import paper_2511_15369_amd as ip
+    rng = np.random.default_rng(9)
+    n, layers = 5000, 4
+    x = rng.integers(-128, 128, size=(layers, n), dtype=np.int8)
+    ps = [prepare.gelu_prepare(2.0 ** -(4 + l), 2.0 ** -(5 + l), 0, l, l % 2) for l in range(layers)]
+    d_x = torch.from_numpy(x).cuda()
+    d_y = torch.zeros_like(d_x)
+    ip.gelu_i8_layers(d_x, n, d_y, n, n, layers, [lib_gelu(q) for q in ps])
+    torch.cuda.synchronize()
+    y = d_y.cpu().numpy()
+    for l in range(layers):
+        assert np.array_equal(y[l], ref.gelu_i8(x[l], ps[l]))
+
+
+# --------------------------------------------------------------------------------- requant
+@pytest.mark.parametrize("seed", range(3))
+def test_requant(seed):
+    rng = np.random.default_rng(seed)
+    n = 100003
+    x = rng.integers(INT32_MIN, 2 ** 31, size=n).astype(np.int32)
+    x[:4] = [INT32_MIN, 2 ** 31 - 1, 0, -1]
+    small = np.rint(rng.standard_normal(n) * 3000).astype(np.int32)
+    for _ in range(12):
+        m = int(rng.integers(-32767, 32768))
+        s = int(rng.integers(0, 63))
+        zp = int(rng.integers(-300, 300))
+        signed = int(rng.integers(0, 2))
+        lo, hi = (-128, 127) if signed else (0, 255)
+        d = ref.Dyadic(m, s, zp, lo, hi)
+        for data in (x, small):
+            assert np.array_equal(gpu_requant(data, d, signed), ref.requant(data, d, signed)), (m, s)
+    d = ref.Dyadic(*prepare.make_dyadic(0.0123), 3, -128, 127)
+    assert np.array_equal(gpu_requant(small, d, 1), ref.requant(small, d, 1))
