@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the integer softmax + GELU hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of the chosen workload: for every
+layer (ViT / DeiT) or stage (Swin), the integer softmax over the int32 attention scores
+(with the Swin bias / detection mask where the workload has one) followed by the integer
+GELU over the int8 MLP activations, each layer with its own buffers, scales and variant.
+Inputs are seeded synthetic tensors already resident in HBM when the timed region starts.
+
+Prints one JSON line: whole-job elements/s, the roofline figures of the dominant kernel
+(softmax; measured live with events on the launch stream) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak
+SOFTMAX_BYTES_PER_EL = 5       # int32 in, one byte out
+GELU_BYTES_PER_EL = 2          # int8 in, int8 out
+# HBM bytes per softmax launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script (see profiles/), keyed by workload; None until measured.
+MEASURED_TRAFFIC = {"vit_b": None, "swin_b": None}
+
+
+class Unit:
+    """Device buffers and parameters of one layer / stage."""
+
+    def __init__(self, name, unit, batch=None, seed=0, variant_override=None):
+        import numpy as np
+        import torch
+
+        import paper_2511_15369_amd as ip
+        import workloads
+
+        cfg = workloads.CONFIGS[name]
+        self.name, self.unit = name, unit
+        b = cfg["batch"] if batch is None else batch
+        heads, tokens, windows = cfg["heads"][unit], cfg["tokens"][unit], cfg["windows"][unit]
+        sc = workloads.layer_scales(name, unit, seed)
+        self.scales = sc
+        sv = sc["softmax_variant"] if variant_override is None else variant_override
+        gv = sc["gelu_variant"] if variant_override is None else variant_override
+
+        # scores = Q K^T formed on the GPU in float32 (exact: |sum| < 2^24), then cast
+        q, k = workloads.softmax_qk(name, unit, batch, seed)
+        dq = torch.from_numpy(q).cuda().float()
+        dk = torch.from_numpy(k).cuda().float()
+        s = torch.bmm(dq, dk.transpose(1, 2)).to(torch.int32)
+        del dq, dk
+        if cfg["mask"]:
+            km = torch.from_numpy(workloads.detection_key_mask()).cuda()      # [windows, tokens]
+            s = s.view(b, windows, heads, tokens, tokens)
+            s = torch.where(km[None, :, None, None, :], torch.tensor(-2 ** 31, dtype=torch.int32,
+                                                                     device="cuda"), s)
+        self.rows, self.cols = b * windows * heads * tokens, tokens
+        self.d_scores = s.reshape(self.rows, self.cols).contiguous()
+        bias, period = workloads.softmax_bias(name, unit, seed)
+        self.d_bias = None if bias is None else torch.from_numpy(bias).cuda()
+        self.period = period
+        self.d_probs = torch.empty((self.rows, self.cols), dtype=torch.uint8, device="cuda")
+        self.sp = ip.softmax_prepare(sc["s_delta"], self.cols, sv, 0)
+
+        g = workloads.gelu_case(name, unit, batch, seed)
+        self.gelu_n = int(g.x.size)
+        self.d_x = torch.from_numpy(g.x).cuda().reshape(-1)
+        self.d_y = torch.empty_like(self.d_x)
+        self.gp = ip.gelu_prepare(g.s_in, g.s_out, g.zp_in, g.zp_out, gv, 255)
+        del np
+
+    def softmax(self):
+        import paper_2511_15369_amd as ip
+        ip.softmax_i32(self.d_scores, self.d_bias, self.period, self.d_probs, self.rows, self.cols,
+                       self.sp)
+
+    def gelu(self):
+        import paper_2511_15369_amd as ip
+        ip.gelu_i8(self.d_x, self.d_y, self.gelu_n, self.gp)
+
+    @property
+    def softmax_elements(self):
+        return self.rows * self.cols
+
+
+def build_units(name, batch=None, seed=0, variant_override=None):
+    import workloads
+    return [Unit(name, u, batch, seed, variant_override) for u in range(workloads.CONFIGS[name]["units"])]
+
+
+def time_region(fn, reps):
+    """Average milliseconds of fn() over reps calls, events on the launch stream."""
+    import torch
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(reps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / reps
+
+
+def cpu_baseline(name, budget_units=4):
+    """The CPU oracle, single thread, on the first layers of the same workload."""
+    import workloads
+    from oracle import prepare, ref
+
+    n_units = min(budget_units, workloads.CONFIGS[name]["units"])
+    elements, seconds = 0, 0.0
+    for u in range(n_units):
+        sc = workloads.softmax_case(name, u)
+        p = prepare.softmax_prepare(sc.s_delta, sc.scores.shape[1], sc.variant)
+        gc = workloads.gelu_case(name, u)
+        gp = prepare.gelu_prepare(gc.s_in, gc.s_out, gc.zp_in, gc.zp_out, gc.variant)
+        t0 = time.perf_counter()
+        ref.softmax_i32(sc.scores, p, sc.bias, sc.bias_period_rows)
+        ref.gelu_i8(gc.x, gp)
+        seconds += time.perf_counter() - t0
+        elements += sc.scores.size + gc.x.size
+        if seconds > 20.0:
+            n_units = u + 1
+            break
+    return {"value": elements / seconds, "unit": "elements/s", "cores": 1, "kind": "oracle",
+            "sample": "softmax+GELU of the first %d of %d units of %s, full size, %.1f s"
+                      % (n_units, workloads.CONFIGS[name]["units"], name, seconds)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="vit_b",
+                    choices=["deit_t", "vit_s", "vit_b", "swin_b", "swin_s_det"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary Swin-B measurement")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this path has no multi-GPU form "
+              "(rows and elements are independent; see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2511_15369_amd as ip
+    import workloads
+
+    ip.load()
+    torch.cuda.set_device(0)
+
+    def measure(name):
+        units = build_units(name)
+
+        def step():
+            for u in units:
+                u.softmax()
+                u.gelu()
+
+        def softmax_only():
+            for u in units:
+                u.softmax()
+
+        def gelu_only():
+            for u in units:
+                u.gelu()
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ms = time_region(step, args.steps)
+        wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        sm_ms = time_region(softmax_only, args.steps) / len(units)
+        ge_ms = time_region(gelu_only, args.steps) / len(units)
+        sm_el = sum(u.softmax_elements for u in units)
+        ge_el = sum(u.gelu_n for u in units)
+        res = {
+            "ms_per_step": ms, "wall_ms_per_step": wall_ms,
+            "elements_per_step": sm_el + ge_el,
+            "softmax": {"elements": sm_el, "launches": len(units), "avg_launch_us": sm_ms * 1e3,
+                        "gbps": SOFTMAX_BYTES_PER_EL * sm_el / len(units) / (sm_ms * 1e-3) / 1e9},
+            "gelu": {"elements": ge_el, "launches": len(units), "avg_launch_us": ge_ms * 1e3,
+                     "gbps": GELU_BYTES_PER_EL * ge_el / len(units) / (ge_ms * 1e-3) / 1e9},
+        }
+        res["value"] = (sm_el + ge_el) / (ms * 1e-3)
+        res["algorithmic_gbps"] = (SOFTMAX_BYTES_PER_EL * sm_el + GELU_BYTES_PER_EL * ge_el) / (ms * 1e-3) / 1e9
+        del units
+        torch.cuda.empty_cache()
+        return res
+
+    main_res = measure(args.workload)
+    sm = main_res["softmax"]
+    cfg = workloads.CONFIGS[args.workload]
+    out = {
+        "metric": "int softmax+GELU elements/s and achieved HBM GB/s (% of peak), 1xMI355X",
+        "value": main_res["value"],
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %d units x (softmax int32->uint8 + GELU int8->int8), batch %d, "
+                               "per-unit scales and variants, seed 0"
+                               % (args.workload, cfg["units"], cfg["batch"]),
+                   "softmax_elements_per_step": sm["elements"],
+                   "gelu_elements_per_step": main_res["gelu"]["elements"]},
+        "algorithmic_gbps": main_res["algorithmic_gbps"],
+        "pct_of_hbm_peak": 100.0 * main_res["algorithmic_gbps"] / HBM_PEAK_GBS,
+        "roofline": {
+            "bound": "hbm", "kernel": "softmax_rows_kernel",
+            "achieved": sm["gbps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": sm["gbps"] / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC.get(args.workload),
+            "avg_launch_us": sm["avg_launch_us"],
+            "algorithmic_bytes_per_launch": SOFTMAX_BYTES_PER_EL * sm["elements"] // sm["launches"],
+        },
+        "kernels": {"softmax": sm, "gelu": main_res["gelu"]},
+    }
+    if not args.no_extra and args.workload != "swin_b":
+        sw = measure("swin_b")
+        out["extra"] = {"swin_b": {k: sw[k] for k in ("value", "ms_per_step", "algorithmic_gbps",
+                                                      "softmax", "gelu")}}
+        out["extra"]["swin_b"]["pct_of_hbm_peak"] = 100.0 * sw["algorithmic_gbps"] / HBM_PEAK_GBS
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,61 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle processes about 35 M softmax elements and 110 M GELU elements per second on one
+core, so whole layers are compared element by element rather than sampled: one layer of
+each ViT-shaped config, every Swin-B stage and the detection-scale Swin-S stage.
+"""
+import numpy as np
+import pytest
+
+import bench
+import workloads
+from oracle import prepare, ref
+from tests.helpers import gelu_fields, softmax_fields
+
+pytestmark = pytest.mark.gpu
+
+FULL_UNITS = [("deit_t", 0), ("vit_s", 4), ("vit_b", 0), ("vit_b", 11), ("swin_b", 0), ("swin_b", 1),
+              ("swin_b", 2), ("swin_b", 3), ("swin_s_det", 0)]
+
+
+@pytest.mark.parametrize("name,unit", FULL_UNITS)
+def test_full_size_unit_matches_oracle(name, unit):
+    import torch
+    print("full-size parity", name, unit, flush=True)
+    u = bench.Unit(name, unit)
+    u.softmax()
+    u.gelu()
+    torch.cuda.synchronize()
+    probs = u.d_probs.cpu().numpy()
+    y = u.d_y.cpu().numpy()
+
+    sc = workloads.softmax_case(name, unit)
+    assert sc.scores.shape == (u.rows, u.cols)
+    assert np.array_equal(u.d_scores.cpu().numpy(), sc.scores)      # same input on both sides
+    p = prepare.softmax_prepare(sc.s_delta, u.cols, sc.variant)
+    assert softmax_fields(p) == softmax_fields(u.sp)
+    want = ref.softmax_i32(sc.scores, p, sc.bias, sc.bias_period_rows)
+    assert np.array_equal(probs, want)
+
+    gc = workloads.gelu_case(name, unit)
+    gp = prepare.gelu_prepare(gc.s_in, gc.s_out, gc.zp_in, gc.zp_out, gc.variant)
+    assert gelu_fields(gp) == gelu_fields(u.gp)
+    assert np.array_equal(y, ref.gelu_i8(gc.x.reshape(-1), gp))
+
+
+def test_other_variant_at_full_size():
+    """The variant the seeded draw did not pick, on the two target shapes."""
+    import torch
+    for name, unit in (("vit_b", 0), ("swin_b", 0)):
+        sc = workloads.softmax_case(name, unit)
+        other = 1 - sc.variant
+        u = bench.Unit(name, unit, variant_override=other)
+        u.softmax()
+        u.gelu()
+        torch.cuda.synchronize()
+        p = prepare.softmax_prepare(sc.s_delta, u.cols, other)
+        assert np.array_equal(u.d_probs.cpu().numpy(),
+                              ref.softmax_i32(sc.scores, p, sc.bias, sc.bias_period_rows))
+        gc = workloads.gelu_case(name, unit)
+        gp = prepare.gelu_prepare(gc.s_in, gc.s_out, gc.zp_in, gc.zp_out, other)
+        assert np.array_equal(u.d_y.cpu().numpy(), ref.gelu_i8(gc.x.reshape(-1), gp))

@@ -1,0 +1,28 @@
+"""The kernels must be integer-only: compile the device code to gfx950 assembly (hipcc
+cross-compiles without a GPU) and fail on any floating-point, conversion, reciprocal or
+matrix-core instruction."""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2511_15369_amd", "csrc")
+FORBIDDEN = re.compile(r"^\s+(v_[a-z0-9_]*_(f16|f32|f64|bf16)\b|v_cvt_|v_rcp|v_rsq|v_sqrt|v_mfma|v_smfmac|"
+                       r"v_exp|v_log|v_pk_[a-z]+_f|v_dot[0-9]*_f|v_fma|v_mad_f|v_mac_f|v_div_)", re.M)
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not installed")
+@pytest.mark.parametrize("src", ["softmax_kernels.hip", "elementwise_kernels.hip"])
+def test_no_floating_point_instructions(src, tmp_path):
+    out = tmp_path / (src + ".s")
+    subprocess.check_call(["hipcc", "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17",
+                           "--cuda-device-only", "-S", "-Xclang", "-target-feature", "-Xclang",
+                           "-packed-fp32-ops", os.path.join(CSRC, src), "-o", str(out)],
+                          stderr=subprocess.DEVNULL)
+    text = out.read_text()
+    assert "v_mul_hi_u32" in text or "v_mad_u64_u32" in text      # sanity: this is device code
+    hits = FORBIDDEN.findall(text)
+    assert not hits, hits[:5]

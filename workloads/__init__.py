@@ -16,6 +16,7 @@ from .generators import (  # noqa: F401
     layer_scales,
     qk_pair,
     scores_from_qk,
+    softmax_bias,
     softmax_case,
     softmax_qk,
     swin_bias,

@@ -111,17 +111,47 @@ def detection_key_mask(map_h: int = 200, map_w: int = 334, win: int = 7) -> np.n
     return pad.reshape(nh, win, nw, win).transpose(0, 2, 1, 3).reshape(nh * nw, win * win)
 
 
-def gelu_input(rng: np.random.Generator, tokens: int, width: int) -> np.ndarray:
-    """int8 [tokens, width]: 0.9*N(0,20) + 0.1*Laplace(0,60), 2% of channels x4, clipped to +-127."""
+_GELU_BLOCK_TOKENS = 2048
+
+
+def _gelu_block(seed_seq, tokens: int, width: int, scale_row: np.ndarray) -> np.ndarray:
+    rng = np.random.default_rng(seed_seq)
     n = tokens * width
-    x = rng.standard_normal(n, dtype=np.float32) * np.float32(20.0)
+    x = rng.standard_normal(n, dtype=np.float32)
+    x *= np.float32(20.0)
     pick = np.flatnonzero(rng.random(n, dtype=np.float32) < np.float32(0.1))
     x[pick] = rng.laplace(0.0, 60.0, size=pick.size).astype(np.float32)
     x = x.reshape(tokens, width)
+    x *= scale_row
+    np.rint(x, out=x)
+    np.clip(x, -127, 127, out=x)
+    return x.astype(np.int8)
+
+
+def gelu_input(rng: np.random.Generator, tokens: int, width: int) -> np.ndarray:
+    """int8 [tokens, width]: 0.9*N(0,20) + 0.1*Laplace(0,60), 2% of channels x4, clipped to +-127.
+
+    Drawn in blocks of 2048 tokens, each from its own child seed, so that the
+    blocks can be filled by a few threads without changing the result.
+    """
+    from concurrent.futures import ThreadPoolExecutor
+
     n_out = max(1, int(round(0.02 * width)))
     chans = rng.choice(width, size=n_out, replace=False)
-    x[:, chans] *= np.float32(4.0)
-    return np.clip(np.rint(x), -127, 127).astype(np.int8)
+    scale_row = np.ones(width, dtype=np.float32)
+    scale_row[chans] = 4.0
+    n_blocks = -(-tokens // _GELU_BLOCK_TOKENS)
+    seeds = rng.bit_generator.seed_seq.spawn(n_blocks)
+    out = np.empty((tokens, width), dtype=np.int8)
+
+    def fill(i):
+        lo = i * _GELU_BLOCK_TOKENS
+        hi = min(tokens, lo + _GELU_BLOCK_TOKENS)
+        out[lo:hi] = _gelu_block(seeds[i], hi - lo, width, scale_row)
+
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        list(ex.map(fill, range(n_blocks)))
+    return out
 
 
 # --------------------------------------------------------------------------- scales
@@ -186,6 +216,15 @@ def softmax_qk(name: str, unit: int = 0, batch: Optional[int] = None, seed: int 
                    cfg["heavy_tail"])
 
 
+def softmax_bias(name: str, unit: int = 0, seed: int = 0):
+    """(bias, bias_period_rows) of one unit, or (None, 0) for configs without a bias."""
+    cfg = CONFIGS[name]
+    if not cfg["bias"]:
+        return None, 0
+    heads, tokens = cfg["heads"][unit], cfg["tokens"][unit]
+    return swin_bias(_rng(seed, cfg["index"], unit, 2), heads, tokens), heads * tokens
+
+
 def softmax_case(name: str, unit: int = 0, batch: Optional[int] = None, seed: int = 0,
                  scores: Optional[np.ndarray] = None) -> SoftmaxCase:
     """Scores (and bias / mask where the config has them) of one unit.
@@ -205,10 +244,7 @@ def softmax_case(name: str, unit: int = 0, batch: Optional[int] = None, seed: in
         assert km.shape == (windows, tokens)
         scores = np.where(km[None, :, None, None, :], np.int32(INT32_MIN), scores)
     scores = np.ascontiguousarray(scores.reshape(-1, tokens), dtype=np.int32)
-    bias, period = None, 0
-    if cfg["bias"]:
-        bias = swin_bias(_rng(seed, cfg["index"], unit, 2), heads, tokens)
-        period = heads * tokens
+    bias, period = softmax_bias(name, unit, seed)
     sc = layer_scales(name, unit, seed)
     return SoftmaxCase(name, unit, scores, bias, period, sc["s_delta"], sc["softmax_variant"])
 
