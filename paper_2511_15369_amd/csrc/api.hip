@@ -133,13 +133,14 @@ extern "C" uint32_t iptq_debug_floor_pow2_div(int32_t m_bits, uint32_t sigma)
 }
 
 extern "C" int iptq_debug_softmax_plan(const iptq_softmax_params_t *p, int64_t rows, int32_t cols,
-                                       int32_t has_bias, int64_t bias_period_rows, int64_t *out8)
+                                       int32_t has_bias, int64_t bias_period_rows, int64_t *out12)
 {
     SoftmaxDev dev;
     int rc = plan_softmax(p, rows, cols, has_bias, bias_period_rows, &dev);
-    if (rc != IPTQ_OK || !out8) return rc;
-    out8[0] = dev.magic; out8[1] = dev.magic_sh; out8[2] = dev.d_clamp; out8[3] = dev.i0n;
-    out8[4] = dev.p_shift; out8[5] = dev.period_magic; out8[6] = dev.period_sh;
-    out8[7] = neg_qp_of(dev.d_clamp);
+    if (rc != IPTQ_OK || !out12) return rc;
+    out12[0] = dev.magic; out12[1] = dev.magic_sh; out12[2] = dev.d_clamp; out12[3] = dev.i0n;
+    out12[4] = dev.p_shift; out12[5] = dev.period_magic; out12[6] = dev.period_sh;
+    out12[7] = neg_qp_of(dev.d_clamp);
+    out12[8] = dev.mode16; out12[9] = dev.mg24; out12[10] = dev.t16; out12[11] = 0;
     return rc;
 }

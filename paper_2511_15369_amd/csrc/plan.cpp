@@ -122,6 +122,27 @@ int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int
     out->post_m = p->post.m; out->post_s = p->post.s; out->post_zp = p->post.zp;
     out->qmin = p->post.qmin; out->qmax = p->post.qmax;
     out->variant = p->variant;
+    // Packed 16-bit path: clamped delta, n and (i0 << N) must fit 16 bits, the per-row factor
+    // shifted to the top byte must fit 24 bits, and a 24-bit divider multiplier must be exact.
+    out->mode16 = 0;
+    out->mg24 = 0;
+    out->t16 = 0;
+    if (D <= 32767 && i0n < (1 << 15) && out->p_shift <= 24 && i0n >= ((int64_t)1 << p->out_bits)) {
+        for (int t = 0; t <= 12; ++t) {
+            const uint64_t two = (uint64_t)1 << (32 - t);
+            const uint64_t mg = two / (uint64_t)p->i0 + 1;
+            if (mg >= ((uint64_t)1 << 24)) continue;
+            const uint64_t e = mg * (uint64_t)p->i0 - two;      // 0 < e <= i0
+            const bool fits = ((uint64_t)n_max << t) <= 65535;
+            const bool exact = e > 0 && e <= (uint64_t)p->i0 && (uint64_t)n_max * e < two;
+            if (fits && exact) {
+                out->mode16 = t == 0 ? 1 : 2;
+                out->mg24 = (uint32_t)mg;
+                out->t16 = t;
+            }
+            break;
+        }
+    }
     out->bias_period_rows = has_bias ? (int32_t)bias_period_rows : 1;
     out->period_magic = 0;
     out->period_sh = 0;

@@ -17,6 +17,9 @@ struct SoftmaxDev {
     uint32_t magic;     // q = mulhi(n, magic) >> magic_sh == n div i0 for 0 <= n <= n_max
     int32_t magic_sh;
     int32_t d_clamp;    // D: deltas below -D have Qexp == 0 and are clamped to -D
+    int32_t mode16;     // 0: 32-bit lanes only; 1: packed 16-bit path valid; 2: same with n << t16
+    uint32_t mg24;      // packed path divider: q = bits 47..32 of (n << t16) * mg24
+    int32_t t16;
     int32_t m_bits;     // M
     int32_t p_shift;    // M - (b - 1)
     int32_t pre_m, pre_s;

@@ -1,0 +1,364 @@
+// Fixed-row-length integer softmax kernel for gfx950 (Section 4.4, Eq. 6-15).
+//
+// A wavefront owns 64/K whole rows (a "slab"), K lanes per row.  The slab is contiguous
+// and 16-byte aligned in both the int32 input and the byte output, so all global traffic
+// is full dwordx4: the slab is copied flat into LDS (with the additive bias fused into the
+// copy), lanes then read their rows from LDS on the 16-byte grid of the flat tensor
+// ("blocks" of 4 elements; a row that does not start on that grid ignores the
+// neighbours' elements in its first and last block), results are assembled as bytes in
+// LDS and stored flat.  Only wavefront-level ordering is needed: no workgroup barrier.
+//
+// Two arithmetic paths give identical results:
+//   MODE 0  every step in 32-bit lanes; valid for the whole parameter domain.
+//   MODE 1  two elements per 32-bit lane in packed 16-bit (v_pk_*), for the usual case
+//           where the clamped delta, n = -Qp and (i0 << N) all fit 16 bits.
+//   MODE 2  as MODE 1, with n pre-shifted so that the divider's multiplier fits 24 bits
+//           for small i0.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "device_common.h"
+#include "plan.h"
+
+namespace iptq {
+
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+enum { PM_NONE = 0, PM_CLAMP127 = 1, PM_GENERAL = 2 };
+
+// One exponential in 32-bit lanes (Eq. 7-10 / 13-14).  x is the (biased) score, `lower`
+// is max(row) - D saturated, mx the row maximum.  Elements at or below `lower` get the
+// same all-zero result as their true value, which keeps every intermediate in 32 bits.
+template <int VARIANT, bool EXPLICIT_MASK>
+IPTQ_DEV uint32_t bit_exp_dev(int32_t x, int32_t lower, int32_t mx, const SoftmaxDev &P)
+{
+    const int32_t xc = max(x, lower);
+    const int32_t dl = xc - mx;                        // Eq. 6, in [-D, 0]
+    const int32_t s1 = dl >> 1, s4 = dl >> 4;
+    const int32_t n = (s4 - dl) - s1;                  // -Qp of Eq. 7, >= 0
+    const uint32_t q = mulhi_u32((uint32_t)n, P.magic) >> P.magic_sh;   // Eq. 8: n div i0
+    const int32_t nr = (int32_t)__umul24(q, (uint32_t)P.i0) - n;        // -r in (-i0, 0]
+    int32_t fr = nr >> 1;                              // Eq. 10: x / 2
+    if (VARIANT == 1) fr += (nr >> 3) + (nr >> 4);     // Eq. 13: (0.1011)b x
+    const uint32_t base = ((uint32_t)fr << P.n_shift) + (uint32_t)P.i0n;  // Eq. 14, << N
+    uint32_t e = base >> q;                            // Eq. 9 (q <= 31 by the clamp)
+    if (EXPLICIT_MASK) e = (x == kI32Min) ? 0u : e;
+    return e;
+}
+
+template <int POSTMODE>
+IPTQ_DEV uint32_t post_dev(uint32_t p, const SoftmaxDev &P)
+{
+    if (POSTMODE == PM_NONE) return p;
+    if (POSTMODE == PM_CLAMP127) return min(p, 127u);
+    // general dyadic requantization; p <= 2^(b-1) so 64-bit arithmetic is ample
+    const int64_t rnd = P.post_s > 0 ? ((int64_t)1 << (P.post_s - 1)) : 0;
+    int64_t v = (((int64_t)p * P.post_m + rnd) >> P.post_s) + P.post_zp;
+    v = v < P.qmin ? P.qmin : v;
+    v = v > P.qmax ? P.qmax : v;
+    return (uint32_t)(int32_t)v & 0xffu;
+}
+
+// row index modulo the bias period without a divide
+IPTQ_DEV uint32_t row_mod_period(uint32_t row, const SoftmaxDev &P)
+{
+    if (P.bias_period_rows == 1) return 0u;
+    const uint32_t q = mulhi_u32(row, P.period_magic) >> P.period_sh;
+    return row - q * (uint32_t)P.bias_period_rows;
+}
+
+// bytes 3 of (a, b, c, d) -> one dword (a in byte 0)
+IPTQ_DEV uint32_t pack_top_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    const uint32_t ab = __builtin_amdgcn_perm(b, a, 0x0c0c0703u);
+    const uint32_t cd = __builtin_amdgcn_perm(d, c, 0x0c0c0703u);
+    return __builtin_amdgcn_perm(cd, ab, 0x05040100u);
+}
+
+// per-byte min(v, 127) for bytes that are at most 128
+IPTQ_DEV uint32_t clamp127_bytes(uint32_t w) { return w - ((w >> 7) & 0x01010101u); }
+
+// Eq. 15 for one block of four exponentials in 32-bit lanes -> four output bytes
+template <int POSTMODE>
+IPTQ_DEV uint32_t normalise4(uint32_t e0, uint32_t e1, uint32_t e2, uint32_t e3, uint32_t f,
+                             uint32_t f_top, const SoftmaxDev &P)
+{
+    if (POSTMODE != PM_GENERAL && P.p_shift <= 24) {
+        // (f << (24 - p_shift)) * Qexp <= 2^31 carries p in its top byte
+        uint32_t w = pack_top_bytes(e0 * f_top, e1 * f_top, e2 * f_top, e3 * f_top);
+        if (POSTMODE == PM_CLAMP127) w = clamp127_bytes(w);
+        return w;
+    }
+    const uint32_t p0 = post_dev<POSTMODE>((e0 * f) >> P.p_shift, P);
+    const uint32_t p1 = post_dev<POSTMODE>((e1 * f) >> P.p_shift, P);
+    const uint32_t p2 = post_dev<POSTMODE>((e2 * f) >> P.p_shift, P);
+    const uint32_t p3 = post_dev<POSTMODE>((e3 * f) >> P.p_shift, P);
+    return p0 | (p1 << 8) | (p2 << 16) | (p3 << 24);
+}
+
+IPTQ_DEV uint32_t mulhi_u24(uint32_t a, uint32_t b)   // both below 2^24: bits 47..32 of a*b
+{
+    return (uint32_t)(((uint64_t)(a & 0xffffffu) * (uint64_t)(b & 0xffffffu)) >> 32);
+}
+
+// Two exponentials at once in packed 16-bit lanes.  Preconditions (checked on the host,
+// SoftmaxDev::p16): D <= 32767, n_max <= 65535 >> t16, i0 << N < 2^15 (so q <= 15 at the
+// clamp), divider multiplier mg24 < 2^24 exact for (n << t16).
+template <int VARIANT, bool SHIFTED>
+IPTQ_DEV u16x2 bit_exp_pair(int32_t xa, int32_t xb, int32_t mx, const SoftmaxDev &P)
+{
+    const int32_t da = __builtin_elementwise_sub_sat(xa, mx);
+    const int32_t db = __builtin_elementwise_sub_sat(xb, mx);
+    s16x2 dl = __builtin_amdgcn_cvt_pk_i16(da, db);            // saturates to 16 bits
+    const short nd = (short)(-P.d_clamp);
+    dl = __builtin_elementwise_max(dl, (s16x2){nd, nd});       // Eq. 6 with the clamp at -D
+    const s16x2 s1 = dl >> 1, s4 = dl >> 4;
+    const u16x2 n = (u16x2)((s4 - dl) - s1);                   // -Qp of Eq. 7
+    u16x2 ns = n;
+    if (SHIFTED) ns = n << (unsigned short)P.t16;
+    const uint32_t qa = mulhi_u24((uint32_t)ns.x, P.mg24);     // Eq. 8: n div i0
+    const uint32_t qb = mulhi_u24((uint32_t)ns.y, P.mg24);
+    const u16x2 q = {(unsigned short)qa, (unsigned short)qb};
+    const unsigned short i0 = (unsigned short)P.i0;
+    const s16x2 nr = (s16x2)(q * (u16x2){i0, i0} - n);         // -r in (-i0, 0]
+    s16x2 fr = nr >> 1;                                        // Eq. 10
+    if (VARIANT == 1) fr = fr + (nr >> 3) + (nr >> 4);         // Eq. 13
+    const unsigned short sc = (unsigned short)(1u << P.n_shift), one = (unsigned short)P.i0n;
+    const u16x2 base = (u16x2)fr * (u16x2){sc, sc} + (u16x2){one, one};   // Eq. 14, << N
+    return base >> q;                                          // Eq. 9 (q <= 15)
+}
+
+template <int COLS, int K, int MODE, int VARIANT, bool BIAS, int POSTMODE>
+__global__ void __launch_bounds__(256)
+softmax_rows_kernel(const int32_t *__restrict__ scores, const int32_t *__restrict__ bias,
+                    uint8_t *__restrict__ out, int64_t n_slabs, SoftmaxDev P)
+{
+    constexpr int RPW = 64 / K;                       // rows per wavefront
+    constexpr int SLAB = RPW * COLS;                  // elements per slab
+    static_assert(SLAB % 16 == 0, "slab must be 16-byte aligned in the byte output");
+    static_assert(MODE == 0 || POSTMODE != PM_GENERAL, "packed path has no general post step");
+    constexpr int NB = (COLS + 3 + 3) / 4;            // 16-byte blocks a row can touch
+    constexpr int SLOTS = (NB + K - 1) / K;           // blocks per lane
+    constexpr int IN_CHUNKS = SLAB / 4;               // 16-byte chunks of the input slab
+    constexpr int OUT_CHUNKS = SLAB / 16;             // 16-byte chunks of the output slab
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4][SLAB * 4];
+
+    const int lane = threadIdx.x & 63;
+    const int wv = threadIdx.x >> 6;
+    const int64_t slab = (int64_t)blockIdx.x * 4 + wv;
+    if (slab >= n_slabs) return;                      // no workgroup barrier below
+
+    uint8_t *lds = lds_all[wv];
+    const i32x4 *src = reinterpret_cast<const i32x4 *>(scores + slab * SLAB);
+    const int lr = lane / K;                          // row inside the slab
+    const int j = lane % K;                           // lane inside the row
+    const int e_r = lr * COLS;                        // first element of the row in the slab
+    const int b_r = e_r >> 2;                         // its 16-byte block
+    const int phi = e_r & 3;                          // and its offset inside that block
+
+    // ---- flat copy of the slab into LDS, bias added on the way
+    {
+        i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
+        uint32_t boff = 0;
+        if (BIAS) boff = row_mod_period((uint32_t)(slab * RPW), P) * (uint32_t)COLS;
+        const uint32_t pe = (uint32_t)P.bias_period_rows * (uint32_t)COLS;
+#pragma unroll
+        for (int i = 0; i < (IN_CHUNKS + 63) / 64; ++i) {
+            const int idx = i * 64 + lane;
+            if ((i + 1) * 64 <= IN_CHUNKS || idx < IN_CHUNKS) {
+                i32x4 v = stream_load(src + idx);
+                if (BIAS) {
+                    uint32_t o = boff + 4u * (uint32_t)idx;
+                    if (o >= pe) o -= pe;
+                    const i32x4 bv = *reinterpret_cast<const i32x4 *>(bias + o);
+                    v.x = v.x == kI32Min ? v.x : sat_add_i32(v.x, bv.x);
+                    v.y = v.y == kI32Min ? v.y : sat_add_i32(v.y, bv.y);
+                    v.z = v.z == kI32Min ? v.z : sat_add_i32(v.z, bv.z);
+                    v.w = v.w == kI32Min ? v.w : sat_add_i32(v.w, bv.w);
+                }
+                lds4[idx] = v;
+            }
+        }
+        wave_lds_fence();
+    }
+
+    // ---- this lane's blocks; elements outside the row become "minus infinity"
+    int32_t x[SLOTS][4];
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+        const int b = s * K + j;
+        const bool always_inside = 4 * (s * K + K - 1) < COLS;
+        i32x4 v = {kI32Min, kI32Min, kI32Min, kI32Min};
+        if (always_inside || 4 * b < phi + COLS) v = reinterpret_cast<const i32x4 *>(lds)[b_r + b];
+        x[s][0] = v.x; x[s][1] = v.y; x[s][2] = v.z; x[s][3] = v.w;
+        const bool may_cut = (s == 0) || (4 * (s * K + K - 1) + 3 >= COLS);
+        if (may_cut) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int c = 4 * b + e - phi;
+                if ((unsigned)c >= (unsigned)COLS) x[s][e] = kI32Min;
+            }
+        }
+    }
+    wave_lds_fence();                                 // the slab area is reused for the output
+
+    // ---- Eq. 6: row maximum
+    int32_t mx = kI32Min;
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mx = max(mx, x[s][e]);
+    mx = group_max_i32<K>(mx);
+
+    // Rows whose maximum lies within D of INT32_MIN cannot rely on the clamp to zero out
+    // masked entries; the whole wavefront then takes the 32-bit path with an explicit test.
+    const int32_t D = P.d_clamp;
+    const bool low_row = mx < kI32Min + D;
+    const int32_t lower = low_row ? kI32Min : mx - D;
+    const bool any_low = __builtin_amdgcn_ballot_w64(low_row) != 0;
+    uint32_t w[SLOTS];                                // four output bytes per block
+
+    if (MODE != 0 && !any_low) {
+        // ---- packed 16-bit path
+        uint32_t e2[SLOTS][2];
+        uint32_t sum = 0;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const u16x2 qe = bit_exp_pair<VARIANT, MODE == 2>(x[s][2 * h], x[s][2 * h + 1], mx, P);
+                sum = __builtin_amdgcn_udot2(qe, (u16x2){1, 1}, sum, false);
+                e2[s][h] = __builtin_bit_cast(uint32_t, qe);
+            }
+        sum = group_sum_u32<K>(sum);
+        const uint32_t f_top = floor_pow2_div(P.m_bits, sum) << (24 - P.p_shift);   // < 2^24
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const uint32_t a = __umul24(e2[s][0] & 0xffffu, f_top), b = __umul24(e2[s][0] >> 16, f_top);
+            const uint32_t c = __umul24(e2[s][1] & 0xffffu, f_top), d = __umul24(e2[s][1] >> 16, f_top);
+            uint32_t ww = pack_top_bytes(a, b, c, d);
+            if (POSTMODE == PM_CLAMP127) ww = clamp127_bytes(ww);
+            w[s] = ww;
+        }
+    } else {
+        // ---- 32-bit path
+        uint32_t sum = 0;
+        if (!any_low) {
+#pragma unroll
+            for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t q = bit_exp_dev<VARIANT, false>(x[s][e], lower, mx, P);
+                    x[s][e] = (int32_t)q;
+                    sum += q;
+                }
+        } else {
+#pragma unroll
+            for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t q = bit_exp_dev<VARIANT, true>(x[s][e], lower, mx, P);
+                    x[s][e] = (int32_t)q;
+                    sum += q;
+                }
+        }
+        sum = group_sum_u32<K>(sum);
+        const uint32_t f = floor_pow2_div(P.m_bits, sum);
+        const uint32_t f_top = P.p_shift <= 24 ? f << (24 - P.p_shift) : 0u;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s)
+            w[s] = normalise4<POSTMODE>((uint32_t)x[s][0], (uint32_t)x[s][1], (uint32_t)x[s][2],
+                                        (uint32_t)x[s][3], f, f_top, P);
+    }
+
+    // ---- assemble the slab's bytes in LDS
+    uint32_t *lds32 = reinterpret_cast<uint32_t *>(lds);
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+        const int b = s * K + j;
+        const bool always_full = (s != 0) && (4 * (s * K + K - 1) + 3 < COLS);
+        if (always_full) {
+            lds32[b_r + b] = w[s];
+        } else {
+            const int c0 = 4 * b - phi;
+            if (c0 >= 0 && c0 + 3 < COLS) {
+                lds32[b_r + b] = w[s];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if ((unsigned)(c0 + e) < (unsigned)COLS)
+                        lds[4 * (b_r + b) + e] = (uint8_t)(w[s] >> (8 * e));
+            }
+        }
+    }
+    wave_lds_fence();
+
+    // ---- flat, fully coalesced store
+    u32x4 *dst = reinterpret_cast<u32x4 *>(out + slab * SLAB);
+    const u32x4 *lds4o = reinterpret_cast<const u32x4 *>(lds);
+#pragma unroll
+    for (int i = 0; i < (OUT_CHUNKS + 63) / 64; ++i) {
+        const int idx = i * 64 + lane;
+        if ((i + 1) * 64 <= OUT_CHUNKS || idx < OUT_CHUNKS) stream_store(lds4o[idx], dst + idx);
+    }
+}
+
+// Launch helper: picks the POSTMODE instantiation.  Declared per row length in
+// softmax_rows_<cols>.hip so that the instantiations compile in parallel.
+template <int COLS, int K>
+hipError_t launch_softmax_rows(const int32_t *scores, const int32_t *bias, uint8_t *out,
+                               int64_t n_slabs, int mode, int post_mode, const SoftmaxDev &P,
+                               hipStream_t stream);
+
+template <>
+hipError_t launch_softmax_rows<197, 4>(const int32_t *, const int32_t *, uint8_t *, int64_t, int, int,
+                                       const SoftmaxDev &, hipStream_t);
+template <>
+hipError_t launch_softmax_rows<49, 1>(const int32_t *, const int32_t *, uint8_t *, int64_t, int, int,
+                                      const SoftmaxDev &, hipStream_t);
+
+#define IPTQ_ROWS_LAUNCH(COLS, K, MODE, VARIANT, BIAS, PM)                                        \
+    hipLaunchKernelGGL((softmax_rows_kernel<COLS, K, MODE, VARIANT, BIAS, PM>), grid, block, 0,   \
+                       stream, scores, bias, out, n_slabs, P)
+
+template <int COLS, int K, int VARIANT, bool BIAS>
+static hipError_t launch_rows_vb(const int32_t *scores, const int32_t *bias, uint8_t *out,
+                                 int64_t n_slabs, int mode, int post_mode, const SoftmaxDev &P,
+                                 hipStream_t stream)
+{
+    const dim3 grid((unsigned)((n_slabs + 3) / 4)), block(256);
+    if (post_mode == PM_GENERAL || mode == 0) {
+        switch (post_mode) {
+        case PM_NONE: IPTQ_ROWS_LAUNCH(COLS, K, 0, VARIANT, BIAS, PM_NONE); break;
+        case PM_CLAMP127: IPTQ_ROWS_LAUNCH(COLS, K, 0, VARIANT, BIAS, PM_CLAMP127); break;
+        default: IPTQ_ROWS_LAUNCH(COLS, K, 0, VARIANT, BIAS, PM_GENERAL); break;
+        }
+    } else if (mode == 1) {
+        if (post_mode == PM_NONE) IPTQ_ROWS_LAUNCH(COLS, K, 1, VARIANT, BIAS, PM_NONE);
+        else IPTQ_ROWS_LAUNCH(COLS, K, 1, VARIANT, BIAS, PM_CLAMP127);
+    } else {
+        if (post_mode == PM_NONE) IPTQ_ROWS_LAUNCH(COLS, K, 2, VARIANT, BIAS, PM_NONE);
+        else IPTQ_ROWS_LAUNCH(COLS, K, 2, VARIANT, BIAS, PM_CLAMP127);
+    }
+    return hipGetLastError();
+}
+
+#define IPTQ_DEFINE_ROWS_LAUNCHER(COLS, K)                                                        \
+    template <>                                                                                   \
+    hipError_t launch_softmax_rows<COLS, K>(const int32_t *scores, const int32_t *bias,           \
+                                            uint8_t *out, int64_t n_slabs, int mode,              \
+                                            int post_mode, const SoftmaxDev &P,                   \
+                                            hipStream_t stream)                                   \
+    {                                                                                             \
+        if (bias != nullptr)                                                                      \
+            return P.variant == 0                                                                 \
+                       ? launch_rows_vb<COLS, K, 0, true>(scores, bias, out, n_slabs, mode, post_mode, P, stream) \
+                       : launch_rows_vb<COLS, K, 1, true>(scores, bias, out, n_slabs, mode, post_mode, P, stream); \
+        return P.variant == 0                                                                     \
+                   ? launch_rows_vb<COLS, K, 0, false>(scores, bias, out, n_slabs, mode, post_mode, P, stream) \
+                   : launch_rows_vb<COLS, K, 1, false>(scores, bias, out, n_slabs, mode, post_mode, P, stream); \
+    }
+
+}  // namespace iptq

@@ -1,0 +1,7 @@
+// Instantiations of the fixed-row-length softmax for 49 columns (Swin 7x7 windows):
+// one lane per row, 64 rows per wavefront.
+#include "softmax_rows.h"
+
+namespace iptq {
+IPTQ_DEFINE_ROWS_LAUNCHER(49, 1)
+}

@@ -78,7 +78,7 @@ def _plan(p, rows, cols, has_bias=0, period=0):
     fn.restype = ctypes.c_int
     fn.argtypes = [ctypes.POINTER(ip.SoftmaxParams), ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                    ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
-    out = (ctypes.c_int64 * 8)()
+    out = (ctypes.c_int64 * 12)()
     rc = fn(ctypes.byref(p), rows, cols, has_bias, period, out)
     return rc, list(out)
 
@@ -89,7 +89,7 @@ def test_softmax_plan_divider_and_clamp(i0, n):
     p = lib_softmax(ref.SoftmaxParams(variant=1, i0=i0, n_shift=n))
     rc, o = _plan(p, 10, 3)
     assert rc == 0
-    magic, sh, D, i0n, p_shift, _, _, n_max = o
+    magic, sh, D, i0n, p_shift, _, _, n_max = o[:8]
     assert i0n == i0 << n and p_shift == 23
     # the divider is exact on the whole reachable range (sampled densely for large i0)
     step = max(1, n_max // 200000)
@@ -104,6 +104,33 @@ def test_softmax_plan_divider_and_clamp(i0, n):
         assert ref.bit_exp(-D, op) == 0 and ref.bit_exp(-D - 1, op) == 0
         assert ref.bit_exp(-(2 ** 30), op) == 0
     assert n_max // i0 <= 31
+
+
+def test_packed_path_divider_is_exact_wherever_it_is_enabled():
+    """Every i0 of the usual scale range: when the plan enables the packed 16-bit path, its
+    24-bit divider must give n div i0 for every reachable n, and all values must fit."""
+    enabled = 0
+    for i0 in list(range(16, 3400)) + [4000, 5000, 2 ** 14, 2 ** 15 - 1]:
+        for n_shift in {max(0, 15 - i0.bit_length()), 0}:
+            p = lib_softmax(ref.SoftmaxParams(variant=1, i0=i0, n_shift=n_shift))
+            rc, o = _plan(p, 10, 49)
+            assert rc == 0
+            D, n_max, mode, mg24, t16 = o[2], o[7], o[8], o[9], o[10]
+            if mode == 0:
+                continue
+            enabled += 1
+            assert mode == (1 if t16 == 0 else 2)
+            assert D <= 32767 and (n_max << t16) <= 65535 and mg24 < 2 ** 24 and (i0 << n_shift) < 2 ** 15
+            n = np.arange(0, n_max + 1, dtype=np.uint64)
+            q = ((n << np.uint64(t16)) * np.uint64(mg24)) >> np.uint64(32)
+            assert np.array_equal(q, n // np.uint64(i0)), i0
+            assert int(q.max()) <= 15
+    assert enabled > 3000
+    # default parameters of the whole benchmark scale range take the packed path
+    for log2s in np.linspace(-10, -4, 25):
+        p = ip.softmax_prepare(float(2.0 ** log2s), 197, 1, 0)
+        rc, o = _plan(p, 10, 197)
+        assert rc == 0 and o[8] in (1, 2)
 
 
 def test_bias_period_divider():
