@@ -118,8 +118,43 @@ gelu_i8_bytes_kernel(const uint8_t *in, uint8_t *out, int64_t n, GeluDev P)
         out[i] = (uint8_t)gelu_eval_any((int32_t)(int8_t)in[i], P);
 }
 
-// int32 accumulators -> int8 with the requantization in front.  A thread owns 16
-// consecutive elements: four dwordx4 loads, one dwordx4 store.
+// int32 -> byte streaming skeleton shared by the int32 GELU and the requantization: lane i
+// of a pass owns the 4 consecutive elements of 16-byte chunk i (a wavefront reads 1 KiB
+// contiguous per load and writes 256 B contiguous per store); four passes are in flight
+// per thread.  ALIGNED needs a 16-byte aligned input and a 4-byte aligned output.
+template <bool ALIGNED, typename F>
+IPTQ_DEV void stream_i32_to_bytes(const int32_t *in, uint8_t *out, int64_t n, F one)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (ALIGNED) {
+        const int64_t n4 = n >> 2;
+        const i32x4 *in4 = reinterpret_cast<const i32x4 *>(in);
+        uint32_t *out32 = reinterpret_cast<uint32_t *>(out);
+        for (int64_t base = tid; base < n4; base += 4 * stride) {
+            i32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t i = base + u * stride;
+                if (i < n4) v[u] = stream_load(in4 + i);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t i = base + u * stride;
+                if (i < n4)
+                    stream_store(pack4(one(v[u].x), one(v[u].y), one(v[u].z), one(v[u].w)), out32 + i);
+            }
+        }
+        if (blockIdx.x == 0) {
+            const int64_t i = (n4 << 2) + threadIdx.x;
+            if (threadIdx.x < 4 && i < n) out[i] = (uint8_t)one(in[i]);
+        }
+    } else {
+        for (int64_t i = tid; i < n; i += stride) out[i] = (uint8_t)one(in[i]);
+    }
+}
+
+// int32 accumulators -> int8 GELU with the requantization in front.
 template <bool ALIGNED>
 __global__ void __launch_bounds__(256)
 gelu_i32_kernel(const int32_t *in, uint8_t *out, int64_t n, GeluDev P)
@@ -136,31 +171,10 @@ gelu_i32_kernel(const int32_t *in, uint8_t *out, int64_t n, GeluDev P)
         const int32_t q = (int32_t)(c < -lim ? -lim : (c > lim ? lim : c));
         return gelu_eval_any(q, Q);
     };
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    if (ALIGNED) {
-        const int64_t n16 = n >> 4;
-        const i32x4 *in4 = reinterpret_cast<const i32x4 *>(in);
-        u32x4 *out4 = reinterpret_cast<u32x4 *>(out);
-        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
-            u32x4 r;
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const i32x4 v = stream_load(in4 + 4 * i + d);
-                r[d] = pack4(one(v.x), one(v.y), one(v.z), one(v.w));
-            }
-            stream_store(r, out4 + i);
-        }
-        if (blockIdx.x == 0) {
-            const int64_t i = (n16 << 4) + threadIdx.x;
-            if (threadIdx.x < 16 && i < n) out[i] = (uint8_t)one(in[i]);
-        }
-    } else {
-        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
-            out[i] = (uint8_t)one(in[i]);
-    }
+    stream_i32_to_bytes<ALIGNED>(in, out, n, one);
 }
 
-// int32 -> int8 / uint8 requantization, same access pattern.
+// int32 -> int8 / uint8 requantization.
 template <bool ALIGNED>
 __global__ void __launch_bounds__(256)
 requant_kernel(const int32_t *in, uint8_t *out, int64_t n, DyadicDev P)
@@ -169,28 +183,7 @@ requant_kernel(const int32_t *in, uint8_t *out, int64_t n, DyadicDev P)
         return P.s >= 16 ? requant_dev<true>(x, P.m, P.s, P.zp, P.qmin, P.qmax)
                          : requant_dev<false>(x, P.m, P.s, P.zp, P.qmin, P.qmax);
     };
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    if (ALIGNED) {
-        const int64_t n16 = n >> 4;
-        const i32x4 *in4 = reinterpret_cast<const i32x4 *>(in);
-        u32x4 *out4 = reinterpret_cast<u32x4 *>(out);
-        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
-            u32x4 r;
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const i32x4 v = stream_load(in4 + 4 * i + d);
-                r[d] = pack4(one(v.x), one(v.y), one(v.z), one(v.w));
-            }
-            stream_store(r, out4 + i);
-        }
-        if (blockIdx.x == 0) {
-            const int64_t i = (n16 << 4) + threadIdx.x;
-            if (threadIdx.x < 16 && i < n) out[i] = (uint8_t)one(in[i]);
-        }
-    } else {
-        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
-            out[i] = (uint8_t)one(in[i]);
-    }
+    stream_i32_to_bytes<ALIGNED>(in, out, n, one);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -229,9 +222,9 @@ hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const Ge
                              hipStream_t stream)
 {
     uint8_t *uout = reinterpret_cast<uint8_t *>(out);
-    const bool aligned = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+    const bool aligned = (reinterpret_cast<uintptr_t>(in) & 15) == 0 && (reinterpret_cast<uintptr_t>(out) & 3) == 0;
     if (aligned)
-        hipLaunchKernelGGL(gelu_i32_kernel<true>, dim3(grid_for(n >> 4, 256)), dim3(256), 0, stream, in,
+        hipLaunchKernelGGL(gelu_i32_kernel<true>, dim3(grid_for(n >> 2, 1024)), dim3(256), 0, stream, in,
                            uout, n, P);
     else
         hipLaunchKernelGGL(gelu_i32_kernel<false>, dim3(grid_for(n, 256)), dim3(256), 0, stream, in,
@@ -243,9 +236,9 @@ hipError_t requant_dispatch(const int32_t *in, void *out, int64_t n, const Dyadi
                             hipStream_t stream)
 {
     uint8_t *uout = reinterpret_cast<uint8_t *>(out);
-    const bool aligned = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+    const bool aligned = (reinterpret_cast<uintptr_t>(in) & 15) == 0 && (reinterpret_cast<uintptr_t>(out) & 3) == 0;
     if (aligned)
-        hipLaunchKernelGGL(requant_kernel<true>, dim3(grid_for(n >> 4, 256)), dim3(256), 0, stream, in,
+        hipLaunchKernelGGL(requant_kernel<true>, dim3(grid_for(n >> 2, 1024)), dim3(256), 0, stream, in,
                            uout, n, P);
     else
         hipLaunchKernelGGL(requant_kernel<false>, dim3(grid_for(n, 256)), dim3(256), 0, stream, in, uout,

@@ -99,14 +99,17 @@ hipError_t softmax_dispatch(const int32_t *scores, const int32_t *bias, uint8_t 
                    ((int64_t)P.bias_period_rows * cols) % 4 == 0 && P.bias_period_rows >= rpw;
         };
         hipError_t err = hipSuccess;
-        if (cols == 197 && bias_ok(16)) {
-            const int64_t n_slabs = rows / 16;
-            if (n_slabs > 0) err = launch_softmax_rows<197, 4>(scores, bias, out, n_slabs, P.mode16, post_mode, P, stream);
-            done = n_slabs * 16;
-        } else if (cols == 49 && bias_ok(64)) {
-            const int64_t n_slabs = rows / 64;
-            if (n_slabs > 0) err = launch_softmax_rows<49, 1>(scores, bias, out, n_slabs, P.mode16, post_mode, P, stream);
-            done = n_slabs * 64;
+        constexpr int rpw197 = 64 / IPTQ_K197, rpw49 = 64 / IPTQ_K49;
+        if (cols == 197 && bias_ok(rpw197)) {
+            const int64_t n_slabs = rows / rpw197;
+            if (n_slabs > 0)
+                err = launch_softmax_rows<197, IPTQ_K197>(scores, bias, out, n_slabs, P.mode16, post_mode, P, stream);
+            done = n_slabs * rpw197;
+        } else if (cols == 49 && bias_ok(rpw49)) {
+            const int64_t n_slabs = rows / rpw49;
+            if (n_slabs > 0)
+                err = launch_softmax_rows<49, IPTQ_K49>(scores, bias, out, n_slabs, P.mode16, post_mode, P, stream);
+            done = n_slabs * rpw49;
         }
         if (err != hipSuccess) return err;
     }

@@ -137,12 +137,13 @@ softmax_rows_kernel(const int32_t *__restrict__ scores, const int32_t *__restric
 {
     constexpr int RPW = 64 / K;                       // rows per wavefront
     constexpr int SLAB = RPW * COLS;                  // elements per slab
-    static_assert(SLAB % 16 == 0, "slab must be 16-byte aligned in the byte output");
+    static_assert(RPW % 4 == 0, "slab must start on a 16-byte boundary of the int32 input");
     static_assert(MODE == 0 || POSTMODE != PM_GENERAL, "packed path has no general post step");
     constexpr int NB = (COLS + 3 + 3) / 4;            // 16-byte blocks a row can touch
     constexpr int SLOTS = (NB + K - 1) / K;           // blocks per lane
     constexpr int IN_CHUNKS = SLAB / 4;               // 16-byte chunks of the input slab
-    constexpr int OUT_CHUNKS = SLAB / 16;             // 16-byte chunks of the output slab
+    constexpr bool OUT16 = SLAB % 16 == 0;            // output slab is whole 16-byte chunks
+    constexpr int OUT_CHUNKS = OUT16 ? SLAB / 16 : SLAB / 4;   // else whole dwords
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4][SLAB * 4];
 
     const int lane = threadIdx.x & 63;
@@ -296,12 +297,21 @@ softmax_rows_kernel(const int32_t *__restrict__ scores, const int32_t *__restric
     wave_lds_fence();
 
     // ---- flat, fully coalesced store
-    u32x4 *dst = reinterpret_cast<u32x4 *>(out + slab * SLAB);
-    const u32x4 *lds4o = reinterpret_cast<const u32x4 *>(lds);
+    if (OUT16) {
+        u32x4 *dst = reinterpret_cast<u32x4 *>(out + slab * SLAB);
+        const u32x4 *lds4o = reinterpret_cast<const u32x4 *>(lds);
 #pragma unroll
-    for (int i = 0; i < (OUT_CHUNKS + 63) / 64; ++i) {
-        const int idx = i * 64 + lane;
-        if ((i + 1) * 64 <= OUT_CHUNKS || idx < OUT_CHUNKS) stream_store(lds4o[idx], dst + idx);
+        for (int i = 0; i < (OUT_CHUNKS + 63) / 64; ++i) {
+            const int idx = i * 64 + lane;
+            if ((i + 1) * 64 <= OUT_CHUNKS || idx < OUT_CHUNKS) stream_store(lds4o[idx], dst + idx);
+        }
+    } else {
+        uint32_t *dst = reinterpret_cast<uint32_t *>(out + slab * SLAB);
+#pragma unroll
+        for (int i = 0; i < (OUT_CHUNKS + 63) / 64; ++i) {
+            const int idx = i * 64 + lane;
+            if ((i + 1) * 64 <= OUT_CHUNKS || idx < OUT_CHUNKS) stream_store(lds32[idx], dst + idx);
+        }
     }
 }
 
@@ -312,12 +322,19 @@ hipError_t launch_softmax_rows(const int32_t *scores, const int32_t *bias, uint8
                                int64_t n_slabs, int mode, int post_mode, const SoftmaxDev &P,
                                hipStream_t stream);
 
+// lanes per row of the two instantiated row lengths
+#ifndef IPTQ_K197
+#define IPTQ_K197 4
+#endif
+#ifndef IPTQ_K49
+#define IPTQ_K49 1
+#endif
 template <>
-hipError_t launch_softmax_rows<197, 4>(const int32_t *, const int32_t *, uint8_t *, int64_t, int, int,
-                                       const SoftmaxDev &, hipStream_t);
+hipError_t launch_softmax_rows<197, IPTQ_K197>(const int32_t *, const int32_t *, uint8_t *, int64_t,
+                                               int, int, const SoftmaxDev &, hipStream_t);
 template <>
-hipError_t launch_softmax_rows<49, 1>(const int32_t *, const int32_t *, uint8_t *, int64_t, int, int,
-                                      const SoftmaxDev &, hipStream_t);
+hipError_t launch_softmax_rows<49, IPTQ_K49>(const int32_t *, const int32_t *, uint8_t *, int64_t, int,
+                                             int, const SoftmaxDev &, hipStream_t);
 
 #define IPTQ_ROWS_LAUNCH(COLS, K, MODE, VARIANT, BIAS, PM)                                        \
     hipLaunchKernelGGL((softmax_rows_kernel<COLS, K, MODE, VARIANT, BIAS, PM>), grid, block, 0,   \

@@ -3,5 +3,5 @@
 #include "softmax_rows.h"
 
 namespace iptq {
-IPTQ_DEFINE_ROWS_LAUNCHER(197, 4)
+IPTQ_DEFINE_ROWS_LAUNCHER(197, IPTQ_K197)
 }

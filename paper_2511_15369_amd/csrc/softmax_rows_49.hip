@@ -3,5 +3,5 @@
 #include "softmax_rows.h"
 
 namespace iptq {
-IPTQ_DEFINE_ROWS_LAUNCHER(49, 1)
+IPTQ_DEFINE_ROWS_LAUNCHER(49, IPTQ_K49)
 }
