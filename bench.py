@@ -106,7 +106,7 @@ def time_region(fn, reps):
     return start.elapsed_time(stop) / reps
 
 
-def cpu_baseline(name, budget_units=4):
+def cpu_baseline(name, budget_units=12):
     """The CPU oracle, single thread, on the first layers of the same workload."""
     import workloads
     from oracle import prepare, ref
@@ -170,6 +170,18 @@ def main():
             for u in units:
                 u.gelu()
 
+        # the same work through the batched entry points: one launch per kernel family
+        sm_probs = (ip.SoftmaxProblem * len(units))(*[
+            ip.softmax_problem(u.d_scores, u.d_bias, u.period, u.d_probs, u.rows, u.cols, u.sp)
+            for u in units])
+        ge_probs = (ip.GeluProblem * len(units))(*[
+            ip.gelu_problem(u.d_x, u.d_y, u.gelu_n, u.gp) for u in units])
+        cols = units[0].cols
+
+        def step_batched():
+            ip.softmax_i32_batch(sm_probs, len(units), cols)
+            ip.gelu_i8_batch(ge_probs, len(units))
+
         for _ in range(args.warmup):
             step()
         torch.cuda.synchronize()
@@ -189,7 +201,18 @@ def main():
                      "gbps": GELU_BYTES_PER_EL * ge_el / len(units) / (ge_ms * 1e-3) / 1e9},
         }
         res["value"] = (sm_el + ge_el) / (ms * 1e-3)
-        res["algorithmic_gbps"] = (SOFTMAX_BYTES_PER_EL * sm_el + GELU_BYTES_PER_EL * ge_el) / (ms * 1e-3) / 1e9
+        alg_bytes = SOFTMAX_BYTES_PER_EL * sm_el + GELU_BYTES_PER_EL * ge_el
+        res["algorithmic_gbps"] = alg_bytes / (ms * 1e-3) / 1e9
+        if len(units) <= ip.BATCH_MAX:
+            for _ in range(3):
+                step_batched()
+            bms = time_region(step_batched, args.steps)
+            bsm = time_region(lambda: ip.softmax_i32_batch(sm_probs, len(units), cols), args.steps)
+            res["batched"] = {"ms_per_step": bms, "value": (sm_el + ge_el) / (bms * 1e-3),
+                              "algorithmic_gbps": alg_bytes / (bms * 1e-3) / 1e9,
+                              "pct_of_hbm_peak": 100.0 * alg_bytes / (bms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                              "softmax_launch_us": bsm * 1e3,
+                              "softmax_gbps": SOFTMAX_BYTES_PER_EL * sm_el / (bsm * 1e-3) / 1e9}
         del units
         torch.cuda.empty_cache()
         return res
@@ -226,11 +249,12 @@ def main():
             "algorithmic_bytes_per_launch": SOFTMAX_BYTES_PER_EL * sm["elements"] // sm["launches"],
         },
         "kernels": {"softmax": sm, "gelu": main_res["gelu"]},
+        "batched": main_res.get("batched"),
     }
     if not args.no_extra and args.workload != "swin_b":
         sw = measure("swin_b")
         out["extra"] = {"swin_b": {k: sw[k] for k in ("value", "ms_per_step", "algorithmic_gbps",
-                                                      "softmax", "gelu")}}
+                                                      "softmax", "gelu", "batched")}}
         out["extra"]["swin_b"]["pct_of_hbm_peak"] = 100.0 * sw["algorithmic_gbps"] / HBM_PEAK_GBS
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)

@@ -159,10 +159,39 @@ int iptq_gelu_i32(const int32_t *d_in, int8_t *d_out, int64_t n, const iptq_gelu
                   void *stream);
 
 /*
- * Layer-batched forms for model sweeps: layer l reads d_scores + l * in_stride (elements)
- * and writes d_out + l * out_stride (bytes) with p[l]; all layers share rows and cols (or n).
- * Equivalent to n_layers single calls on `stream`; the per-layer variant choice of
- * Section 4.2 is the `variant` field of each p[l].  No bias.
+ * Batched forms: several independent problems in as few kernel launches as possible (at most
+ * IPTQ_BATCH_MAX problems per call), e.g. the layers of a model sweep or the stages of a Swin
+ * backbone.  Results are identical to one single call per problem; all problems are checked
+ * before anything is enqueued.  The per-layer variant choice of Section 4.2 is the `variant`
+ * field of each problem's parameters.  Softmax problems of one call share the row length.
+ */
+#define IPTQ_BATCH_MAX 16
+
+typedef struct {
+    const int32_t *d_scores;  /* rows * cols int32 (device) */
+    const int32_t *d_bias;    /* NULL or [bias_period_rows, cols] int32 (device) */
+    int64_t bias_period_rows;
+    void *d_out;              /* rows * cols bytes (device) */
+    int64_t rows;
+    iptq_softmax_params_t params;
+} iptq_softmax_problem_t;
+
+typedef struct {
+    const int8_t *d_in; /* n int8 (device) */
+    int8_t *d_out;      /* n int8 (device), may equal d_in */
+    int64_t n;
+    iptq_gelu_params_t params;
+} iptq_gelu_problem_t;
+
+int iptq_softmax_i32_batch(const iptq_softmax_problem_t *problems /*host*/, int32_t n_problems,
+                           int32_t cols, void *stream);
+int iptq_gelu_i8_batch(const iptq_gelu_problem_t *problems /*host*/, int32_t n_problems,
+                       void *stream);
+
+/*
+ * Layer-strided forms of the same: layer l reads d_scores + l * in_stride (elements) and
+ * writes d_out + l * out_stride (bytes) with p[l]; all layers share rows and cols (or n);
+ * any number of layers.  No bias.
  */
 int iptq_softmax_i32_layers(const int32_t *d_scores, int64_t in_stride, void *d_out,
                             int64_t out_stride, int64_t rows, int32_t cols, int32_t n_layers,

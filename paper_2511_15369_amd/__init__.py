@@ -5,12 +5,17 @@ gfx950).  PyTorch is used only for device memory and streams.
 """
 
 from .binding import (  # noqa: F401
+    BATCH_MAX,
     Dyadic,
+    GeluProblem,
+    SoftmaxProblem,
     GeluParams,
     IptqError,
     SoftmaxParams,
     gelu_i8,
+    gelu_i8_batch,
     gelu_i8_layers,
+    gelu_problem,
     gelu_i32,
     gelu_prepare,
     lib_path,
@@ -18,7 +23,9 @@ from .binding import (  # noqa: F401
     make_dyadic,
     requant,
     softmax_i32,
+    softmax_i32_batch,
     softmax_i32_layers,
+    softmax_problem,
     softmax_prepare,
     strerror,
     version,

@@ -45,6 +45,20 @@ class GeluParams(ctypes.Structure):
                 ("algo", ctypes.c_int32)]
 
 
+class SoftmaxProblem(ctypes.Structure):
+    _fields_ = [("d_scores", ctypes.c_void_p), ("d_bias", ctypes.c_void_p),
+                ("bias_period_rows", ctypes.c_int64), ("d_out", ctypes.c_void_p),
+                ("rows", ctypes.c_int64), ("params", SoftmaxParams)]
+
+
+class GeluProblem(ctypes.Structure):
+    _fields_ = [("d_in", ctypes.c_void_p), ("d_out", ctypes.c_void_p), ("n", ctypes.c_int64),
+                ("params", GeluParams)]
+
+
+BATCH_MAX = 16
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -69,13 +83,16 @@ def load():
     lib.iptq_softmax_i32_layers.argtypes = [vp, i64, vp, i64, i64, i32, i32,
                                             ctypes.POINTER(SoftmaxParams), vp]
     lib.iptq_gelu_i8_layers.argtypes = [vp, i64, vp, i64, i64, i32, ctypes.POINTER(GeluParams), vp]
+    lib.iptq_softmax_i32_batch.argtypes = [ctypes.POINTER(SoftmaxProblem), i32, i32, vp]
+    lib.iptq_gelu_i8_batch.argtypes = [ctypes.POINTER(GeluProblem), i32, vp]
     lib.iptq_make_dyadic.argtypes = [ctypes.c_double, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     lib.iptq_softmax_prepare.argtypes = [ctypes.c_double, i32, i32, i32,
                                          ctypes.POINTER(SoftmaxParams)]
     lib.iptq_gelu_prepare.argtypes = [ctypes.c_double, ctypes.c_double, i32, i32, i32, i32,
                                       ctypes.POINTER(GeluParams)]
     for name in ("iptq_requant", "iptq_softmax_i32", "iptq_gelu_i8", "iptq_gelu_i32",
-                 "iptq_softmax_i32_layers", "iptq_gelu_i8_layers", "iptq_make_dyadic",
+                 "iptq_softmax_i32_layers", "iptq_gelu_i8_layers", "iptq_softmax_i32_batch",
+                 "iptq_gelu_i8_batch", "iptq_make_dyadic",
                  "iptq_softmax_prepare", "iptq_gelu_prepare"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -201,3 +218,39 @@ def gelu_i8_layers(d_in, in_stride: int, d_out, out_stride: int, n: int, n_layer
     arr = (GeluParams * max(n_layers, 1))(*params)
     _check(load().iptq_gelu_i8_layers(_dptr(d_in), in_stride, _dptr(d_out), out_stride, n,
                                       n_layers, arr, _stream()), "iptq_gelu_i8_layers")
+
+
+def softmax_problem(d_scores, d_bias, bias_period_rows: int, d_out, rows: int, cols: int,
+                    p: SoftmaxParams) -> SoftmaxProblem:
+    """One entry of a softmax batch (same checks as softmax_i32)."""
+    import torch
+    _need(d_scores, torch.int32, "d_scores")
+    _need(d_out, torch.int8 if p.out_is_signed else torch.uint8, "d_out")
+    assert d_scores.numel() >= rows * cols and d_out.numel() >= rows * cols
+    if d_bias is not None:
+        _need(d_bias, torch.int32, "d_bias")
+        assert d_bias.numel() >= bias_period_rows * cols
+    return SoftmaxProblem(d_scores.data_ptr(), None if d_bias is None else d_bias.data_ptr(),
+                          bias_period_rows, d_out.data_ptr(), rows, p)
+
+
+def gelu_problem(d_in, d_out, n: int, p: GeluParams) -> GeluProblem:
+    import torch
+    _need(d_in, torch.int8, "d_in")
+    _need(d_out, torch.int8, "d_out")
+    assert d_in.numel() >= n and d_out.numel() >= n
+    return GeluProblem(d_in.data_ptr(), d_out.data_ptr(), n, p)
+
+
+def softmax_i32_batch(problems, n_problems: int, cols: int):
+    """problems: a ctypes array (SoftmaxProblem * n) or a sequence of SoftmaxProblem."""
+    if not isinstance(problems, ctypes.Array):
+        problems = (SoftmaxProblem * max(n_problems, 1))(*problems)
+    _check(load().iptq_softmax_i32_batch(problems, n_problems, cols, _stream()),
+           "iptq_softmax_i32_batch")
+
+
+def gelu_i8_batch(problems, n_problems: int):
+    if not isinstance(problems, ctypes.Array):
+        problems = (GeluProblem * max(n_problems, 1))(*problems)
+    _check(load().iptq_gelu_i8_batch(problems, n_problems, _stream()), "iptq_gelu_i8_batch")

@@ -32,37 +32,94 @@ extern "C" int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t
     return hip_rc(requant_dispatch(d_in, d_out, n, dev, static_cast<hipStream_t>(stream)));
 }
 
-extern "C" int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias,
-                                int64_t bias_period_rows, void *d_out, int64_t rows, int32_t cols,
-                                const iptq_softmax_params_t *p, void *stream)
+// Validates one softmax problem and fills its launch record.  rows == 0 is valid.
+static int softmax_call(const int32_t *d_scores, const int32_t *d_bias, int64_t bias_period_rows,
+                        void *d_out, int64_t rows, int32_t cols, const iptq_softmax_params_t *p,
+                        SoftmaxCall *out)
 {
     if (!p) return IPTQ_ERR_NULL;
-    SoftmaxDev dev;
-    int rc = plan_softmax(p, rows, cols, d_bias != nullptr, bias_period_rows, &dev);
+    int rc = plan_softmax(p, rows, cols, d_bias != nullptr, bias_period_rows, &out->P);
     if (rc != IPTQ_OK) return rc;
+    out->scores = d_scores; out->bias = d_bias; out->out = static_cast<uint8_t *>(d_out);
+    out->rows = rows; out->out_bits = p->out_bits; out->force_generic = p->algo == IPTQ_ALGO_GENERIC;
     if (rows == 0) return IPTQ_OK;
     if (!d_scores || !d_out) return IPTQ_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(d_scores) & 3) || (reinterpret_cast<uintptr_t>(d_bias) & 3))
         return IPTQ_ERR_ALIGN;
     if (overlap(d_scores, rows * cols * 4, d_out, rows * cols)) return IPTQ_ERR_PARAM;
-    return hip_rc(softmax_dispatch(d_scores, d_bias, static_cast<uint8_t *>(d_out), rows, cols,
-                                   p->out_bits, p->algo == IPTQ_ALGO_GENERIC, dev,
-                                   static_cast<hipStream_t>(stream)));
+    return IPTQ_OK;
+}
+
+static int gelu_call(const int8_t *d_in, int8_t *d_out, int64_t n, const iptq_gelu_params_t *p,
+                     GeluCall *out)
+{
+    if (!p) return IPTQ_ERR_NULL;
+    if (n < 0) return IPTQ_ERR_SHAPE;
+    int rc = plan_gelu(p, 1, &out->P);
+    if (rc != IPTQ_OK) return rc;
+    out->in = d_in; out->out = d_out; out->n = n; out->force_direct = p->algo == IPTQ_ALGO_GENERIC;
+    if (n == 0) return IPTQ_OK;
+    if (!d_in || !d_out) return IPTQ_ERR_NULL;
+    if (d_in != d_out && overlap(d_in, n, d_out, n)) return IPTQ_ERR_PARAM;
+    return IPTQ_OK;
+}
+
+extern "C" int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias,
+                                int64_t bias_period_rows, void *d_out, int64_t rows, int32_t cols,
+                                const iptq_softmax_params_t *p, void *stream)
+{
+    SoftmaxCall call;
+    int rc = softmax_call(d_scores, d_bias, bias_period_rows, d_out, rows, cols, p, &call);
+    if (rc != IPTQ_OK || rows == 0) return rc;
+    return hip_rc(softmax_dispatch(&call, 1, cols, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int iptq_softmax_i32_batch(const iptq_softmax_problem_t *problems, int32_t n_problems,
+                                      int32_t cols, void *stream)
+{
+    if (n_problems < 0) return IPTQ_ERR_SHAPE;
+    if (n_problems == 0) return IPTQ_OK;
+    if (!problems) return IPTQ_ERR_NULL;
+    if (n_problems > IPTQ_BATCH_MAX) return IPTQ_ERR_SHAPE;
+    SoftmaxCall calls[IPTQ_BATCH_MAX];
+    int n = 0;
+    for (int32_t i = 0; i < n_problems; ++i) {           // every problem is checked before any launch
+        const iptq_softmax_problem_t &q = problems[i];
+        int rc = softmax_call(q.d_scores, q.d_bias, q.bias_period_rows, q.d_out, q.rows, cols,
+                              &q.params, &calls[n]);
+        if (rc != IPTQ_OK) return rc;
+        if (q.rows > 0) ++n;
+    }
+    if (n == 0) return IPTQ_OK;
+    return hip_rc(softmax_dispatch(calls, n, cols, static_cast<hipStream_t>(stream)));
 }
 
 extern "C" int iptq_gelu_i8(const int8_t *d_in, int8_t *d_out, int64_t n,
                             const iptq_gelu_params_t *p, void *stream)
 {
-    if (!p) return IPTQ_ERR_NULL;
-    if (n < 0) return IPTQ_ERR_SHAPE;
-    GeluDev dev;
-    int rc = plan_gelu(p, 1, &dev);
-    if (rc != IPTQ_OK) return rc;
+    GeluCall call;
+    int rc = gelu_call(d_in, d_out, n, p, &call);
+    if (rc != IPTQ_OK || n == 0) return rc;
+    return hip_rc(gelu_i8_dispatch(&call, 1, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int iptq_gelu_i8_batch(const iptq_gelu_problem_t *problems, int32_t n_problems,
+                                  void *stream)
+{
+    if (n_problems < 0) return IPTQ_ERR_SHAPE;
+    if (n_problems == 0) return IPTQ_OK;
+    if (!problems) return IPTQ_ERR_NULL;
+    if (n_problems > IPTQ_BATCH_MAX) return IPTQ_ERR_SHAPE;
+    GeluCall calls[IPTQ_BATCH_MAX];
+    int n = 0;
+    for (int32_t i = 0; i < n_problems; ++i) {
+        const iptq_gelu_problem_t &q = problems[i];
+        int rc = gelu_call(q.d_in, q.d_out, q.n, &q.params, &calls[n]);
+        if (rc != IPTQ_OK) return rc;
+        if (q.n > 0) ++n;
+    }
     if (n == 0) return IPTQ_OK;
-    if (!d_in || !d_out) return IPTQ_ERR_NULL;
-    if (d_in != d_out && overlap(d_in, n, d_out, n)) return IPTQ_ERR_PARAM;
-    return hip_rc(gelu_i8_dispatch(d_in, d_out, n, p->algo == IPTQ_ALGO_GENERIC, dev,
-                                   static_cast<hipStream_t>(stream)));
+    return hip_rc(gelu_i8_dispatch(calls, n, static_cast<hipStream_t>(stream)));
 }
 
 extern "C" int iptq_gelu_i32(const int32_t *d_in, int8_t *d_out, int64_t n,
@@ -85,20 +142,29 @@ extern "C" int iptq_softmax_i32_layers(const int32_t *d_scores, int64_t in_strid
                                        int32_t n_layers, const iptq_softmax_params_t *p,
                                        void *stream)
 {
-    if (!p) return IPTQ_ERR_NULL;
     if (n_layers < 0 || in_stride < 0 || out_stride < 0) return IPTQ_ERR_SHAPE;
-    // validate every layer before the first launch
-    for (int32_t l = 0; l < n_layers; ++l) {
-        SoftmaxDev dev;
-        int rc = plan_softmax(&p[l], rows, cols, 0, 0, &dev);
-        if (rc != IPTQ_OK) return rc;
-    }
+    if (n_layers == 0) return IPTQ_OK;
+    if (!p) return IPTQ_ERR_NULL;
     if (n_layers > 1 && rows > 0 && (in_stride < rows * cols || out_stride < rows * cols))
         return IPTQ_ERR_SHAPE;
+    // every layer is checked before the first launch
     for (int32_t l = 0; l < n_layers; ++l) {
-        int rc = iptq_softmax_i32(d_scores ? d_scores + l * in_stride : nullptr, nullptr, 0,
-                                  d_out ? static_cast<uint8_t *>(d_out) + l * out_stride : nullptr,
-                                  rows, cols, &p[l], stream);
+        SoftmaxCall call;
+        int rc = softmax_call(d_scores ? d_scores + l * in_stride : nullptr, nullptr, 0,
+                              d_out ? static_cast<uint8_t *>(d_out) + l * out_stride : nullptr, rows,
+                              cols, &p[l], &call);
+        if (rc != IPTQ_OK) return rc;
+    }
+    if (rows == 0) return IPTQ_OK;
+    for (int32_t base = 0; base < n_layers; base += IPTQ_BATCH_MAX) {
+        SoftmaxCall calls[IPTQ_BATCH_MAX];
+        const int32_t cnt = n_layers - base < IPTQ_BATCH_MAX ? n_layers - base : IPTQ_BATCH_MAX;
+        for (int32_t i = 0; i < cnt; ++i) {
+            const int32_t l = base + i;
+            softmax_call(d_scores + l * in_stride, nullptr, 0, static_cast<uint8_t *>(d_out) + l * out_stride,
+                         rows, cols, &p[l], &calls[i]);
+        }
+        int rc = hip_rc(softmax_dispatch(calls, cnt, cols, static_cast<hipStream_t>(stream)));
         if (rc != IPTQ_OK) return rc;
     }
     return IPTQ_OK;
@@ -108,17 +174,25 @@ extern "C" int iptq_gelu_i8_layers(const int8_t *d_in, int64_t in_stride, int8_t
                                    int64_t out_stride, int64_t n, int32_t n_layers,
                                    const iptq_gelu_params_t *p, void *stream)
 {
-    if (!p) return IPTQ_ERR_NULL;
     if (n_layers < 0 || in_stride < 0 || out_stride < 0 || n < 0) return IPTQ_ERR_SHAPE;
-    for (int32_t l = 0; l < n_layers; ++l) {
-        GeluDev dev;
-        int rc = plan_gelu(&p[l], 1, &dev);
-        if (rc != IPTQ_OK) return rc;
-    }
+    if (n_layers == 0) return IPTQ_OK;
+    if (!p) return IPTQ_ERR_NULL;
     if (n_layers > 1 && (in_stride < n || out_stride < n)) return IPTQ_ERR_SHAPE;
     for (int32_t l = 0; l < n_layers; ++l) {
-        int rc = iptq_gelu_i8(d_in ? d_in + l * in_stride : nullptr,
-                              d_out ? d_out + l * out_stride : nullptr, n, &p[l], stream);
+        GeluCall call;
+        int rc = gelu_call(d_in ? d_in + l * in_stride : nullptr, d_out ? d_out + l * out_stride : nullptr,
+                           n, &p[l], &call);
+        if (rc != IPTQ_OK) return rc;
+    }
+    if (n == 0) return IPTQ_OK;
+    for (int32_t base = 0; base < n_layers; base += IPTQ_BATCH_MAX) {
+        GeluCall calls[IPTQ_BATCH_MAX];
+        const int32_t cnt = n_layers - base < IPTQ_BATCH_MAX ? n_layers - base : IPTQ_BATCH_MAX;
+        for (int32_t i = 0; i < cnt; ++i) {
+            const int32_t l = base + i;
+            gelu_call(d_in + l * in_stride, d_out + l * out_stride, n, &p[l], &calls[i]);
+        }
+        int rc = hip_rc(gelu_i8_dispatch(calls, cnt, static_cast<hipStream_t>(stream)));
         if (rc != IPTQ_OK) return rc;
     }
     return IPTQ_OK;

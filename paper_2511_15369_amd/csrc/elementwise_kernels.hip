@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include "device_common.h"
+#include "kernels.h"
 #include "plan.h"
 
 namespace iptq {
@@ -46,20 +47,42 @@ IPTQ_DEV int32_t sbyte(uint32_t w, int i) { return (int32_t)(int8_t)(w >> (8 * i
 // ---------------------------------------------------------------------------------------
 // int8 -> int8 through a per-workgroup table: the polynomial is evaluated once for each of
 // the 256 input codes with the exact integer formula, then every element is one byte
-// gather from LDS.  n16 = number of whole 16-byte chunks; the last (n & 15) bytes are done
-// by workgroup 0.  in and out must be 16-byte aligned; they may be the same buffer.
+// gather from LDS.  One launch serves up to kGeluBatchMax independent problems (the layers
+// of a sweep): workgroups [first_wg, first_wg + n_wgs) stream item i.  The last (n & 15)
+// bytes of an item are done by its first workgroup.  in and out must be 16-byte aligned;
+// they may be the same buffer.
+constexpr int kGeluBatchMax = 16;
+struct GeluItem {
+    const uint8_t *in;
+    uint8_t *out;
+    int64_t n;
+    uint32_t first_wg;
+    uint32_t n_wgs;
+    GeluDev P;
+};
+struct GeluBatch {
+    int32_t n_items;
+    GeluItem item[kGeluBatchMax];
+};
+
 __global__ void __launch_bounds__(256)
-gelu_i8_table_kernel(const uint8_t *in, uint8_t *out, int64_t n, GeluDev P)
+gelu_i8_table_kernel(GeluBatch B)
 {
+    int it = 0;
+    for (int i = 1; i < B.n_items; ++i)
+        if (blockIdx.x >= B.item[i].first_wg) it = i;
+    const GeluItem &I = B.item[it];
     __shared__ uint8_t table[256];
-    table[threadIdx.x] = (uint8_t)gelu_eval_any((int32_t)(int8_t)threadIdx.x, P);
+    table[threadIdx.x] = (uint8_t)gelu_eval_any((int32_t)(int8_t)threadIdx.x, I.P);
     __syncthreads();
 
+    const int64_t n = I.n;
     const int64_t n16 = n >> 4;
-    const u32x4 *in4 = reinterpret_cast<const u32x4 *>(in);
-    u32x4 *out4 = reinterpret_cast<u32x4 *>(out);
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+    const u32x4 *in4 = reinterpret_cast<const u32x4 *>(I.in);
+    u32x4 *out4 = reinterpret_cast<u32x4 *>(I.out);
+    const uint32_t lb = blockIdx.x - I.first_wg;
+    const int64_t stride = (int64_t)I.n_wgs * 256;
+    for (int64_t i = (int64_t)lb * 256 + threadIdx.x; i < n16; i += stride) {
         const u32x4 v = stream_load(in4 + i);
         u32x4 r;
 #pragma unroll
@@ -73,9 +96,9 @@ gelu_i8_table_kernel(const uint8_t *in, uint8_t *out, int64_t n, GeluDev P)
         }
         stream_store(r, out4 + i);
     }
-    if (blockIdx.x == 0) {
+    if (lb == 0) {
         const int64_t i = (n16 << 4) + threadIdx.x;
-        if (threadIdx.x < 16 && i < n) out[i] = table[in[i]];
+        if (threadIdx.x < 16 && i < n) I.out[i] = table[I.in[i]];
     }
 }
 
@@ -199,22 +222,39 @@ static unsigned grid_for(int64_t work_items, int per_block)
     return (unsigned)g;
 }
 
-hipError_t gelu_i8_dispatch(const int8_t *in, int8_t *out, int64_t n, bool force_direct,
-                            const GeluDev &P, hipStream_t stream)
+hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stream)
 {
-    const uint8_t *uin = reinterpret_cast<const uint8_t *>(in);
-    uint8_t *uout = reinterpret_cast<uint8_t *>(out);
-    const bool aligned = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
-    if (!aligned) {
-        hipLaunchKernelGGL(gelu_i8_bytes_kernel, dim3(grid_for(n, 256)), dim3(256), 0, stream, uin,
-                           uout, n, P);
-    } else if (force_direct) {
-        hipLaunchKernelGGL(gelu_i8_direct_kernel, dim3(grid_for(n >> 4, 256)), dim3(256), 0, stream,
-                           uin, uout, n, P);
-    } else {
-        hipLaunchKernelGGL(gelu_i8_table_kernel, dim3(grid_for(n >> 4, 256)), dim3(256), 0, stream,
-                           uin, uout, n, P);
+    GeluBatch B;
+    B.n_items = 0;
+    unsigned total_wgs = 0;
+    auto flush = [&]() {
+        if (B.n_items == 0) return;
+        hipLaunchKernelGGL(gelu_i8_table_kernel, dim3(total_wgs), dim3(256), 0, stream, B);
+        B.n_items = 0;
+        total_wgs = 0;
+    };
+    for (int c = 0; c < n_calls; ++c) {
+        const GeluCall &g = calls[c];
+        if (g.n == 0) continue;
+        const uint8_t *uin = reinterpret_cast<const uint8_t *>(g.in);
+        uint8_t *uout = reinterpret_cast<uint8_t *>(g.out);
+        const bool aligned = ((reinterpret_cast<uintptr_t>(g.in) | reinterpret_cast<uintptr_t>(g.out)) & 15) == 0;
+        if (!aligned) {
+            hipLaunchKernelGGL(gelu_i8_bytes_kernel, dim3(grid_for(g.n, 256)), dim3(256), 0, stream,
+                               uin, uout, g.n, g.P);
+        } else if (g.force_direct) {
+            hipLaunchKernelGGL(gelu_i8_direct_kernel, dim3(grid_for(g.n >> 4, 256)), dim3(256), 0,
+                               stream, uin, uout, g.n, g.P);
+        } else {
+            if (B.n_items == kGeluBatchMax) flush();
+            GeluItem &it = B.item[B.n_items++];
+            it.in = uin; it.out = uout; it.n = g.n; it.P = g.P;
+            it.first_wg = total_wgs;
+            it.n_wgs = grid_for(g.n >> 4, 256);
+            total_wgs += it.n_wgs;
+        }
     }
+    flush();
     return hipGetLastError();
 }
 

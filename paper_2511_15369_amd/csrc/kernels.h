@@ -8,11 +8,27 @@
 
 namespace iptq {
 
-hipError_t softmax_dispatch(const int32_t *scores, const int32_t *bias, uint8_t *out, int64_t rows,
-                            int32_t cols, int out_bits, bool force_generic, const SoftmaxDev &P,
-                            hipStream_t stream);
-hipError_t gelu_i8_dispatch(const int8_t *in, int8_t *out, int64_t n, bool force_direct,
-                            const GeluDev &P, hipStream_t stream);
+// One softmax problem: rows x cols scores -> bytes, validated parameters.
+struct SoftmaxCall {
+    const int32_t *scores;
+    const int32_t *bias;
+    uint8_t *out;
+    int64_t rows;
+    int out_bits;
+    bool force_generic;
+    SoftmaxDev P;
+};
+// One int8 GELU problem.
+struct GeluCall {
+    const int8_t *in;
+    int8_t *out;
+    int64_t n;
+    bool force_direct;
+    GeluDev P;
+};
+
+hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols, hipStream_t stream);
+hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stream);
 hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,
                              hipStream_t stream);
 hipError_t requant_dispatch(const int32_t *in, void *out, int64_t n, const DyadicDev &P,

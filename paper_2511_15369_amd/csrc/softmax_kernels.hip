@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include "device_common.h"
+#include "kernels.h"
 #include "plan.h"
 #include "softmax_rows.h"
 
@@ -81,39 +82,66 @@ static hipError_t launch_generic(const int32_t *scores, const int32_t *bias, uin
     return hipGetLastError();
 }
 
-// Enqueue the softmax of rows [0, rows).  Returns a hipError_t.
-hipError_t softmax_dispatch(const int32_t *scores, const int32_t *bias, uint8_t *out, int64_t rows,
-                            int32_t cols, int out_bits, bool force_generic, const SoftmaxDev &P,
-                            hipStream_t stream)
+// Enqueue the softmax of every call (all with the same row length).  Calls that can use a
+// fixed-row-length kernel are grouped, up to kBatchMax per launch, while they agree on what
+// the kernel instantiation fixes (bias or not, post step, packed or 32-bit arithmetic); the
+// rows a slab decomposition leaves over, and calls it cannot serve, go to the generic kernel.
+hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols, hipStream_t stream)
 {
-    const bool has_bias = bias != nullptr;
-    const bool has_pre = !(P.pre_m == 1 && P.pre_s == 0);
-    const bool aligned = ((reinterpret_cast<uintptr_t>(scores) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
-    const int post_mode = post_mode_of(P, out_bits);
-    int64_t done = 0;
-    if (!force_generic && !has_pre && aligned) {
-        // the fused bias needs 16-byte aligned bias blocks and at most one wrap per slab
-        auto bias_ok = [&](int rpw) {
-            if (!has_bias) return true;
-            return (reinterpret_cast<uintptr_t>(bias) & 15) == 0 &&
-                   ((int64_t)P.bias_period_rows * cols) % 4 == 0 && P.bias_period_rows >= rpw;
-        };
-        hipError_t err = hipSuccess;
-        constexpr int rpw197 = 64 / IPTQ_K197, rpw49 = 64 / IPTQ_K49;
-        if (cols == 197 && bias_ok(rpw197)) {
-            const int64_t n_slabs = rows / rpw197;
-            if (n_slabs > 0)
-                err = launch_softmax_rows<197, IPTQ_K197>(scores, bias, out, n_slabs, P.mode16, post_mode, P, stream);
-            done = n_slabs * rpw197;
-        } else if (cols == 49 && bias_ok(rpw49)) {
-            const int64_t n_slabs = rows / rpw49;
-            if (n_slabs > 0)
-                err = launch_softmax_rows<49, IPTQ_K49>(scores, bias, out, n_slabs, P.mode16, post_mode, P, stream);
-            done = n_slabs * rpw49;
+    const int rpw = cols == 197 ? 64 / IPTQ_K197 : (cols == 49 ? 64 / IPTQ_K49 : 0);
+    SoftmaxBatch B;
+    B.n_items = 0;
+    unsigned total_wgs = 0;
+    bool g_bias = false;
+    int g_pm = 0, g_mode = 0;
+    hipError_t err = hipSuccess;
+    auto flush = [&]() {
+        if (B.n_items == 0 || err != hipSuccess) return;
+        err = cols == 197 ? launch_softmax_rows<197, IPTQ_K197>(B, total_wgs, g_bias, g_mode, g_pm, stream)
+                          : launch_softmax_rows<49, IPTQ_K49>(B, total_wgs, g_bias, g_mode, g_pm, stream);
+        B.n_items = 0;
+        total_wgs = 0;
+    };
+    int64_t done[kBatchMax];
+    for (int base = 0; base < n_calls; base += kBatchMax) {
+        const int cnt = n_calls - base < kBatchMax ? n_calls - base : kBatchMax;
+        for (int i = 0; i < cnt; ++i) {
+            const SoftmaxCall &c = calls[base + i];
+            done[i] = 0;
+            const bool has_bias = c.bias != nullptr;
+            const bool has_pre = !(c.P.pre_m == 1 && c.P.pre_s == 0);
+            const bool aligned =
+                ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.out)) & 15) == 0;
+            // the fused bias needs 16-byte aligned bias blocks and at most one wrap per slab
+            const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
+                                               ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
+                                               c.P.bias_period_rows >= rpw);
+            if (rpw == 0 || c.force_generic || has_pre || !aligned || !bias_ok) continue;
+            const int64_t n_slabs = c.rows / rpw;
+            if (n_slabs == 0) continue;
+            const int pm = post_mode_of(c.P, c.out_bits);
+            const int mode = pm == PM_GENERAL ? 0 : c.P.mode16;
+            const bool compatible = B.n_items == 0 || (has_bias == g_bias && pm == g_pm &&
+                                                       (mode == 0) == (g_mode == 0));
+            if (!compatible || B.n_items == kBatchMax) flush();
+            if (B.n_items == 0) { g_bias = has_bias; g_pm = pm; g_mode = mode; }
+            else if (mode > g_mode) g_mode = mode;       // 2 covers 1: items with t16 == 0 shift by 0
+            SoftmaxItem &it = B.item[B.n_items++];
+            it.scores = c.scores; it.bias = c.bias; it.out = c.out;
+            it.n_slabs = n_slabs; it.first_wg = total_wgs; it.P = c.P;
+            total_wgs += (unsigned)((n_slabs + 3) / 4);
+            done[i] = n_slabs * rpw;
+        }
+        flush();
+        for (int i = 0; i < cnt && err == hipSuccess; ++i) {
+            const SoftmaxCall &c = calls[base + i];
+            const bool has_pre = !(c.P.pre_m == 1 && c.P.pre_s == 0);
+            err = launch_generic(c.scores, c.bias, c.out, done[i], c.rows, cols, c.bias != nullptr,
+                                 has_pre, c.P, stream);
         }
         if (err != hipSuccess) return err;
     }
-    return launch_generic(scores, bias, out, done, rows, cols, has_bias, has_pre, P, stream);
+    return err;
 }
 
 }  // namespace iptq

@@ -28,6 +28,23 @@ typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
 enum { PM_NONE = 0, PM_CLAMP127 = 1, PM_GENERAL = 2 };
 
+// One launch serves up to kBatchMax independent problems of the same row length (the layers
+// of a model sweep, the stages of a Swin backbone): workgroups [first_wg, next first_wg)
+// belong to item i.  The table travels in the kernel arguments.
+constexpr int kBatchMax = 16;
+struct SoftmaxItem {
+    const int32_t *scores;
+    const int32_t *bias;
+    uint8_t *out;
+    int64_t n_slabs;
+    uint32_t first_wg;
+    SoftmaxDev P;
+};
+struct SoftmaxBatch {
+    int32_t n_items;
+    SoftmaxItem item[kBatchMax];
+};
+
 // One exponential in 32-bit lanes (Eq. 7-10 / 13-14).  x is the (biased) score, `lower`
 // is max(row) - D saturated, mx the row maximum.  Elements at or below `lower` get the
 // same all-zero result as their true value, which keeps every intermediate in 32 bits.
@@ -130,10 +147,69 @@ IPTQ_DEV u16x2 bit_exp_pair(int32_t xa, int32_t xb, int32_t mx, const SoftmaxDev
     return base >> q;                                          // Eq. 9 (q <= 15)
 }
 
-template <int COLS, int K, int MODE, int VARIANT, bool BIAS, int POSTMODE>
+// The arithmetic of one wavefront's slab once its rows sit in registers: exponentials, row
+// sum, reciprocal, probabilities -> four output bytes per block in w[].
+template <int K, int SLOTS, int MODE, int VARIANT, int POSTMODE>
+IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], int32_t mx,
+                                int32_t lower, bool any_low, const SoftmaxDev &P)
+{
+    if (MODE != 0 && !any_low) {
+        // ---- packed 16-bit path
+        uint32_t e2[SLOTS][2];
+        uint32_t sum = 0;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const u16x2 qe = bit_exp_pair<VARIANT, MODE == 2>(x[s][2 * h], x[s][2 * h + 1], mx, P);
+                sum = __builtin_amdgcn_udot2(qe, (u16x2){1, 1}, sum, false);
+                e2[s][h] = __builtin_bit_cast(uint32_t, qe);
+            }
+        sum = group_sum_u32<K>(sum);
+        const uint32_t f_top = floor_pow2_div(P.m_bits, sum) << (24 - P.p_shift);   // < 2^24
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const uint32_t a = __umul24(e2[s][0] & 0xffffu, f_top), b = __umul24(e2[s][0] >> 16, f_top);
+            const uint32_t c = __umul24(e2[s][1] & 0xffffu, f_top), d = __umul24(e2[s][1] >> 16, f_top);
+            uint32_t ww = pack_top_bytes(a, b, c, d);
+            if (POSTMODE == PM_CLAMP127) ww = clamp127_bytes(ww);
+            w[s] = ww;
+        }
+    } else {
+        // ---- 32-bit path
+        uint32_t sum = 0;
+        if (!any_low) {
+#pragma unroll
+            for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t q = bit_exp_dev<VARIANT, false>(x[s][e], lower, mx, P);
+                    x[s][e] = (int32_t)q;
+                    sum += q;
+                }
+        } else {
+#pragma unroll
+            for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t q = bit_exp_dev<VARIANT, true>(x[s][e], lower, mx, P);
+                    x[s][e] = (int32_t)q;
+                    sum += q;
+                }
+        }
+        sum = group_sum_u32<K>(sum);
+        const uint32_t f = floor_pow2_div(P.m_bits, sum);
+        const uint32_t f_top = P.p_shift <= 24 ? f << (24 - P.p_shift) : 0u;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s)
+            w[s] = normalise4<POSTMODE>((uint32_t)x[s][0], (uint32_t)x[s][1], (uint32_t)x[s][2],
+                                        (uint32_t)x[s][3], f, f_top, P);
+    }
+}
+
+template <int COLS, int K, int MODE, bool BIAS, int POSTMODE>
 __global__ void __launch_bounds__(256)
-softmax_rows_kernel(const int32_t *__restrict__ scores, const int32_t *__restrict__ bias,
-                    uint8_t *__restrict__ out, int64_t n_slabs, SoftmaxDev P)
+softmax_rows_kernel(SoftmaxBatch B)
 {
     constexpr int RPW = 64 / K;                       // rows per wavefront
     constexpr int SLAB = RPW * COLS;                  // elements per slab
@@ -148,8 +224,16 @@ softmax_rows_kernel(const int32_t *__restrict__ scores, const int32_t *__restric
 
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
-    const int64_t slab = (int64_t)blockIdx.x * 4 + wv;
-    if (slab >= n_slabs) return;                      // no workgroup barrier below
+    int it = 0;                                       // which problem this workgroup serves
+    for (int i = 1; i < B.n_items; ++i)
+        if (blockIdx.x >= B.item[i].first_wg) it = i;
+    const SoftmaxItem &I = B.item[it];
+    const SoftmaxDev &P = I.P;
+    const int32_t *__restrict__ scores = I.scores;
+    const int32_t *__restrict__ bias = I.bias;
+    uint8_t *__restrict__ out = I.out;
+    const int64_t slab = (int64_t)(blockIdx.x - I.first_wg) * 4 + wv;
+    if (slab >= I.n_slabs) return;                    // no workgroup barrier below
 
     uint8_t *lds = lds_all[wv];
     const i32x4 *src = reinterpret_cast<const i32x4 *>(scores + slab * SLAB);
@@ -221,58 +305,8 @@ softmax_rows_kernel(const int32_t *__restrict__ scores, const int32_t *__restric
     const bool any_low = __builtin_amdgcn_ballot_w64(low_row) != 0;
     uint32_t w[SLOTS];                                // four output bytes per block
 
-    if (MODE != 0 && !any_low) {
-        // ---- packed 16-bit path
-        uint32_t e2[SLOTS][2];
-        uint32_t sum = 0;
-#pragma unroll
-        for (int s = 0; s < SLOTS; ++s)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const u16x2 qe = bit_exp_pair<VARIANT, MODE == 2>(x[s][2 * h], x[s][2 * h + 1], mx, P);
-                sum = __builtin_amdgcn_udot2(qe, (u16x2){1, 1}, sum, false);
-                e2[s][h] = __builtin_bit_cast(uint32_t, qe);
-            }
-        sum = group_sum_u32<K>(sum);
-        const uint32_t f_top = floor_pow2_div(P.m_bits, sum) << (24 - P.p_shift);   // < 2^24
-#pragma unroll
-        for (int s = 0; s < SLOTS; ++s) {
-            const uint32_t a = __umul24(e2[s][0] & 0xffffu, f_top), b = __umul24(e2[s][0] >> 16, f_top);
-            const uint32_t c = __umul24(e2[s][1] & 0xffffu, f_top), d = __umul24(e2[s][1] >> 16, f_top);
-            uint32_t ww = pack_top_bytes(a, b, c, d);
-            if (POSTMODE == PM_CLAMP127) ww = clamp127_bytes(ww);
-            w[s] = ww;
-        }
-    } else {
-        // ---- 32-bit path
-        uint32_t sum = 0;
-        if (!any_low) {
-#pragma unroll
-            for (int s = 0; s < SLOTS; ++s)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t q = bit_exp_dev<VARIANT, false>(x[s][e], lower, mx, P);
-                    x[s][e] = (int32_t)q;
-                    sum += q;
-                }
-        } else {
-#pragma unroll
-            for (int s = 0; s < SLOTS; ++s)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t q = bit_exp_dev<VARIANT, true>(x[s][e], lower, mx, P);
-                    x[s][e] = (int32_t)q;
-                    sum += q;
-                }
-        }
-        sum = group_sum_u32<K>(sum);
-        const uint32_t f = floor_pow2_div(P.m_bits, sum);
-        const uint32_t f_top = P.p_shift <= 24 ? f << (24 - P.p_shift) : 0u;
-#pragma unroll
-        for (int s = 0; s < SLOTS; ++s)
-            w[s] = normalise4<POSTMODE>((uint32_t)x[s][0], (uint32_t)x[s][1], (uint32_t)x[s][2],
-                                        (uint32_t)x[s][3], f, f_top, P);
-    }
+    if (P.variant == 0) softmax_slab_math<K, SLOTS, MODE, 0, POSTMODE>(x, w, mx, lower, any_low, P);
+    else softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE>(x, w, mx, lower, any_low, P);
 
     // ---- assemble the slab's bytes in LDS
     uint32_t *lds32 = reinterpret_cast<uint32_t *>(lds);
@@ -315,12 +349,11 @@ softmax_rows_kernel(const int32_t *__restrict__ scores, const int32_t *__restric
     }
 }
 
-// Launch helper: picks the POSTMODE instantiation.  Declared per row length in
-// softmax_rows_<cols>.hip so that the instantiations compile in parallel.
+// Launch helper, defined once per row length in softmax_rows_<cols>.hip so that the
+// instantiations compile in parallel.  mode: 0 / 1 / 2 as above; all items share has_bias.
 template <int COLS, int K>
-hipError_t launch_softmax_rows(const int32_t *scores, const int32_t *bias, uint8_t *out,
-                               int64_t n_slabs, int mode, int post_mode, const SoftmaxDev &P,
-                               hipStream_t stream);
+hipError_t launch_softmax_rows(const SoftmaxBatch &B, unsigned total_wgs, bool has_bias, int mode,
+                               int post_mode, hipStream_t stream);
 
 // lanes per row of the two instantiated row lengths
 #ifndef IPTQ_K197
@@ -330,52 +363,42 @@ hipError_t launch_softmax_rows(const int32_t *scores, const int32_t *bias, uint8
 #define IPTQ_K49 1
 #endif
 template <>
-hipError_t launch_softmax_rows<197, IPTQ_K197>(const int32_t *, const int32_t *, uint8_t *, int64_t,
-                                               int, int, const SoftmaxDev &, hipStream_t);
+hipError_t launch_softmax_rows<197, IPTQ_K197>(const SoftmaxBatch &, unsigned, bool, int, int, hipStream_t);
 template <>
-hipError_t launch_softmax_rows<49, IPTQ_K49>(const int32_t *, const int32_t *, uint8_t *, int64_t, int,
-                                             int, const SoftmaxDev &, hipStream_t);
+hipError_t launch_softmax_rows<49, IPTQ_K49>(const SoftmaxBatch &, unsigned, bool, int, int, hipStream_t);
 
-#define IPTQ_ROWS_LAUNCH(COLS, K, MODE, VARIANT, BIAS, PM)                                        \
-    hipLaunchKernelGGL((softmax_rows_kernel<COLS, K, MODE, VARIANT, BIAS, PM>), grid, block, 0,   \
-                       stream, scores, bias, out, n_slabs, P)
+#define IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM)                                                 \
+    hipLaunchKernelGGL((softmax_rows_kernel<COLS, K, MODE, BIAS, PM>), grid, block, 0, stream, B)
 
-template <int COLS, int K, int VARIANT, bool BIAS>
-static hipError_t launch_rows_vb(const int32_t *scores, const int32_t *bias, uint8_t *out,
-                                 int64_t n_slabs, int mode, int post_mode, const SoftmaxDev &P,
-                                 hipStream_t stream)
+template <int COLS, int K, bool BIAS>
+static hipError_t launch_rows_b(const SoftmaxBatch &B, unsigned total_wgs, int mode, int post_mode,
+                                hipStream_t stream)
 {
-    const dim3 grid((unsigned)((n_slabs + 3) / 4)), block(256);
+    const dim3 grid(total_wgs), block(256);
     if (post_mode == PM_GENERAL || mode == 0) {
         switch (post_mode) {
-        case PM_NONE: IPTQ_ROWS_LAUNCH(COLS, K, 0, VARIANT, BIAS, PM_NONE); break;
-        case PM_CLAMP127: IPTQ_ROWS_LAUNCH(COLS, K, 0, VARIANT, BIAS, PM_CLAMP127); break;
-        default: IPTQ_ROWS_LAUNCH(COLS, K, 0, VARIANT, BIAS, PM_GENERAL); break;
+        case PM_NONE: IPTQ_ROWS_LAUNCH(COLS, K, 0, BIAS, PM_NONE); break;
+        case PM_CLAMP127: IPTQ_ROWS_LAUNCH(COLS, K, 0, BIAS, PM_CLAMP127); break;
+        default: IPTQ_ROWS_LAUNCH(COLS, K, 0, BIAS, PM_GENERAL); break;
         }
     } else if (mode == 1) {
-        if (post_mode == PM_NONE) IPTQ_ROWS_LAUNCH(COLS, K, 1, VARIANT, BIAS, PM_NONE);
-        else IPTQ_ROWS_LAUNCH(COLS, K, 1, VARIANT, BIAS, PM_CLAMP127);
+        if (post_mode == PM_NONE) IPTQ_ROWS_LAUNCH(COLS, K, 1, BIAS, PM_NONE);
+        else IPTQ_ROWS_LAUNCH(COLS, K, 1, BIAS, PM_CLAMP127);
     } else {
-        if (post_mode == PM_NONE) IPTQ_ROWS_LAUNCH(COLS, K, 2, VARIANT, BIAS, PM_NONE);
-        else IPTQ_ROWS_LAUNCH(COLS, K, 2, VARIANT, BIAS, PM_CLAMP127);
+        if (post_mode == PM_NONE) IPTQ_ROWS_LAUNCH(COLS, K, 2, BIAS, PM_NONE);
+        else IPTQ_ROWS_LAUNCH(COLS, K, 2, BIAS, PM_CLAMP127);
     }
     return hipGetLastError();
 }
 
 #define IPTQ_DEFINE_ROWS_LAUNCHER(COLS, K)                                                        \
     template <>                                                                                   \
-    hipError_t launch_softmax_rows<COLS, K>(const int32_t *scores, const int32_t *bias,           \
-                                            uint8_t *out, int64_t n_slabs, int mode,              \
-                                            int post_mode, const SoftmaxDev &P,                   \
+    hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &B, unsigned total_wgs,            \
+                                            bool has_bias, int mode, int post_mode,               \
                                             hipStream_t stream)                                   \
     {                                                                                             \
-        if (bias != nullptr)                                                                      \
-            return P.variant == 0                                                                 \
-                       ? launch_rows_vb<COLS, K, 0, true>(scores, bias, out, n_slabs, mode, post_mode, P, stream) \
-                       : launch_rows_vb<COLS, K, 1, true>(scores, bias, out, n_slabs, mode, post_mode, P, stream); \
-        return P.variant == 0                                                                     \
-                   ? launch_rows_vb<COLS, K, 0, false>(scores, bias, out, n_slabs, mode, post_mode, P, stream) \
-                   : launch_rows_vb<COLS, K, 1, false>(scores, bias, out, n_slabs, mode, post_mode, P, stream); \
+        return has_bias ? launch_rows_b<COLS, K, true>(B, total_wgs, mode, post_mode, stream)     \
+                        : launch_rows_b<COLS, K, false>(B, total_wgs, mode, post_mode, stream);   \
     }
 
 }  // namespace iptq

@@ -278,3 +278,79 @@ def test_requant(seed):
             assert np.array_equal(gpu_requant(data, d, signed), ref.requant(data, d, signed)), (m, s)
     d = ref.Dyadic(*prepare.make_dyadic(0.0123), 3, -128, 127)
     assert np.array_equal(gpu_requant(small, d, 1), ref.requant(small, d, 1))
+
+
+# --------------------------------------------------------------------------------- batched forms
+def test_softmax_batch_mixed_problems():
+    """One call, problems that differ in size, scale, variant, bias, output type and kernel
+    family (packed, 32-bit, generic, ragged tails): each must equal its single-call result."""
+    import torch
+    import paper_2511_15369_amd as ip
+    rng = np.random.default_rng(21)
+    for cols in (49, 197, 33):
+        specs = []
+        for i in range(11):
+            rows = int(rng.integers(1, 400))
+            x = np.rint(rng.standard_normal((rows, cols)) * float(rng.choice([200, 3000]))).astype(np.int32)
+            if i % 4 == 1:
+                x[0, :] = INT32_MIN
+            p = prepare.softmax_prepare(float(2.0 ** rng.uniform(-10, -4)), cols, i % 2, int(i % 3 == 0))
+            if i == 5:
+                p = ref.SoftmaxParams(variant=1, i0=2 ** 16, n_shift=2, out_is_signed=0)      # 32-bit arithmetic
+            if i == 6:
+                p.post = ref.Dyadic(3, 1, 7, 0, 255) if not p.out_is_signed else ref.Dyadic(3, 1, 7, -128, 127)
+            if i == 7:
+                p.pre_m, p.pre_s = 5, 1
+            bias, period = None, 0
+            if i % 5 == 2:
+                period = 96
+                bias = np.rint(rng.standard_normal((period, cols)) * 50).astype(np.int32)
+            specs.append((x, p, bias, period))
+        probs, keep = [], []
+        for x, p, bias, period in specs:
+            d_x = torch.from_numpy(x).cuda()
+            d_b = None if bias is None else torch.from_numpy(bias).cuda()
+            d_y = torch.full(x.shape, 0x5A, dtype=torch.int8 if p.out_is_signed else torch.uint8, device="cuda")
+            keep.append((d_x, d_b, d_y))
+            probs.append(ip.softmax_problem(d_x, d_b, period, d_y, x.shape[0], cols, lib_softmax(p)))
+        ip.softmax_i32_batch(probs, len(probs), cols)
+        torch.cuda.synchronize()
+        for (x, p, bias, period), (_, _, d_y) in zip(specs, keep):
+            assert np.array_equal(d_y.cpu().numpy(), ref.softmax_i32(x, p, bias, period))
+
+
+def test_gelu_batch_mixed_problems():
+    import torch
+    import paper_2511_15369_amd as ip
+    rng = np.random.default_rng(22)
+    specs, probs, keep = [], [], []
+    for i in range(16):
+        n = int(rng.choice([1, 15, 16, 4099, 70000, 300001]))
+        x = rng.integers(-128, 128, size=n, dtype=np.int8)
+        p = prepare.gelu_prepare(float(2.0 ** rng.uniform(-10, -4)), float(2.0 ** rng.uniform(-9, -4)),
+                                 int(rng.integers(-20, 20)), int(rng.integers(-100, 100)), i % 2)
+        d_x = torch.from_numpy(x).cuda()
+        d_y = torch.full((n,), 0x5A, dtype=torch.int8, device="cuda")
+        specs.append((x, p))
+        keep.append((d_x, d_y))
+        probs.append(ip.gelu_problem(d_x, d_y, n, lib_gelu(p, algo=int(i == 9))))
+    ip.gelu_i8_batch(probs, len(probs))
+    torch.cuda.synchronize()
+    for (x, p), (_, d_y) in zip(specs, keep):
+        assert np.array_equal(d_y.cpu().numpy(), ref.gelu_i8(x, p))
+
+
+def test_layers_entry_more_than_one_batch():
+    import torch
+    import paper_2511_15369_amd as ip
+    rng = np.random.default_rng(23)
+    rows, cols, layers = 70, 49, 19
+    x = np.rint(rng.standard_normal((layers, rows, cols)) * 700).astype(np.int32)
+    ps = [prepare.softmax_prepare(float(2.0 ** rng.uniform(-10, -4)), cols, l % 2) for l in range(layers)]
+    d_x = torch.from_numpy(x).cuda()
+    d_y = torch.zeros((layers, rows, cols), dtype=torch.uint8, device="cuda")
+    ip.softmax_i32_layers(d_x, rows * cols, d_y, rows * cols, rows, cols, layers, [lib_softmax(q) for q in ps])
+    torch.cuda.synchronize()
+    y = d_y.cpu().numpy()
+    for l in range(layers):
+        assert np.array_equal(y[l], ref.softmax_i32(x[l], ps[l])), l

@@ -208,6 +208,27 @@ def test_gelu_and_requant_argument_errors_without_a_gpu():
     assert lib.iptq_gelu_i8_layers(None, 0, None, 0, 0, 1, garr, None) == 0
 
 
+def test_batch_argument_errors_without_a_gpu():
+    lib = ip.load()
+    good = lib_softmax(ref.SoftmaxParams())
+    bad = lib_softmax(ref.SoftmaxParams(i0=3))
+    arr = (ip.SoftmaxProblem * 2)(ip.SoftmaxProblem(None, None, 0, None, 0, good),
+                                  ip.SoftmaxProblem(None, None, 0, None, 0, bad))
+    assert lib.iptq_softmax_i32_batch(arr, 1, 49, None) == 0          # empty problems: no-op
+    assert lib.iptq_softmax_i32_batch(arr, 2, 49, None) == -3         # second problem is invalid
+    assert lib.iptq_softmax_i32_batch(arr, -1, 49, None) == -2
+    assert lib.iptq_softmax_i32_batch(arr, 17, 49, None) == -2
+    assert lib.iptq_softmax_i32_batch(None, 2, 49, None) == -1
+    assert lib.iptq_softmax_i32_batch(None, 0, 49, None) == 0
+    arr = (ip.SoftmaxProblem * 1)(ip.SoftmaxProblem(None, None, 0, None, 5, good))
+    assert lib.iptq_softmax_i32_batch(arr, 1, 49, None) == -1         # data pointers missing
+    g = lib_gelu(prepare.gelu_prepare(2.0 ** -5, 2.0 ** -5, 0, 0, 1))
+    garr = (ip.GeluProblem * 2)(ip.GeluProblem(None, None, 0, g), ip.GeluProblem(None, None, 3, g))
+    assert lib.iptq_gelu_i8_batch(garr, 1, None) == 0
+    assert lib.iptq_gelu_i8_batch(garr, 2, None) == -1
+    assert lib.iptq_gelu_i8_batch(garr, 17, None) == -2
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     import paper_2511_15369_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)
