@@ -31,6 +31,26 @@ IPTQ_DEV int32_t gelu_eval_dev(int32_t in, const GeluDev &P)
     return requant_dev<NARROW>(w, P.post_m, P.post_s, P.post_zp, P.qmin, P.qmax);
 }
 
+// The same value by a shorter route, for the usual case GeluDev::fast (t^2 < 2^31 and
+// post_s >= 16).  q is the centred, clamped input.  The sign of q turns into a mask: the
+// addend (2 q_c or -1) is an OR with it, the final negation an XOR, and t^4 + addend is one
+// 64-bit multiply-add.
+template <bool QUARTIC>
+IPTQ_DEV int32_t gelu_eval_fast(int32_t q, const GeluDev &P)
+{
+    const int32_t aq = max(q, -q);
+    const int32_t t = min(aq, -P.q_b) + P.q_b;               // Eq. 3: clip at -b, add b
+    const uint32_t t2 = (uint32_t)(t * t);
+    const int64_t mask = (int64_t)(q >> 31);                 // all ones for q < 0
+    const uint64_t addend = (uint64_t)((2 * P.q_c) | mask);
+    const uint64_t tp = QUARTIC ? (uint64_t)t2 * (uint64_t)t2 + addend : (uint64_t)t2 + addend;
+    const int32_t v = (int32_t)((int64_t)tp >> P.k) ^ (int32_t)mask;
+    const int32_t w = q * v;                                 // Eq. 5
+    const int64_t r = (int64_t)w * (int64_t)P.post_m + ((int64_t)1 << (P.post_s - 1));
+    const int32_t y = (int32_t)(r >> P.post_s) + P.post_zp;
+    return min(max(y, P.qmin), P.qmax);
+}
+
 IPTQ_DEV int32_t gelu_eval_any(int32_t in, const GeluDev &P)
 {
     return P.post_s >= 16 ? gelu_eval_dev<true>(in, P) : gelu_eval_dev<false>(in, P);
@@ -103,6 +123,7 @@ gelu_i8_table_kernel(GeluBatch B)
 }
 
 // int8 -> int8, polynomial evaluated per element (no table).
+template <int MODE>   // 0: general evaluation, 1: short evaluation degree 2, 2: short evaluation degree 4
 __global__ void __launch_bounds__(256)
 gelu_i8_direct_kernel(const uint8_t *in, uint8_t *out, int64_t n, GeluDev P)
 {
@@ -110,25 +131,24 @@ gelu_i8_direct_kernel(const uint8_t *in, uint8_t *out, int64_t n, GeluDev P)
     const u32x4 *in4 = reinterpret_cast<const u32x4 *>(in);
     u32x4 *out4 = reinterpret_cast<u32x4 *>(out);
     const int64_t stride = (int64_t)gridDim.x * 256;
-    const bool narrow = P.post_s >= 16;
+    auto one = [&](int32_t x) -> int32_t {
+        if (MODE == 0) return gelu_eval_any(x, P);
+        const int32_t q = min(max(x - P.zp_in, -P.max_abs_q), P.max_abs_q);
+        return gelu_eval_fast<MODE == 2>(q, P);
+    };
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
         const u32x4 v = stream_load(in4 + i);
         u32x4 r;
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             const uint32_t w = v[d];
-            if (narrow)
-                r[d] = pack4(gelu_eval_dev<true>(sbyte(w, 0), P), gelu_eval_dev<true>(sbyte(w, 1), P),
-                             gelu_eval_dev<true>(sbyte(w, 2), P), gelu_eval_dev<true>(sbyte(w, 3), P));
-            else
-                r[d] = pack4(gelu_eval_dev<false>(sbyte(w, 0), P), gelu_eval_dev<false>(sbyte(w, 1), P),
-                             gelu_eval_dev<false>(sbyte(w, 2), P), gelu_eval_dev<false>(sbyte(w, 3), P));
+            r[d] = pack4(one(sbyte(w, 0)), one(sbyte(w, 1)), one(sbyte(w, 2)), one(sbyte(w, 3)));
         }
         stream_store(r, out4 + i);
     }
     if (blockIdx.x == 0) {
         const int64_t i = (n16 << 4) + threadIdx.x;
-        if (threadIdx.x < 16 && i < n) out[i] = (uint8_t)gelu_eval_any((int32_t)(int8_t)in[i], P);
+        if (threadIdx.x < 16 && i < n) out[i] = (uint8_t)one((int32_t)(int8_t)in[i]);
     }
 }
 
@@ -143,8 +163,9 @@ gelu_i8_bytes_kernel(const uint8_t *in, uint8_t *out, int64_t n, GeluDev P)
 
 // int32 -> byte streaming skeleton shared by the int32 GELU and the requantization: lane i
 // of a pass owns the 4 consecutive elements of 16-byte chunk i (a wavefront reads 1 KiB
-// contiguous per load and writes 256 B contiguous per store); four passes are in flight
-// per thread.  ALIGNED needs a 16-byte aligned input and a 4-byte aligned output.
+// contiguous per load and writes 256 B contiguous per store).  One chunk in flight per thread
+// and many resident wavefronts measured fastest on MI355X (deeper per-thread unrolling lost
+// 10 %).  ALIGNED needs a 16-byte aligned input and a 4-byte aligned output.
 template <bool ALIGNED, typename F>
 IPTQ_DEV void stream_i32_to_bytes(const int32_t *in, uint8_t *out, int64_t n, F one)
 {
@@ -154,19 +175,9 @@ IPTQ_DEV void stream_i32_to_bytes(const int32_t *in, uint8_t *out, int64_t n, F 
         const int64_t n4 = n >> 2;
         const i32x4 *in4 = reinterpret_cast<const i32x4 *>(in);
         uint32_t *out32 = reinterpret_cast<uint32_t *>(out);
-        for (int64_t base = tid; base < n4; base += 4 * stride) {
-            i32x4 v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t i = base + u * stride;
-                if (i < n4) v[u] = stream_load(in4 + i);
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t i = base + u * stride;
-                if (i < n4)
-                    stream_store(pack4(one(v[u].x), one(v[u].y), one(v[u].z), one(v[u].w)), out32 + i);
-            }
+        for (int64_t i = tid; i < n4; i += stride) {
+            const i32x4 v = stream_load(in4 + i);
+            stream_store(pack4(one(v.x), one(v.y), one(v.z), one(v.w)), out32 + i);
         }
         if (blockIdx.x == 0) {
             const int64_t i = (n4 << 2) + threadIdx.x;
@@ -178,21 +189,30 @@ IPTQ_DEV void stream_i32_to_bytes(const int32_t *in, uint8_t *out, int64_t n, F 
 }
 
 // int32 accumulators -> int8 GELU with the requantization in front.
-template <bool ALIGNED>
+// MODE 0: general evaluation; 1 / 2: short evaluation of degree 2 / 4 with no or a narrow
+// (pre_s >= 15) pre-requantization.
+template <bool ALIGNED, int MODE>
 __global__ void __launch_bounds__(256)
 gelu_i32_kernel(const int32_t *in, uint8_t *out, int64_t n, GeluDev P)
 {
-    const bool has_pre = !(P.pre_m == 1 && P.pre_s == 0);
     GeluDev Q = P;
     Q.zp_in = 0;
     auto one = [&](int32_t x) -> int32_t {
-        if (has_pre) x = pre_requant_dev(x, P.pre_m, P.pre_s);
-        // in - zp_in may leave 32 bits; clamping the 64-bit difference to +-max_abs_q first
-        // gives the same q as the definition
-        const int64_t c = (int64_t)x - (int64_t)P.zp_in;
-        const int64_t lim = (int64_t)P.max_abs_q;
-        const int32_t q = (int32_t)(c < -lim ? -lim : (c > lim ? lim : c));
-        return gelu_eval_any(q, Q);
+        if (MODE == 0) {
+            if (P.pre_mode != 0) x = pre_requant_dev(x, P.pre_m, P.pre_s);
+            // in - zp_in may leave 32 bits; clamping the 64-bit difference to +-max_abs_q first
+            // gives the same q as the definition
+            const int64_t c = (int64_t)x - (int64_t)P.zp_in;
+            const int64_t lim = (int64_t)P.max_abs_q;
+            const int32_t q = (int32_t)(c < -lim ? -lim : (c > lim ? lim : c));
+            return gelu_eval_any(q, Q);
+        }
+        if (P.pre_mode == 1)     // |x * m + round| < 2^47 and pre_s >= 15: the result fits 32 bits
+            x = (int32_t)(((int64_t)x * (int64_t)P.pre_m + ((int64_t)1 << (P.pre_s - 1))) >> P.pre_s);
+        // a saturated difference is beyond +-max_abs_q exactly when the true one is
+        int32_t q = __builtin_elementwise_sub_sat(x, P.zp_in);
+        q = min(max(q, -P.max_abs_q), P.max_abs_q);
+        return gelu_eval_fast<MODE == 2>(q, P);
     };
     stream_i32_to_bytes<ALIGNED>(in, out, n, one);
 }
@@ -213,10 +233,9 @@ requant_kernel(const int32_t *in, uint8_t *out, int64_t n, DyadicDev P)
 // Host-side dispatch.  Grid: enough workgroups to fill 256 compute units several times
 // over, capped by the amount of work.
 
-static unsigned grid_for(int64_t work_items, int per_block)
+static unsigned grid_for(int64_t work_items, int per_block, int64_t cap = 256 * 16)
 {
     int64_t g = (work_items + per_block - 1) / per_block;
-    const int64_t cap = 256 * 16;
     if (g > cap) g = cap;
     if (g < 1) g = 1;
     return (unsigned)g;
@@ -243,8 +262,13 @@ hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stre
             hipLaunchKernelGGL(gelu_i8_bytes_kernel, dim3(grid_for(g.n, 256)), dim3(256), 0, stream,
                                uin, uout, g.n, g.P);
         } else if (g.force_direct) {
-            hipLaunchKernelGGL(gelu_i8_direct_kernel, dim3(grid_for(g.n >> 4, 256)), dim3(256), 0,
-                               stream, uin, uout, g.n, g.P);
+            const dim3 grid(grid_for(g.n >> 4, 256, 256 * 64));
+            if (!g.P.fast)
+                hipLaunchKernelGGL(gelu_i8_direct_kernel<0>, grid, dim3(256), 0, stream, uin, uout, g.n, g.P);
+            else if (!g.P.quartic)
+                hipLaunchKernelGGL(gelu_i8_direct_kernel<1>, grid, dim3(256), 0, stream, uin, uout, g.n, g.P);
+            else
+                hipLaunchKernelGGL(gelu_i8_direct_kernel<2>, grid, dim3(256), 0, stream, uin, uout, g.n, g.P);
         } else {
             if (B.n_items == kGeluBatchMax) flush();
             GeluItem &it = B.item[B.n_items++];
@@ -263,12 +287,18 @@ hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const Ge
 {
     uint8_t *uout = reinterpret_cast<uint8_t *>(out);
     const bool aligned = (reinterpret_cast<uintptr_t>(in) & 15) == 0 && (reinterpret_cast<uintptr_t>(out) & 3) == 0;
-    if (aligned)
-        hipLaunchKernelGGL(gelu_i32_kernel<true>, dim3(grid_for(n >> 2, 1024)), dim3(256), 0, stream, in,
-                           uout, n, P);
-    else
-        hipLaunchKernelGGL(gelu_i32_kernel<false>, dim3(grid_for(n, 256)), dim3(256), 0, stream, in,
-                           uout, n, P);
+    const int mode = (P.fast && P.pre_mode != 2) ? (P.quartic ? 2 : 1) : 0;
+    if (aligned) {
+        const dim3 grid(grid_for(n >> 2, 256, 256 * 64)), block(256);
+        if (mode == 0) hipLaunchKernelGGL((gelu_i32_kernel<true, 0>), grid, block, 0, stream, in, uout, n, P);
+        else if (mode == 1) hipLaunchKernelGGL((gelu_i32_kernel<true, 1>), grid, block, 0, stream, in, uout, n, P);
+        else hipLaunchKernelGGL((gelu_i32_kernel<true, 2>), grid, block, 0, stream, in, uout, n, P);
+    } else {
+        const dim3 grid(grid_for(n, 256)), block(256);
+        if (mode == 0) hipLaunchKernelGGL((gelu_i32_kernel<false, 0>), grid, block, 0, stream, in, uout, n, P);
+        else if (mode == 1) hipLaunchKernelGGL((gelu_i32_kernel<false, 1>), grid, block, 0, stream, in, uout, n, P);
+        else hipLaunchKernelGGL((gelu_i32_kernel<false, 2>), grid, block, 0, stream, in, uout, n, P);
+    }
     return hipGetLastError();
 }
 
@@ -278,7 +308,7 @@ hipError_t requant_dispatch(const int32_t *in, void *out, int64_t n, const Dyadi
     uint8_t *uout = reinterpret_cast<uint8_t *>(out);
     const bool aligned = (reinterpret_cast<uintptr_t>(in) & 15) == 0 && (reinterpret_cast<uintptr_t>(out) & 3) == 0;
     if (aligned)
-        hipLaunchKernelGGL(requant_kernel<true>, dim3(grid_for(n >> 2, 1024)), dim3(256), 0, stream, in,
+        hipLaunchKernelGGL(requant_kernel<true>, dim3(grid_for(n >> 2, 256, 256 * 64)), dim3(256), 0, stream, in,
                            uout, n, P);
     else
         hipLaunchKernelGGL(requant_kernel<false>, dim3(grid_for(n, 256)), dim3(256), 0, stream, in, uout,

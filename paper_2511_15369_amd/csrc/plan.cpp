@@ -182,6 +182,8 @@ int plan_gelu(const iptq_gelu_params_t *p, int is_i8_entry, GeluDev *out)
     out->pre_m = p->pre_m; out->pre_s = p->pre_s;
     out->post_m = p->post.m; out->post_s = p->post.s; out->post_zp = p->post.zp;
     out->qmin = p->post.qmin; out->qmax = p->post.qmax;
+    out->fast = (p->post.s >= 16 && t <= 46340) ? 1 : 0;
+    out->pre_mode = (p->pre_m == 1 && p->pre_s == 0) ? 0 : (p->pre_s >= 15 ? 1 : 2);
     return IPTQ_OK;
 }
 

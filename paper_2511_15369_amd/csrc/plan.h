@@ -41,6 +41,8 @@ struct GeluDev {
     int32_t max_abs_q;
     int32_t pre_m, pre_s;
     int32_t post_m, post_s, post_zp, qmin, qmax;
+    int32_t fast;       // 1: t^2 fits 32 bits and post_s >= 16, the short evaluation applies
+    int32_t pre_mode;   // 0: no pre-requantization, 1: pre_s >= 15 (result fits 32 bits), 2: general
 };
 
 struct DyadicDev {
