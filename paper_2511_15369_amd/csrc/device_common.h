@@ -110,6 +110,15 @@ IPTQ_DEV int32_t pre_requant_dev(int32_t x, int32_t m, int32_t s)
     return (int32_t)v;
 }
 
+// clamp(v, lo, hi) for lo <= hi in one instruction (the compiler cannot prove lo <= hi for
+// run-time bounds and would emit a max and a min)
+IPTQ_DEV int32_t clamp_i32(int32_t v, int32_t lo, int32_t hi)
+{
+    int32_t r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+    return r;
+}
+
 IPTQ_DEV int32_t sat_add_i32(int32_t a, int32_t b)
 {
     return __builtin_elementwise_add_sat(a, b);

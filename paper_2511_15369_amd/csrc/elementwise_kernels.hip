@@ -41,14 +41,15 @@ IPTQ_DEV int32_t gelu_eval_fast(int32_t q, const GeluDev &P)
     const int32_t aq = max(q, -q);
     const int32_t t = min(aq, -P.q_b) + P.q_b;               // Eq. 3: clip at -b, add b
     const uint32_t t2 = (uint32_t)(t * t);
-    const int64_t mask = (int64_t)(q >> 31);                 // all ones for q < 0
-    const uint64_t addend = (uint64_t)((2 * P.q_c) | mask);
+    const uint32_t mask = (uint32_t)(q >> 31);               // all ones for q < 0
+    const uint64_t qc2 = (uint64_t)(2 * P.q_c);
+    const uint64_t addend = ((uint64_t)((uint32_t)(qc2 >> 32) | mask) << 32) | ((uint32_t)qc2 | mask);
     const uint64_t tp = QUARTIC ? (uint64_t)t2 * (uint64_t)t2 + addend : (uint64_t)t2 + addend;
     const int32_t v = (int32_t)((int64_t)tp >> P.k) ^ (int32_t)mask;
     const int32_t w = q * v;                                 // Eq. 5
     const int64_t r = (int64_t)w * (int64_t)P.post_m + ((int64_t)1 << (P.post_s - 1));
     const int32_t y = (int32_t)(r >> P.post_s) + P.post_zp;
-    return min(max(y, P.qmin), P.qmax);
+    return clamp_i32(y, P.qmin, P.qmax);
 }
 
 IPTQ_DEV int32_t gelu_eval_any(int32_t in, const GeluDev &P)
@@ -133,7 +134,7 @@ gelu_i8_direct_kernel(const uint8_t *in, uint8_t *out, int64_t n, GeluDev P)
     const int64_t stride = (int64_t)gridDim.x * 256;
     auto one = [&](int32_t x) -> int32_t {
         if (MODE == 0) return gelu_eval_any(x, P);
-        const int32_t q = min(max(x - P.zp_in, -P.max_abs_q), P.max_abs_q);
+        const int32_t q = clamp_i32(x - P.zp_in, -P.max_abs_q, P.max_abs_q);
         return gelu_eval_fast<MODE == 2>(q, P);
     };
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
@@ -210,8 +211,7 @@ gelu_i32_kernel(const int32_t *in, uint8_t *out, int64_t n, GeluDev P)
         if (P.pre_mode == 1)     // |x * m + round| < 2^47 and pre_s >= 15: the result fits 32 bits
             x = (int32_t)(((int64_t)x * (int64_t)P.pre_m + ((int64_t)1 << (P.pre_s - 1))) >> P.pre_s);
         // a saturated difference is beyond +-max_abs_q exactly when the true one is
-        int32_t q = __builtin_elementwise_sub_sat(x, P.zp_in);
-        q = min(max(q, -P.max_abs_q), P.max_abs_q);
+        const int32_t q = clamp_i32(__builtin_elementwise_sub_sat(x, P.zp_in), -P.max_abs_q, P.max_abs_q);
         return gelu_eval_fast<MODE == 2>(q, P);
     };
     stream_i32_to_bytes<ALIGNED>(in, out, n, one);

@@ -129,7 +129,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             SoftmaxItem &it = B.item[B.n_items++];
             it.scores = c.scores; it.bias = c.bias; it.out = c.out;
             it.n_slabs = n_slabs; it.first_wg = total_wgs; it.P = c.P;
-            total_wgs += (unsigned)((n_slabs + 3) / 4);
+            total_wgs += (unsigned)((n_slabs + kRowsWpb - 1) / kRowsWpb);
             done[i] = n_slabs * rpw;
         }
         flush();

@@ -32,6 +32,12 @@ enum { PM_NONE = 0, PM_CLAMP127 = 1, PM_GENERAL = 2 };
 // of a model sweep, the stages of a Swin backbone): workgroups [first_wg, next first_wg)
 // belong to item i.  The table travels in the kernel arguments.
 constexpr int kBatchMax = 16;
+// wavefronts per workgroup of the row kernel; they do not cooperate, so this only sets the
+// granularity at which the dispatcher hands out work and LDS
+#ifndef IPTQ_ROWS_WPB
+#define IPTQ_ROWS_WPB 4
+#endif
+constexpr int kRowsWpb = IPTQ_ROWS_WPB;
 struct SoftmaxItem {
     const int32_t *scores;
     const int32_t *bias;
@@ -208,7 +214,7 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
 }
 
 template <int COLS, int K, int MODE, bool BIAS, int POSTMODE>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64 * kRowsWpb)
 softmax_rows_kernel(SoftmaxBatch B)
 {
     constexpr int RPW = 64 / K;                       // rows per wavefront
@@ -220,7 +226,7 @@ softmax_rows_kernel(SoftmaxBatch B)
     constexpr int IN_CHUNKS = SLAB / 4;               // 16-byte chunks of the input slab
     constexpr bool OUT16 = SLAB % 16 == 0;            // output slab is whole 16-byte chunks
     constexpr int OUT_CHUNKS = OUT16 ? SLAB / 16 : SLAB / 4;   // else whole dwords
-    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4][SLAB * 4];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[kRowsWpb][SLAB * 4];
 
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
@@ -232,7 +238,7 @@ softmax_rows_kernel(SoftmaxBatch B)
     const int32_t *__restrict__ scores = I.scores;
     const int32_t *__restrict__ bias = I.bias;
     uint8_t *__restrict__ out = I.out;
-    const int64_t slab = (int64_t)(blockIdx.x - I.first_wg) * 4 + wv;
+    const int64_t slab = (int64_t)(blockIdx.x - I.first_wg) * kRowsWpb + wv;
     if (slab >= I.n_slabs) return;                    // no workgroup barrier below
 
     uint8_t *lds = lds_all[wv];
@@ -360,7 +366,7 @@ hipError_t launch_softmax_rows(const SoftmaxBatch &B, unsigned total_wgs, bool h
 #define IPTQ_K197 4
 #endif
 #ifndef IPTQ_K49
-#define IPTQ_K49 1
+#define IPTQ_K49 2
 #endif
 template <>
 hipError_t launch_softmax_rows<197, IPTQ_K197>(const SoftmaxBatch &, unsigned, bool, int, int, hipStream_t);
@@ -374,7 +380,7 @@ template <int COLS, int K, bool BIAS>
 static hipError_t launch_rows_b(const SoftmaxBatch &B, unsigned total_wgs, int mode, int post_mode,
                                 hipStream_t stream)
 {
-    const dim3 grid(total_wgs), block(256);
+    const dim3 grid(total_wgs), block(64 * kRowsWpb);
     if (post_mode == PM_GENERAL || mode == 0) {
         switch (post_mode) {
         case PM_NONE: IPTQ_ROWS_LAUNCH(COLS, K, 0, BIAS, PM_NONE); break;

@@ -1,5 +1,5 @@
 // Instantiations of the fixed-row-length softmax for 49 columns (Swin 7x7 windows):
-// one lane per row, 64 rows per wavefront.
+// two lanes per row, 32 rows per wavefront.
 #include "softmax_rows.h"
 
 namespace iptq {
