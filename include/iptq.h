@@ -47,6 +47,8 @@ extern "C" {
 /* algo field: which kernel family serves the call (results are identical) */
 #define IPTQ_ALGO_AUTO 0
 #define IPTQ_ALGO_GENERIC 1 /* softmax: one wavefront per row, any cols; GELU: polynomial per element */
+#define IPTQ_ALGO_FLEX 2    /* softmax only: the run-time-row-length slab kernel also where a
+                               compiled row length (197, 49) would be picked */
 
 /*
  * y = clamp(rshr_round(x * m, s) + zp, qmin, qmax)

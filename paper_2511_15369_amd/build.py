@@ -15,7 +15,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libiptq.so")
-SOURCES = ["plan.cpp", "api.hip", "softmax_kernels.hip", "softmax_rows_197.hip", "softmax_rows_49.hip",
+SOURCES = ["plan.cpp", "api.hip", "softmax_kernels.hip", "softmax_flex.hip", "softmax_rows_197.hip",
+           "softmax_rows_49.hip",
            "elementwise_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Wno-unused-parameter",

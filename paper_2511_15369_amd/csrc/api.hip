@@ -41,7 +41,7 @@ static int softmax_call(const int32_t *d_scores, const int32_t *d_bias, int64_t 
     int rc = plan_softmax(p, rows, cols, d_bias != nullptr, bias_period_rows, &out->P);
     if (rc != IPTQ_OK) return rc;
     out->scores = d_scores; out->bias = d_bias; out->out = static_cast<uint8_t *>(d_out);
-    out->rows = rows; out->out_bits = p->out_bits; out->force_generic = p->algo == IPTQ_ALGO_GENERIC;
+    out->rows = rows; out->out_bits = p->out_bits; out->algo = p->algo;
     if (rows == 0) return IPTQ_OK;
     if (!d_scores || !d_out) return IPTQ_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(d_scores) & 3) || (reinterpret_cast<uintptr_t>(d_bias) & 3))

@@ -15,7 +15,7 @@ struct SoftmaxCall {
     uint8_t *out;
     int64_t rows;
     int out_bits;
-    bool force_generic;
+    int algo;            // IPTQ_ALGO_*
     SoftmaxDev P;
 };
 // One int8 GELU problem.
@@ -28,6 +28,10 @@ struct GeluCall {
 };
 
 hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols, hipStream_t stream);
+// Run-time-row-length slab kernel on the leading rows of one call that fill whole slabs;
+// *done receives how many rows it took (0 if the shape or the pointers do not qualify).
+hipError_t softmax_flex_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
+                               hipStream_t stream);
 hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stream);
 hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,
                              hipStream_t stream);

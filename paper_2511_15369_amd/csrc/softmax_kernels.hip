@@ -5,6 +5,7 @@
 //                          the fused pre-requantization.
 #include <hip/hip_runtime.h>
 
+#include "../../include/iptq.h"
 #include "device_common.h"
 #include "kernels.h"
 #include "plan.h"
@@ -116,7 +117,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
                                                ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
                                                c.P.bias_period_rows >= rpw);
-            if (rpw == 0 || c.force_generic || has_pre || !aligned || !bias_ok) continue;
+            if (rpw == 0 || c.algo != IPTQ_ALGO_AUTO || has_pre || !aligned || !bias_ok) continue;
             const int64_t n_slabs = c.rows / rpw;
             if (n_slabs == 0) continue;
             const int pm = post_mode_of(c.P, c.out_bits);
@@ -136,6 +137,10 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
         for (int i = 0; i < cnt && err == hipSuccess; ++i) {
             const SoftmaxCall &c = calls[base + i];
             const bool has_pre = !(c.P.pre_m == 1 && c.P.pre_s == 0);
+            if (done[i] == 0 && c.algo != IPTQ_ALGO_GENERIC) {
+                err = softmax_flex_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
+                if (err != hipSuccess) break;
+            }
             err = launch_generic(c.scores, c.bias, c.out, done[i], c.rows, cols, c.bias != nullptr,
                                  has_pre, c.P, stream);
         }

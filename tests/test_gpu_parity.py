@@ -42,6 +42,9 @@ def test_softmax_configs(name, unit, batch, variant):
     want = ref.softmax_i32(scores, p, case.bias, case.bias_period_rows)
     got = gpu_softmax(scores, p, case.bias, case.bias_period_rows, algo=1)
     assert np.array_equal(got, want)
+    # and so does the run-time-row-length slab kernel
+    got = gpu_softmax(scores, p, case.bias, case.bias_period_rows, algo=2)
+    assert np.array_equal(got, want)
 
 
 @pytest.mark.parametrize("cols", [197, 49])
@@ -85,12 +88,14 @@ def test_softmax_mask_and_extreme_rows(cols):
             want = ref.softmax_i32(scores, p)
             assert np.array_equal(gpu_softmax(scores, p), want), (variant, i0, n)
             assert np.array_equal(gpu_softmax(scores, p, algo=1), want), (variant, i0, n)
+            assert np.array_equal(gpu_softmax(scores, p, algo=2), want), (variant, i0, n)
 
 
-@pytest.mark.parametrize("cols", [1, 2, 3, 4, 5, 16, 63, 64, 65, 128, 196, 198, 577, 1025, 4099])
+@pytest.mark.parametrize("cols", [1, 2, 3, 4, 5, 6, 7, 16, 50, 63, 64, 65, 128, 144, 145, 196, 198, 199,
+                                  257, 577, 785, 800, 1025, 4099])
 def test_softmax_any_row_length(cols):
     rng = np.random.default_rng(cols)
-    rows = 37
+    rows = 137 if cols < 300 else 37
     scores = np.rint(rng.standard_normal((rows, cols)) * 300).astype(np.int32)
     scores[2, : max(1, cols // 3)] = INT32_MIN
     for variant in (0, 1):
@@ -133,6 +138,7 @@ def test_softmax_pre_post_outbits_bias(cols, rows):
         for b, period in ((None, 0), (bias, 7), (big_bias, 96), (bias[:1], 1)):
             want = ref.softmax_i32(scores, p, b, period)
             assert np.array_equal(gpu_softmax(scores, p, b, period), want)
+            assert np.array_equal(gpu_softmax(scores, p, b, period, algo=2), want)
 
 
 def test_softmax_empty_and_layers_entry():

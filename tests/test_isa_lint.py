@@ -16,7 +16,7 @@ FORBIDDEN = re.compile(r"^\s+(v_[a-z0-9_]*_(f16|f32|f64|bf16)\b|v_cvt_(?!pk_[iu]
 
 
 @pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not installed")
-@pytest.mark.parametrize("src", ["softmax_kernels.hip", "softmax_rows_197.hip", "softmax_rows_49.hip",
+@pytest.mark.parametrize("src", ["softmax_kernels.hip", "softmax_flex.hip", "softmax_rows_197.hip", "softmax_rows_49.hip",
                                  "elementwise_kernels.hip"])
 def test_no_floating_point_instructions(src, tmp_path):
     out = tmp_path / (src + ".s")
