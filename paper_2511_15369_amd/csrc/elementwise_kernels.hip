@@ -73,6 +73,9 @@ IPTQ_DEV int32_t sbyte(uint32_t w, int i) { return (int32_t)(int8_t)(w >> (8 * i
 // bytes of an item are done by its first workgroup.  in and out must be 16-byte aligned;
 // they may be the same buffer.
 constexpr int kGeluBatchMax = 16;
+#ifndef IPTQ_GELU_TABLE_GRID_CAP
+#define IPTQ_GELU_TABLE_GRID_CAP (256 * 16)
+#endif
 struct GeluItem {
     const uint8_t *in;
     uint8_t *out;
@@ -274,7 +277,7 @@ hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stre
             GeluItem &it = B.item[B.n_items++];
             it.in = uin; it.out = uout; it.n = g.n; it.P = g.P;
             it.first_wg = total_wgs;
-            it.n_wgs = grid_for(g.n >> 4, 256);
+            it.n_wgs = grid_for(g.n >> 4, 256, IPTQ_GELU_TABLE_GRID_CAP);
             total_wgs += it.n_wgs;
         }
     }
