@@ -15,9 +15,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libiptq.so")
-SOURCES = ["plan.cpp", "api.hip", "softmax_kernels.hip", "softmax_flex.hip", "softmax_rows_197.hip",
-           "softmax_rows_49.hip",
-           "elementwise_kernels.hip"]
+SOURCES = ["plan.cpp", "api.hip", "softmax_kernels.hip", "softmax_flex.hip", "elementwise_kernels.hip",
+           "softmax_rows_197.hip", "softmax_rows_49.hip", "softmax_rows_198.hip", "softmax_rows_144.hip",
+           "softmax_rows_257.hip", "softmax_rows_577.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Wno-unused-parameter",
          # packed-FP32 instructions stay off: the kernels are integer-only anyway
@@ -33,7 +33,7 @@ def _compile(src: str, extra) -> str:
 
 def build(extra_flags=(), verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra_flags), SOURCES))
     tmp = LIB + ".tmp%d" % os.getpid()
     subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs)

@@ -89,7 +89,12 @@ static hipError_t launch_generic(const int32_t *scores, const int32_t *bias, uin
 // rows a slab decomposition leaves over, and calls it cannot serve, go to the generic kernel.
 hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols, hipStream_t stream)
 {
-    const int rpw = cols == 197 ? 64 / IPTQ_K197 : (cols == 49 ? 64 / IPTQ_K49 : 0);
+    int rpw = 0;                                      // rows per wavefront of the compiled row length
+    hipError_t (*launch)(const SoftmaxBatch &, unsigned, bool, int, int, hipStream_t) = nullptr;
+#define IPTQ_PICK_ROWS_SHAPE(COLS, K)                                                             \
+    if (cols == COLS) { rpw = 64 / K; launch = launch_softmax_rows<COLS, K>; }
+    IPTQ_ROWS_SHAPES(IPTQ_PICK_ROWS_SHAPE)
+#undef IPTQ_PICK_ROWS_SHAPE
     SoftmaxBatch B;
     B.n_items = 0;
     unsigned total_wgs = 0;
@@ -98,8 +103,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
     hipError_t err = hipSuccess;
     auto flush = [&]() {
         if (B.n_items == 0 || err != hipSuccess) return;
-        err = cols == 197 ? launch_softmax_rows<197, IPTQ_K197>(B, total_wgs, g_bias, g_mode, g_pm, stream)
-                          : launch_softmax_rows<49, IPTQ_K49>(B, total_wgs, g_bias, g_mode, g_pm, stream);
+        err = launch(B, total_wgs, g_bias, g_mode, g_pm, stream);
         B.n_items = 0;
         total_wgs = 0;
     };

@@ -221,7 +221,9 @@ softmax_rows_kernel(SoftmaxBatch B)
     constexpr int SLAB = RPW * COLS;                  // elements per slab
     static_assert(RPW % 4 == 0, "slab must start on a 16-byte boundary of the int32 input");
     static_assert(MODE == 0 || POSTMODE != PM_GENERAL, "packed path has no general post step");
-    constexpr int NB = (COLS + 3 + 3) / 4;            // 16-byte blocks a row can touch
+    // 16-byte blocks a row can touch: rows start at element offsets that are multiples of
+    // gcd(COLS, 4) inside a block
+    constexpr int NB = (COLS % 4 == 0) ? COLS / 4 : ((COLS % 2 == 0) ? (COLS + 2 + 3) / 4 : (COLS + 3 + 3) / 4);
     constexpr int SLOTS = (NB + K - 1) / K;           // blocks per lane
     constexpr int IN_CHUNKS = SLAB / 4;               // 16-byte chunks of the input slab
     constexpr bool OUT16 = SLAB % 16 == 0;            // output slab is whole 16-byte chunks
@@ -361,17 +363,14 @@ template <int COLS, int K>
 hipError_t launch_softmax_rows(const SoftmaxBatch &B, unsigned total_wgs, bool has_bias, int mode,
                                int post_mode, hipStream_t stream);
 
-// lanes per row of the two instantiated row lengths
-#ifndef IPTQ_K197
-#define IPTQ_K197 4
-#endif
-#ifndef IPTQ_K49
-#define IPTQ_K49 2
-#endif
-template <>
-hipError_t launch_softmax_rows<197, IPTQ_K197>(const SoftmaxBatch &, unsigned, bool, int, int, hipStream_t);
-template <>
-hipError_t launch_softmax_rows<49, IPTQ_K49>(const SoftmaxBatch &, unsigned, bool, int, int, hipStream_t);
+// The compiled row lengths with their lanes per row: ViT / DeiT at 224^2 (197; 198 with a
+// distillation token), Swin 7x7 and 12x12 windows (49, 144), ViT-L/14 (257), 384^2 / 16 (577).
+// Each is instantiated in its own softmax_rows_<cols>.hip.
+#define IPTQ_ROWS_SHAPES(X) X(197, 4) X(49, 2) X(198, 4) X(144, 4) X(257, 8) X(577, 16)
+#define IPTQ_DECLARE_ROWS_LAUNCHER(COLS, K)                                                       \
+    template <>                                                                                   \
+    hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &, unsigned, bool, int, int, hipStream_t);
+IPTQ_ROWS_SHAPES(IPTQ_DECLARE_ROWS_LAUNCHER)
 
 #define IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM)                                                 \
     hipLaunchKernelGGL((softmax_rows_kernel<COLS, K, MODE, BIAS, PM>), grid, block, 0, stream, B)

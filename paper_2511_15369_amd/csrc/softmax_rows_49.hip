@@ -1,7 +1,6 @@
-// Instantiations of the fixed-row-length softmax for 49 columns (Swin 7x7 windows):
-// two lanes per row, 32 rows per wavefront.
+// Instantiations of the fixed-row-length softmax for 49 columns (Swin 7x7 windows: 2 lanes per row, 32 rows per wavefront).
 #include "softmax_rows.h"
 
 namespace iptq {
-IPTQ_DEFINE_ROWS_LAUNCHER(49, IPTQ_K49)
+IPTQ_DEFINE_ROWS_LAUNCHER(49, 2)
 }

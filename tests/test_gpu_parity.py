@@ -141,6 +141,30 @@ def test_softmax_pre_post_outbits_bias(cols, rows):
             assert np.array_equal(gpu_softmax(scores, p, b, period, algo=2), want)
 
 
+def test_swin_shifted_window_mask_as_a_combined_table():
+    """Relative-position bias [heads*49, 49] plus a per-window additive mask [windows, 49, 49]
+    (0 or 'minus infinity'), folded into one table of period windows*heads*49 rows."""
+    rng = np.random.default_rng(31)
+    images, windows, heads, t = 3, 4, 4, 49
+    rows = images * windows * heads * t
+    scores = np.rint(rng.standard_normal((rows, t)) * 900).astype(np.int32)
+    rel = np.rint(rng.standard_normal((heads, t, t)) * 8).astype(np.int32)
+    region = rng.integers(0, 3, size=(windows, t))                       # shifted-window regions
+    mask = np.where(region[:, :, None] == region[:, None, :], 0, INT32_MIN).astype(np.int64)
+    mask[0] = 0                                                           # an unshifted window
+    table = np.clip(rel[None].astype(np.int64) + mask[:, None], INT32_MIN, 2 ** 31 - 1)
+    table = table.astype(np.int32).reshape(windows * heads * t, t)
+    period = windows * heads * t
+    for variant in (0, 1):
+        p = prepare.softmax_prepare(2.0 ** -7.5, t, variant)
+        want = ref.softmax_i32(scores, p, table, period)
+        # the masked keys get probability 0, and every row keeps some mass
+        blocked = np.tile(mask[:, None] == INT32_MIN, (images, heads, 1, 1)).reshape(rows, t)
+        assert not want[blocked].any() and want.sum(axis=1).min() > 100
+        assert np.array_equal(gpu_softmax(scores, p, table, period), want)
+        assert np.array_equal(gpu_softmax(scores, p, table, period, algo=2), want)
+
+
 def test_softmax_empty_and_layers_entry():
     import torch
     import paper_2511_15369_amd as ip

@@ -15,9 +15,11 @@ FORBIDDEN = re.compile(r"^\s+(v_[a-z0-9_]*_(f16|f32|f64|bf16)\b|v_cvt_(?!pk_[iu]
                        r"v_exp|v_log|v_pk_[a-z]+_f|v_dot[0-9]*_f|v_fma|v_mad_f|v_mac_f|v_div_)", re.M)
 
 
+SOURCES = sorted(f for f in os.listdir(CSRC) if f.endswith(".hip") and f != "api.hip")
+
+
 @pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not installed")
-@pytest.mark.parametrize("src", ["softmax_kernels.hip", "softmax_flex.hip", "softmax_rows_197.hip", "softmax_rows_49.hip",
-                                 "elementwise_kernels.hip"])
+@pytest.mark.parametrize("src", SOURCES)
 def test_no_floating_point_instructions(src, tmp_path):
     out = tmp_path / (src + ".s")
     subprocess.check_call(["hipcc", "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17",
@@ -25,7 +27,6 @@ def test_no_floating_point_instructions(src, tmp_path):
                            "-packed-fp32-ops", os.path.join(CSRC, src), "-o", str(out)],
                           stderr=subprocess.DEVNULL)
     text = out.read_text()
-    assert "v_mul_hi_u32" in text or "v_mad_u64_u32" in text      # sanity: this is device code
     assert "s_endpgm" in text
     hits = FORBIDDEN.findall(text)
     assert not hits, hits[:5]
