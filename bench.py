@@ -237,6 +237,17 @@ def main():
                               "pct_of_hbm_peak": 100.0 * alg_bytes / (bms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                               "softmax_launch_us": bsm * 1e3,
                               "softmax_gbps": SOFTMAX_BYTES_PER_EL * sm_el / (bsm * 1e-3) / 1e9}
+        # streaming ceiling of this machine for the softmax's byte mix (4 B in, 1 B out per element):
+        # the library's plain requantization kernel over every unit's score tensor
+        dy = ip.Dyadic(1, 0, 0, 0, 255)
+
+        def requant_all():
+            for u in units:
+                ip.requant(u.d_scores.view(-1), u.d_probs.view(-1), u.softmax_elements, 0, dy)
+
+        requant_all()
+        rq_ms = time_region(requant_all, max(1, args.steps // 2))
+        res["stream_ceiling_gbps"] = SOFTMAX_BYTES_PER_EL * sm_el / (rq_ms * 1e-3) / 1e9
         del units
         torch.cuda.empty_cache()
         return res
@@ -273,6 +284,8 @@ def main():
             "algorithmic_bytes_per_launch": SOFTMAX_BYTES_PER_EL * sm["elements"] // sm["launches"],
         },
         "kernels": {"softmax": sm, "gelu": main_res["gelu"]},
+        "stream_ceiling": {"what": "iptq_requant (int32 -> uint8, same 5 B/element mix) over the same tensors, "
+                                   "one launch per unit", "gbps": main_res["stream_ceiling_gbps"]},
         "batched": main_res.get("batched"),
     }
     if not args.no_extra and args.workload != "swin_b":

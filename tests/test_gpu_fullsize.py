@@ -59,3 +59,23 @@ def test_other_variant_at_full_size():
         gc = workloads.gelu_case(name, unit)
         gp = prepare.gelu_prepare(gc.s_in, gc.s_out, gc.zp_in, gc.zp_out, other)
         assert np.array_equal(u.d_y.cpu().numpy(), ref.gelu_i8(gc.x.reshape(-1), gp))
+
+
+def test_batched_launch_configuration_at_full_size():
+    """bench.py's batched form: the four Swin-B stages through one softmax and one GELU call."""
+    import torch
+    import paper_2511_15369_amd as ip
+    units = bench.build_units("swin_b")
+    probs = [ip.softmax_problem(u.d_scores, u.d_bias, u.period, u.d_probs, u.rows, u.cols, u.sp) for u in units]
+    gelus = [ip.gelu_problem(u.d_x, u.d_y, u.gelu_n, u.gp) for u in units]
+    ip.softmax_i32_batch(probs, len(units), units[0].cols)
+    ip.gelu_i8_batch(gelus, len(units))
+    torch.cuda.synchronize()
+    for i, u in enumerate(units):
+        sc = workloads.softmax_case("swin_b", i)
+        p = prepare.softmax_prepare(sc.s_delta, u.cols, sc.variant)
+        assert np.array_equal(u.d_probs.cpu().numpy(),
+                              ref.softmax_i32(sc.scores, p, sc.bias, sc.bias_period_rows)), i
+        gc = workloads.gelu_case("swin_b", i)
+        gp = prepare.gelu_prepare(gc.s_in, gc.s_out, gc.zp_in, gc.zp_out, gc.variant)
+        assert np.array_equal(u.d_y.cpu().numpy(), ref.gelu_i8(gc.x.reshape(-1), gp)), i
