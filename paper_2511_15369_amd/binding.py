@@ -112,9 +112,20 @@ def _check(rc: int, what: str):
         raise IptqError(rc, what)
 
 
+_raw_stream = None
+
+
 def _stream():
+    """The current torch stream of the current device as a raw hipStream_t."""
+    global _raw_stream
     import torch
-    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if _raw_stream is None:
+        fast = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+        if fast is not None:
+            _raw_stream = lambda: fast(torch.cuda.current_device())
+        else:
+            _raw_stream = lambda: torch.cuda.current_stream().cuda_stream
+    return ctypes.c_void_p(_raw_stream())
 
 
 def _dptr(t) -> Optional[int]:
