@@ -292,3 +292,12 @@ int64_t iptq_ref_bit_exp(int64_t delta, const orc_softmax_params *p)
 {
     return bit_exp(delta, p);
 }
+
+/* the same for an array of deltas */
+int iptq_ref_bit_exp_array(const int64_t *delta, int64_t *out, int64_t n, const orc_softmax_params *p)
+{
+    if (n < 0 || !p || (n > 0 && (!delta || !out))) return ORC_ERR_ARG;
+    if (!softmax_params_ok(p, 1)) return ORC_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) out[i] = bit_exp(delta[i] < -((int64_t)1 << 30) ? -((int64_t)1 << 30) : delta[i], p);
+    return ORC_OK;
+}

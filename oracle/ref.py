@@ -111,6 +111,8 @@ def _load():
         lib.iptq_ref_gelu_i32.argtypes = [vp, vp, ctypes.c_int64, ctypes.POINTER(_GeluParams)]
         lib.iptq_ref_bit_exp.argtypes = [ctypes.c_int64, ctypes.POINTER(_SoftmaxParams)]
         lib.iptq_ref_bit_exp.restype = ctypes.c_int64
+        lib.iptq_ref_bit_exp_array.argtypes = [vp, vp, ctypes.c_int64, ctypes.POINTER(_SoftmaxParams)]
+        lib.iptq_ref_bit_exp_array.restype = ctypes.c_int
         for f in (lib.iptq_ref_requant, lib.iptq_ref_softmax_i32, lib.iptq_ref_gelu_i8,
                   lib.iptq_ref_gelu_i32):
             f.restype = ctypes.c_int
@@ -175,3 +177,13 @@ def gelu_i32(x: np.ndarray, p: GeluParams) -> np.ndarray:
 def bit_exp(delta: int, p: SoftmaxParams) -> int:
     pc = p.c()
     return int(_load().iptq_ref_bit_exp(int(delta), ctypes.byref(pc)))
+
+
+def bit_exp_array(delta: np.ndarray, p: SoftmaxParams) -> np.ndarray:
+    """Q_exp of every stabilised score in `delta` (<= 0), with the clamp at -2^30."""
+    delta = np.ascontiguousarray(delta, dtype=np.int64)
+    out = np.empty(delta.shape, dtype=np.int64)
+    pc = p.c()
+    _check(_load().iptq_ref_bit_exp_array(_ptr(delta), _ptr(out), delta.size, ctypes.byref(pc)),
+           "bit_exp_array")
+    return out

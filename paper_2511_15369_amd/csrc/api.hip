@@ -6,6 +6,7 @@
 #include "device_common.h"
 #include "kernels.h"
 #include "plan.h"
+#include "softmax_rows.h"
 
 using namespace iptq;
 
@@ -217,4 +218,43 @@ extern "C" int iptq_debug_softmax_plan(const iptq_softmax_params_t *p, int64_t r
     out12[7] = neg_qp_of(dev.d_clamp);
     out12[8] = dev.mode16; out12[9] = dev.mg24; out12[10] = dev.t16; out12[11] = 0;
     return rc;
+}
+
+// Exponentials of an array of stabilised scores (row maximum 0) through both arithmetic
+// paths of the softmax kernels: out32 from the 32-bit lanes, out16 from the packed 16-bit
+// lanes (pairs (2i, 2i+1); 0xFFFFFFFF where the plan does not enable that path).  n even.
+__global__ void __launch_bounds__(256)
+debug_bit_exp_kernel(const int32_t *delta, uint32_t *out32, uint32_t *out16, int64_t n, SoftmaxDev P)
+{
+    const int64_t i = 2 * ((int64_t)blockIdx.x * 256 + threadIdx.x);
+    if (i + 1 >= n + 1 || i >= n) return;
+    const int32_t xa = delta[i], xb = delta[i + 1];
+    const int32_t lower = -P.d_clamp;
+    if (P.variant == 0) {
+        out32[i] = bit_exp_dev<0, true>(xa, lower, 0, P);
+        out32[i + 1] = bit_exp_dev<0, true>(xb, lower, 0, P);
+    } else {
+        out32[i] = bit_exp_dev<1, true>(xa, lower, 0, P);
+        out32[i + 1] = bit_exp_dev<1, true>(xb, lower, 0, P);
+    }
+    if (P.mode16 == 0) {
+        out16[i] = out16[i + 1] = 0xFFFFFFFFu;
+    } else {
+        const u16x2 e = P.variant == 0 ? bit_exp_pair<0, true>(xa, xb, 0, P) : bit_exp_pair<1, true>(xa, xb, 0, P);
+        out16[i] = e.x;
+        out16[i + 1] = e.y;
+    }
+}
+
+extern "C" int iptq_debug_bit_exp(const int32_t *d_delta, uint32_t *d_out32, uint32_t *d_out16,
+                                  int64_t n, const iptq_softmax_params_t *p, void *stream)
+{
+    if (!p || !d_delta || !d_out32 || !d_out16) return IPTQ_ERR_NULL;
+    if (n < 0 || (n & 1)) return IPTQ_ERR_SHAPE;
+    SoftmaxDev dev;
+    int rc = plan_softmax(p, 1, 1, 0, 0, &dev);
+    if (rc != IPTQ_OK || n == 0) return rc;
+    hipLaunchKernelGGL(debug_bit_exp_kernel, dim3((unsigned)((n / 2 + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), d_delta, d_out32, d_out16, n, dev);
+    return hip_rc(hipGetLastError());
 }
