@@ -384,3 +384,45 @@ def test_layers_entry_more_than_one_batch():
     y = d_y.cpu().numpy()
     for l in range(layers):
         assert np.array_equal(y[l], ref.softmax_i32(x[l], ps[l])), l
+
+
+def test_calls_can_be_captured_in_a_hip_graph():
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no memset,
+    no synchronisation), so a whole DeiT-Tiny block can be captured once and replayed; every
+    replay, with fresh inputs copied into the captured buffers, must match the oracle."""
+    import torch
+    import paper_2511_15369_amd as ip
+    sc = workloads.softmax_case("deit_t")
+    gc = workloads.gelu_case("deit_t")
+    rows, cols = sc.scores.shape
+    sp = prepare.softmax_prepare(sc.s_delta, cols, 1)
+    gp = prepare.gelu_prepare(gc.s_in, gc.s_out, gc.zp_in, gc.zp_out, 1)
+    d_s = torch.from_numpy(sc.scores).cuda()
+    d_p = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda")
+    d_x = torch.from_numpy(gc.x.reshape(-1)).cuda()
+    d_y = torch.zeros_like(d_x)
+    lsp, lgp = lib_softmax(sp), lib_gelu(gp)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside the capture
+        ip.softmax_i32(d_s, None, 0, d_p, rows, cols, lsp)
+        ip.gelu_i8(d_x, d_y, d_x.numel(), lgp)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ip.softmax_i32(d_s, None, 0, d_p, rows, cols, lsp)
+        ip.gelu_i8(d_x, d_y, d_x.numel(), lgp)
+    rng = np.random.default_rng(77)
+    for rep in range(4):
+        s_new = np.rint(rng.standard_normal((rows, cols)) * (300 + 900 * rep)).astype(np.int32)
+        x_new = rng.integers(-128, 128, size=d_x.numel(), dtype=np.int8)
+        d_s.copy_(torch.from_numpy(s_new))
+        d_x.copy_(torch.from_numpy(x_new))
+        d_p.zero_()
+        d_y.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(d_p.cpu().numpy(), ref.softmax_i32(s_new, sp)), rep
+        assert np.array_equal(d_y.cpu().numpy(), ref.gelu_i8(x_new, gp)), rep
