@@ -26,7 +26,7 @@ SOFTMAX_BYTES_PER_EL = 5       # int32 in, one byte out
 GELU_BYTES_PER_EL = 2          # int8 in, int8 out
 # HBM bytes per softmax launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (see profiles/), keyed by workload; None until measured.
-MEASURED_TRAFFIC = {"vit_b": 300.3e6, "swin_b": None}
+MEASURED_TRAFFIC = {"vit_b": 300.4e6, "swin_b": 197.6e6}
 
 
 class Unit:
