@@ -110,7 +110,7 @@ softmax_flex_kernel(FlexArgs A)
     const SoftmaxDev &P = A.P;
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
-    const int64_t slab = (int64_t)blockIdx.x * 4 + wv;
+    const int64_t slab = (int64_t)blockIdx.x * (blockDim.x >> 6) + wv;
     if (slab >= A.n_slabs) return;                    // no workgroup barrier below
 
     const int cols = A.cols;
@@ -224,6 +224,8 @@ softmax_flex_kernel(FlexArgs A)
 // kFlexMinSlab elements per wavefront and does not idle more than 40 % of the lanes in the
 // block loop; otherwise the allowed choice with the largest slab.  The slab must fit the LDS
 // budget.  Returns false if no choice fits.
+// LDS per wavefront may reach a whole workgroup's 64 KB (then a workgroup is one wavefront)
+constexpr int64_t kFlexMaxWaveLds = 64 * 1024;
 #ifndef IPTQ_FLEX_MIN_SLAB
 #define IPTQ_FLEX_MIN_SLAB 768
 #endif
@@ -235,7 +237,7 @@ bool flex_geometry(int32_t cols, int *log2_lanes, int *wave_lds)
     for (int l2 = 0; l2 <= max_log2; ++l2) {
         const int lanes = 1 << l2, rpw = 64 >> l2;
         const int64_t bytes = ((int64_t)rpw * cols * 5 + 15) & ~(int64_t)15;
-        if (bytes > 16 * 1024) continue;
+        if (bytes > kFlexMaxWaveLds) continue;
         if (fallback < 0) fallback = l2;              // fewest lanes that fit: the largest slab
         const int per_lane = (nb + lanes - 1) / lanes;
         const double util = (double)cols / (4.0 * per_lane * lanes);
@@ -268,8 +270,10 @@ hipError_t softmax_flex_launch(const SoftmaxCall &c, int32_t cols, int post_mode
     A.log2_lanes = log2l; A.post_mode = post_mode;
     A.has_pre = !(c.P.pre_m == 1 && c.P.pre_s == 0);
     A.wave_lds = wave_lds; A.P = c.P;
-    const dim3 grid((unsigned)((n_slabs + 3) / 4)), block(256);
-    const size_t lds = (size_t)wave_lds * 4;
+    int wpb = (int)(kFlexMaxWaveLds / wave_lds);      // wavefronts per workgroup: 1..4
+    if (wpb > 4) wpb = 4;
+    const dim3 grid((unsigned)((n_slabs + wpb - 1) / wpb)), block(64 * wpb);
+    const size_t lds = (size_t)wave_lds * wpb;
     if (c.P.mode16 != 0 && post_mode != PM_GENERAL)
         hipLaunchKernelGGL(softmax_flex_kernel<2>, grid, block, lds, stream, A);
     else
