@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak
 SOFTMAX_BYTES_PER_EL = 5       # int32 in, one byte out
 GELU_BYTES_PER_EL = 2          # int8 in, int8 out
 # HBM bytes per softmax launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script (see profiles/), keyed by workload; None until measured.
+# script, keyed by workload (per single-layer / stage-1 launch); None where not measured.
 MEASURED_TRAFFIC = {"vit_b": 300.4e6, "swin_b": 197.6e6}
 
 
@@ -166,8 +166,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary Swin-B measurement")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU only: this path has no multi-GPU form "
-              "(rows and elements are independent; see DESIGN.md)", file=sys.stderr)
+        print("bench.py measures one GPU only: softmax rows and GELU elements are independent, so "
+              "the path has no multi-GPU form to time (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
 
     import torch
