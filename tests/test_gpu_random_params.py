@@ -1,0 +1,103 @@
+"""GPU parity on random parameter sets drawn from the whole documented domain (not only the
+values the derivation helpers produce): every softmax kernel family and arithmetic mode, the
+int8 / int32 GELU with arbitrary constants, against the oracle, bit for bit."""
+import numpy as np
+import pytest
+
+from oracle import ref
+from tests.helpers import gpu_gelu_i8, gpu_gelu_i32, gpu_softmax
+
+pytestmark = pytest.mark.gpu
+I32_MIN, I32_MAX = -(2 ** 31), 2 ** 31 - 1
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_softmax_random_domain(seed):
+    rng = np.random.default_rng(1000 + seed)
+    for _ in range(40):
+        cols = int(rng.choice([49, 197, 198, 144, 257, 577, 31, 64, 100, 333]))
+        rows = int(rng.integers(1, 150))
+        i0 = int(rng.choice([16, 17, 31, 100, 181, 255, 256, 257, 1000, 3139, 3141, 4095, 65536,
+                             2 ** 20 + 3, 2 ** 24 - 1]))
+        out_bits = int(rng.integers(2, 9))
+        n_max = 0
+        while ((i0 << (n_max + 1)) < 2 ** 24) and n_max < 20:
+            n_max += 1
+        n_shift = int(rng.integers(0, n_max + 1))
+        need = (cols * (i0 << n_shift)).bit_length()
+        if need > 31:
+            n_shift = 0
+            need = (cols * i0).bit_length()
+            if need > 31:
+                continue
+        m_bits = int(rng.integers(max(out_bits - 1, need), 32))
+        if cols * (i0 << n_shift) > (1 << m_bits):
+            continue
+        signed = int(rng.integers(0, 2))
+        lo, hi = (-128, 127) if signed else (0, 255)
+        choice = rng.integers(0, 3)
+        if choice == 0:
+            post = ref.Dyadic(1, 0, 0, 0 if not signed else int(rng.integers(-128, 1)), hi)
+        elif choice == 1:
+            post = ref.Dyadic(1, 0, 0, 0, 127)
+        else:
+            post = ref.Dyadic(int(rng.integers(-32767, 32768)), int(rng.integers(0, 63)),
+                              int(rng.integers(-200, 200)), lo, hi)
+        pre = (1, 0) if rng.integers(0, 3) else (int(rng.integers(1, 32768)), int(rng.integers(0, 63)))
+        p = ref.SoftmaxParams(variant=int(rng.integers(0, 2)), i0=i0, n_shift=n_shift, m_bits=m_bits,
+                              out_bits=out_bits, pre_m=pre[0], pre_s=pre[1], post=post,
+                              out_is_signed=signed)
+        kind = rng.integers(0, 3)
+        if kind == 0:
+            x = rng.integers(I32_MIN, I32_MAX + 1, size=(rows, cols))
+        elif kind == 1:
+            x = np.rint(rng.standard_normal((rows, cols)) * 3.0 * i0)
+        else:
+            x = np.rint(rng.standard_normal((rows, cols)) * 40.0 * i0) + rng.integers(-2 ** 30, 2 ** 30)
+        x = np.clip(x, I32_MIN, I32_MAX).astype(np.int32)
+        x[rng.random((rows, cols)) < 0.05] = I32_MIN
+        bias, period = None, 0
+        if rng.integers(0, 2):
+            period = int(rng.choice([1, 3, 64, 96]))
+            bias = np.rint(rng.standard_normal((period, cols)) * 2.0 * i0).astype(np.int32)
+            bias[rng.random((period, cols)) < 0.02] = I32_MIN
+        want = ref.softmax_i32(x, p, bias, period)
+        for algo in (0, 1, 2):
+            got = gpu_softmax(x, p, bias, period, algo=algo)
+            assert np.array_equal(got, want), (algo, cols, rows, p)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_gelu_random_domain(seed):
+    rng = np.random.default_rng(2000 + seed)
+    done = 0
+    while done < 60:
+        variant = int(rng.integers(0, 2))
+        q_b = -int(rng.integers(1, 2 ** int(rng.integers(2, 15 if variant else 30))))
+        q_c = -int(rng.integers(1, 2 ** int(rng.integers(2, 60))))
+        max_abs_q = int(rng.choice([1, 127, 255, 4000, 10 ** 6]))
+        tp = q_b ** 2 if variant == 0 else q_b ** 4
+        if tp >= 2 ** 61:
+            continue
+        k = 0
+        while ((tp + 2 * -q_c) >> k) * max_abs_q >= 2 ** 31:
+            k += 1
+        if k > 62:
+            continue
+        k = min(62, k + int(rng.integers(0, 3)))
+        post = ref.Dyadic(int(rng.integers(-32767, 32768)), int(rng.integers(0, 63)),
+                          int(rng.integers(-300, 300)), -128, 127)
+        pre = (1, 0) if rng.integers(0, 2) else (int(rng.integers(1, 32768)), int(rng.integers(0, 63)))
+        p = ref.GeluParams(variant, q_b, q_c, k, int(rng.integers(-128, 129)), max_abs_q, pre[0], pre[1], post)
+        n = int(rng.choice([7, 64, 1000, 4099]))
+        x8 = rng.integers(-128, 128, size=n, dtype=np.int8)
+        x32 = rng.integers(I32_MIN, I32_MAX + 1, size=n).astype(np.int32)
+        x32[: n // 2] = np.rint(rng.standard_normal(n // 2) * max_abs_q).astype(np.int32)
+        try:
+            want8 = ref.gelu_i8(x8, p)
+        except ref.OracleError:
+            continue
+        assert np.array_equal(gpu_gelu_i8(x8, p), want8), p
+        assert np.array_equal(gpu_gelu_i8(x8, p, algo=1), want8), p
+        assert np.array_equal(gpu_gelu_i32(x32, p), ref.gelu_i32(x32, p)), p
+        done += 1
