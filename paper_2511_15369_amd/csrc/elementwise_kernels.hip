@@ -96,25 +96,18 @@ gelu_i8_table_kernel(GeluBatch B)
     for (int i = 1; i < B.n_items; ++i)
         if (blockIdx.x >= B.item[i].first_wg) it = i;
     const GeluItem &I = B.item[it];
+    __shared__ uint8_t table[256];
+    table[threadIdx.x] = (uint8_t)gelu_eval_any((int32_t)(int8_t)threadIdx.x, I.P);
+    __syncthreads();
+
     const int64_t n = I.n;
     const int64_t n16 = n >> 4;
     const u32x4 *in4 = reinterpret_cast<const u32x4 *>(I.in);
     u32x4 *out4 = reinterpret_cast<u32x4 *>(I.out);
     const uint32_t lb = blockIdx.x - I.first_wg;
     const int64_t stride = (int64_t)I.n_wgs * 256;
-    int64_t i = (int64_t)lb * 256 + threadIdx.x;
-    // the first chunk is already on its way while the table is built
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (i < n16) v = stream_load(in4 + i);
-
-    __shared__ uint8_t table[256];
-    table[threadIdx.x] = (uint8_t)gelu_eval_any((int32_t)(int8_t)threadIdx.x, I.P);
-    __syncthreads();
-
-    while (i < n16) {
-        const int64_t i_next = i + stride;
-        u32x4 v_next = {0u, 0u, 0u, 0u};
-        if (i_next < n16) v_next = stream_load(in4 + i_next);
+    for (int64_t i = (int64_t)lb * 256 + threadIdx.x; i < n16; i += stride) {
+        const u32x4 v = stream_load(in4 + i);
         u32x4 r;
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
@@ -126,8 +119,6 @@ gelu_i8_table_kernel(GeluBatch B)
             r[d] = y0 | (y1 << 8) | (y2 << 16) | (y3 << 24);
         }
         stream_store(r, out4 + i);
-        v = v_next;
-        i = i_next;
     }
     if (lb == 0) {
         const int64_t i = (n16 << 4) + threadIdx.x;
