@@ -116,8 +116,9 @@ typedef struct {
     int32_t pre_m;
     int32_t pre_s;
     iptq_dyadic_t post; /* int8 output: qmin >= -128, qmax <= 127 */
-    int32_t algo;       /* IPTQ_ALGO_AUTO: int8 input evaluates the polynomial once per input
-                           code into a 256-entry table per workgroup and gathers;
+    int32_t algo;       /* IPTQ_ALGO_AUTO: the polynomial is evaluated once per distinct centred
+                           input into a per-workgroup table (int8 input: 256 entries; int32
+                           input with max_abs_q <= 511: 2 max_abs_q + 1 entries) and gathered;
                            IPTQ_ALGO_GENERIC: polynomial per element */
 } iptq_gelu_params_t;
 

@@ -135,7 +135,7 @@ extern "C" int iptq_gelu_i32(const int32_t *d_in, int8_t *d_out, int64_t n,
     if (!d_in || !d_out) return IPTQ_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(d_in) & 3) return IPTQ_ERR_ALIGN;
     if (overlap(d_in, n * 4, d_out, n)) return IPTQ_ERR_PARAM;
-    return hip_rc(gelu_i32_dispatch(d_in, d_out, n, dev, static_cast<hipStream_t>(stream)));
+    return hip_rc(gelu_i32_dispatch(d_in, d_out, n, dev, p->algo == IPTQ_ALGO_GENERIC, static_cast<hipStream_t>(stream)));
 }
 
 extern "C" int iptq_softmax_i32_layers(const int32_t *d_scores, int64_t in_stride, void *d_out,

@@ -74,7 +74,7 @@ IPTQ_DEV int32_t sbyte(uint32_t w, int i) { return (int32_t)(int8_t)(w >> (8 * i
 // they may be the same buffer.
 constexpr int kGeluBatchMax = 16;
 #ifndef IPTQ_GELU_TABLE_GRID_CAP
-#define IPTQ_GELU_TABLE_GRID_CAP (256 * 16)
+#define IPTQ_GELU_TABLE_GRID_CAP (256 * 56)
 #endif
 struct GeluItem {
     const uint8_t *in;
@@ -97,17 +97,13 @@ gelu_i8_table_kernel(GeluBatch B)
         if (blockIdx.x >= B.item[i].first_wg) it = i;
     const GeluItem &I = B.item[it];
     __shared__ uint8_t table[256];
-    table[threadIdx.x] = (uint8_t)gelu_eval_any((int32_t)(int8_t)threadIdx.x, I.P);
-    __syncthreads();
-
     const int64_t n = I.n;
     const int64_t n16 = n >> 4;
     const u32x4 *in4 = reinterpret_cast<const u32x4 *>(I.in);
     u32x4 *out4 = reinterpret_cast<u32x4 *>(I.out);
     const uint32_t lb = blockIdx.x - I.first_wg;
     const int64_t stride = (int64_t)I.n_wgs * 256;
-    for (int64_t i = (int64_t)lb * 256 + threadIdx.x; i < n16; i += stride) {
-        const u32x4 v = stream_load(in4 + i);
+    auto gather = [&](const u32x4 v) -> u32x4 {
         u32x4 r;
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
@@ -118,11 +114,20 @@ gelu_i8_table_kernel(GeluBatch B)
             const uint32_t y3 = table[w >> 24];
             r[d] = y0 | (y1 << 8) | (y2 << 16) | (y3 << 24);
         }
-        stream_store(r, out4 + i);
-    }
+        return r;
+    };
+    int64_t i = (int64_t)lb * 256 + threadIdx.x;
+    // the first chunk's load is in flight while the table is built
+    u32x4 first = {0u, 0u, 0u, 0u};
+    if (i < n16) first = stream_load(in4 + i);
+    table[threadIdx.x] = (uint8_t)gelu_eval_any((int32_t)(int8_t)threadIdx.x, I.P);
+    __syncthreads();
+    if (i < n16) stream_store(gather(first), out4 + i);
+    i += stride;
+    for (; i < n16; i += stride) stream_store(gather(stream_load(in4 + i)), out4 + i);
     if (lb == 0) {
-        const int64_t i = (n16 << 4) + threadIdx.x;
-        if (threadIdx.x < 16 && i < n) I.out[i] = table[I.in[i]];
+        const int64_t j = (n16 << 4) + threadIdx.x;
+        if (threadIdx.x < 16 && j < n) I.out[j] = table[I.in[j]];
     }
 }
 
@@ -220,6 +225,60 @@ gelu_i32_kernel(const int32_t *in, uint8_t *out, int64_t n, GeluDev P)
     stream_i32_to_bytes<ALIGNED>(in, out, n, one);
 }
 
+// int32 accumulators -> int8 GELU through a table.  After the requantization in front the
+// centred input is clamped to [-max_abs_q, max_abs_q]; for max_abs_q <= kGelu32TableMaxQ each
+// workgroup evaluates the polynomial once for every possible q with the exact formula, and an
+// element costs one multiply-shift, a clamp and a byte gather from LDS.
+constexpr int kGelu32TableMaxQ = 511;
+#ifndef IPTQ_GELU32_TABLE_GRID_CAP
+#define IPTQ_GELU32_TABLE_GRID_CAP (256 * 64)
+#endif
+template <bool ALIGNED>
+__global__ void __launch_bounds__(256)
+gelu_i32_table_kernel(const int32_t *in, uint8_t *out, int64_t n, GeluDev P)
+{
+    __shared__ uint8_t table[2 * kGelu32TableMaxQ + 2];
+    GeluDev Q = P;
+    Q.zp_in = 0;
+    const int32_t lim = P.max_abs_q;
+    auto one = [&](int32_t x) -> int32_t {
+        if (P.pre_mode == 1)     // |x * m + round| < 2^47 and pre_s >= 15: the result fits 32 bits
+            x = (int32_t)(((int64_t)x * (int64_t)P.pre_m + ((int64_t)1 << (P.pre_s - 1))) >> P.pre_s);
+        else if (P.pre_mode == 2)
+            x = pre_requant_dev(x, P.pre_m, P.pre_s);
+        // a saturated difference is beyond +-max_abs_q exactly when the true one is
+        const int32_t q = clamp_i32(__builtin_elementwise_sub_sat(x, P.zp_in), -lim, lim);
+        return (int32_t)table[q + lim];
+    };
+    if (ALIGNED) {
+        // the first chunk's load is in flight while the table is built
+        const int64_t stride = (int64_t)gridDim.x * 256;
+        const int64_t n4 = n >> 2;
+        const i32x4 *in4 = reinterpret_cast<const i32x4 *>(in);
+        uint32_t *out32 = reinterpret_cast<uint32_t *>(out);
+        int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        i32x4 v = {0, 0, 0, 0};
+        if (i < n4) v = stream_load(in4 + i);
+        for (int32_t e = threadIdx.x; e <= 2 * lim; e += 256)
+            table[e] = (uint8_t)gelu_eval_any(e - lim, Q);
+        __syncthreads();
+        if (i < n4) stream_store(pack4(one(v.x), one(v.y), one(v.z), one(v.w)), out32 + i);
+        for (i += stride; i < n4; i += stride) {
+            v = stream_load(in4 + i);
+            stream_store(pack4(one(v.x), one(v.y), one(v.z), one(v.w)), out32 + i);
+        }
+        if (blockIdx.x == 0) {
+            const int64_t j = (n4 << 2) + threadIdx.x;
+            if (threadIdx.x < 4 && j < n) out[j] = (uint8_t)one(in[j]);
+        }
+        return;
+    }
+    for (int32_t e = threadIdx.x; e <= 2 * lim; e += 256)
+        table[e] = (uint8_t)gelu_eval_any(e - lim, Q);
+    __syncthreads();
+    stream_i32_to_bytes<ALIGNED>(in, out, n, one);
+}
+
 // int32 -> int8 / uint8 requantization.
 template <bool ALIGNED>
 __global__ void __launch_bounds__(256)
@@ -286,19 +345,24 @@ hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stre
 }
 
 hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,
-                             hipStream_t stream)
+                             bool force_direct, hipStream_t stream)
 {
     uint8_t *uout = reinterpret_cast<uint8_t *>(out);
     const bool aligned = (reinterpret_cast<uintptr_t>(in) & 15) == 0 && (reinterpret_cast<uintptr_t>(out) & 3) == 0;
     const int mode = (P.fast && P.pre_mode != 2) ? (P.quartic ? 2 : 1) : 0;
+    const bool table = !force_direct && P.max_abs_q <= kGelu32TableMaxQ;
     if (aligned) {
         const dim3 grid(grid_for(n >> 2, 256, 256 * 64)), block(256);
-        if (mode == 0) hipLaunchKernelGGL((gelu_i32_kernel<true, 0>), grid, block, 0, stream, in, uout, n, P);
+        if (table)
+            hipLaunchKernelGGL(gelu_i32_table_kernel<true>, dim3(grid_for(n >> 2, 256, IPTQ_GELU32_TABLE_GRID_CAP)),
+                               block, 0, stream, in, uout, n, P);
+        else if (mode == 0) hipLaunchKernelGGL((gelu_i32_kernel<true, 0>), grid, block, 0, stream, in, uout, n, P);
         else if (mode == 1) hipLaunchKernelGGL((gelu_i32_kernel<true, 1>), grid, block, 0, stream, in, uout, n, P);
         else hipLaunchKernelGGL((gelu_i32_kernel<true, 2>), grid, block, 0, stream, in, uout, n, P);
     } else {
         const dim3 grid(grid_for(n, 256)), block(256);
-        if (mode == 0) hipLaunchKernelGGL((gelu_i32_kernel<false, 0>), grid, block, 0, stream, in, uout, n, P);
+        if (table) hipLaunchKernelGGL(gelu_i32_table_kernel<false>, grid, block, 0, stream, in, uout, n, P);
+        else if (mode == 0) hipLaunchKernelGGL((gelu_i32_kernel<false, 0>), grid, block, 0, stream, in, uout, n, P);
         else if (mode == 1) hipLaunchKernelGGL((gelu_i32_kernel<false, 1>), grid, block, 0, stream, in, uout, n, P);
         else hipLaunchKernelGGL((gelu_i32_kernel<false, 2>), grid, block, 0, stream, in, uout, n, P);
     }

@@ -34,7 +34,7 @@ hipError_t softmax_flex_launch(const SoftmaxCall &c, int32_t cols, int post_mode
                                hipStream_t stream);
 hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stream);
 hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,
-                             hipStream_t stream);
+                             bool force_direct, hipStream_t stream);
 hipError_t requant_dispatch(const int32_t *in, void *out, int64_t n, const DyadicDev &P,
                             hipStream_t stream);
 

@@ -51,11 +51,11 @@ def gpu_gelu_i8(x: np.ndarray, p: ref.GeluParams, algo=0, inplace=False) -> np.n
     return d_out.cpu().numpy()
 
 
-def gpu_gelu_i32(x: np.ndarray, p: ref.GeluParams) -> np.ndarray:
+def gpu_gelu_i32(x: np.ndarray, p: ref.GeluParams, algo=0) -> np.ndarray:
     import torch
     d_in = torch.from_numpy(np.ascontiguousarray(x)).cuda()
     d_out = torch.full(x.shape, 0x5A, dtype=torch.int8, device="cuda")
-    ip.gelu_i32(d_in, d_out, x.size, lib_gelu(p))
+    ip.gelu_i32(d_in, d_out, x.size, lib_gelu(p, algo))
     torch.cuda.synchronize()
     return d_out.cpu().numpy()
 

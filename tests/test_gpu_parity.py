@@ -273,6 +273,38 @@ def test_gelu_i32(variant):
         assert np.array_equal(gpu_gelu_i32(x2, p2), ref.gelu_i32(x2, p2))
 
 
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("max_abs_q", [1, 127, 255, 511, 512])
+def test_gelu_i32_small_range(variant, max_abs_q):
+    """Input ranges up to 511 are served by the per-workgroup table, 512 by the per-element
+    kernel; both agree with the oracle and with the per-element kernel forced by `algo`."""
+    import torch
+    import paper_2511_15369_amd as ip
+    rng = np.random.default_rng(500 + 10 * max_abs_q + variant)
+    n = 40003
+    x = np.rint(rng.standard_normal(n + 8) * 60000).astype(np.int32)
+    x[:6] = [INT32_MIN, 2 ** 31 - 1, 0, -1, 1, 123456789]
+    x[6:6 + 2 * max_abs_q + 3] = np.arange(-max_abs_q - 1, max_abs_q + 2) * 256    # every q and one beyond
+    for pre, zp in (((1, 0), 0), ((16384, 22), -7), ((32767, 3), 100), ((1, 0), INT32_MIN), ((5, 1), 2 ** 31 - 1)):
+        p = prepare.gelu_prepare(2.0 ** -5, 2.0 ** -5, zp, -11, variant, max_abs_q=max_abs_q)
+        p.pre_m, p.pre_s = pre
+        xs = x if pre != (1, 0) else (x // 256).astype(np.int32)
+        want = ref.gelu_i32(xs, p)
+        assert np.array_equal(gpu_gelu_i32(xs, p), want), (pre, zp)
+        assert np.array_equal(gpu_gelu_i32(xs, p, algo=1), want), (pre, zp)
+    # unaligned input and output, guard bytes untouched
+    p = prepare.gelu_prepare(2.0 ** -5, 2.0 ** -5, 3, 4, variant, max_abs_q=max_abs_q)
+    p.pre_m, p.pre_s = 20000, 22
+    d_x = torch.from_numpy(x).cuda()
+    for off in (1, 2, 3):
+        d_out = torch.full((n + 8,), 0x5A, dtype=torch.int8, device="cuda")
+        ip.gelu_i32(d_x[off:], d_out[off:], n, lib_gelu(p))
+        torch.cuda.synchronize()
+        got = d_out.cpu().numpy()
+        assert np.array_equal(got[off:off + n], ref.gelu_i32(x[off:off + n], p))
+        assert (got[:off] == 0x5A).all() and (got[off + n:] == 0x5A).all()
+
+
 def test_gelu_layers_entry():
     import torch
     import paper_2511_15369_amd as ip
