@@ -17,7 +17,8 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libiptq.so")
 SOURCES = ["plan.cpp", "api.hip", "softmax_kernels.hip", "softmax_flex.hip", "elementwise_kernels.hip",
            "softmax_rows_197.hip", "softmax_rows_49.hip", "softmax_rows_198.hip", "softmax_rows_144.hip",
-           "softmax_rows_257.hip", "softmax_rows_577.hip"]
+           "softmax_rows_257.hip", "softmax_rows_577.hip", "softmax_rows_197_k8.hip",
+           "softmax_rows_198_k8.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Wno-unused-parameter",
          # packed-FP32 instructions stay off: the kernels are integer-only anyway

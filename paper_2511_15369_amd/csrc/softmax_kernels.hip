@@ -94,6 +94,11 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
 #define IPTQ_PICK_ROWS_SHAPE(COLS, K)                                                             \
     if (cols == COLS) { rpw = 64 / K; launch = launch_softmax_rows<COLS, K>; }
     IPTQ_ROWS_SHAPES(IPTQ_PICK_ROWS_SHAPE)
+    int64_t total_rows = 0;
+    for (int i = 0; i < n_calls; ++i) total_rows += calls[i].rows;
+    if (total_rows * cols <= kRowsAltMaxElements) {   // a short launch: more lanes per row
+        IPTQ_ROWS_SHAPES_ALT(IPTQ_PICK_ROWS_SHAPE)
+    }
 #undef IPTQ_PICK_ROWS_SHAPE
     SoftmaxBatch B;
     B.n_items = 0;
@@ -122,7 +127,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
                                                ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
                                                c.P.bias_period_rows >= rpw);
             if (rpw == 0 || c.algo != IPTQ_ALGO_AUTO || has_pre || !aligned || !bias_ok) continue;
-            const int64_t n_slabs = c.rows / rpw;
+            const int64_t n_slabs = (c.rows + rpw - 1) / rpw;    // a partial last slab is served too
             if (n_slabs == 0) continue;
             const int pm = post_mode_of(c.P, c.out_bits);
             const int mode = pm == PM_GENERAL ? 0 : c.P.mode16;
@@ -134,8 +139,9 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             SoftmaxItem &it = B.item[B.n_items++];
             it.scores = c.scores; it.bias = c.bias; it.out = c.out;
             it.n_slabs = n_slabs; it.first_wg = total_wgs; it.P = c.P;
+            it.tail_rows = (int32_t)(c.rows % rpw);
             total_wgs += (unsigned)((n_slabs + kRowsWpb - 1) / kRowsWpb);
-            done[i] = n_slabs * rpw;
+            done[i] = c.rows;
         }
         flush();
         for (int i = 0; i < cnt && err == hipSuccess; ++i) {

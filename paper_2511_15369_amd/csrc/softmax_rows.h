@@ -18,6 +18,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "device_common.h"
 #include "plan.h"
 
@@ -42,8 +44,9 @@ struct SoftmaxItem {
     const int32_t *scores;
     const int32_t *bias;
     uint8_t *out;
-    int64_t n_slabs;
+    int64_t n_slabs;      // the last one may be partial
     uint32_t first_wg;
+    int32_t tail_rows;    // rows of the last slab if it is partial, else 0
     SoftmaxDev P;
 };
 struct SoftmaxBatch {
@@ -251,8 +254,13 @@ softmax_rows_kernel(SoftmaxBatch B)
     const int b_r = e_r >> 2;                         // its 16-byte block
     const int phi = e_r & 3;                          // and its offset inside that block
 
-    // ---- flat copy of the slab into LDS, bias added on the way
-    {
+    // ---- flat copy of the slab into LDS, bias added on the way.  A partial last slab (the
+    // tensor's row count is not a multiple of RPW) reads nothing beyond its last valid
+    // element and zero-fills the rest; its surplus rows are computed and never stored.
+    const bool partial = I.tail_rows != 0 && slab == I.n_slabs - 1;
+    const int valid_el = (partial ? I.tail_rows : RPW) * COLS;
+    auto copy_in = [&](auto tag) {
+        constexpr bool PARTIAL = decltype(tag)::value;
         i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
         uint32_t boff = 0;
         if (BIAS) boff = row_mod_period((uint32_t)(slab * RPW), P) * (uint32_t)COLS;
@@ -261,7 +269,16 @@ softmax_rows_kernel(SoftmaxBatch B)
         for (int i = 0; i < (IN_CHUNKS + 63) / 64; ++i) {
             const int idx = i * 64 + lane;
             if ((i + 1) * 64 <= IN_CHUNKS || idx < IN_CHUNKS) {
-                i32x4 v = stream_load(src + idx);
+                i32x4 v;
+                if (!PARTIAL || 4 * idx + 3 < valid_el) {
+                    v = stream_load(src + idx);
+                } else {
+                    const int32_t *s = scores + slab * SLAB + 4 * idx;
+                    v = (i32x4){0, 0, 0, 0};
+                    if (4 * idx < valid_el) v.x = s[0];
+                    if (4 * idx + 1 < valid_el) v.y = s[1];
+                    if (4 * idx + 2 < valid_el) v.z = s[2];
+                }
                 if (BIAS) {
                     uint32_t o = boff + 4u * (uint32_t)idx;
                     if (o >= pe) o -= pe;
@@ -275,7 +292,9 @@ softmax_rows_kernel(SoftmaxBatch B)
             }
         }
         wave_lds_fence();
-    }
+    };
+    if (partial) copy_in(std::true_type{});
+    else copy_in(std::false_type{});
 
     // ---- this lane's blocks; elements outside the row become "minus infinity"
     int32_t x[SLOTS][4];
@@ -338,23 +357,29 @@ softmax_rows_kernel(SoftmaxBatch B)
     }
     wave_lds_fence();
 
-    // ---- flat, fully coalesced store
-    if (OUT16) {
-        u32x4 *dst = reinterpret_cast<u32x4 *>(out + slab * SLAB);
-        const u32x4 *lds4o = reinterpret_cast<const u32x4 *>(lds);
+    // ---- flat, fully coalesced store (byte stores at the end of a partial slab)
+    auto copy_out = [&](auto tag) {
+        constexpr bool PARTIAL = decltype(tag)::value;
+        constexpr int CB = OUT16 ? 16 : 4;            // bytes per store
+        uint8_t *dst8 = out + slab * SLAB;
 #pragma unroll
         for (int i = 0; i < (OUT_CHUNKS + 63) / 64; ++i) {
             const int idx = i * 64 + lane;
-            if ((i + 1) * 64 <= OUT_CHUNKS || idx < OUT_CHUNKS) stream_store(lds4o[idx], dst + idx);
+            if ((i + 1) * 64 <= OUT_CHUNKS || idx < OUT_CHUNKS) {
+                if (!PARTIAL || CB * idx + CB - 1 < valid_el) {
+                    if (OUT16)
+                        stream_store(reinterpret_cast<const u32x4 *>(lds)[idx], reinterpret_cast<u32x4 *>(dst8) + idx);
+                    else
+                        stream_store(lds32[idx], reinterpret_cast<uint32_t *>(dst8) + idx);
+                } else {
+#pragma unroll 1
+                    for (int b = CB * idx; b < valid_el && b < CB * idx + CB; ++b) dst8[b] = lds[b];
+                }
+            }
         }
-    } else {
-        uint32_t *dst = reinterpret_cast<uint32_t *>(out + slab * SLAB);
-#pragma unroll
-        for (int i = 0; i < (OUT_CHUNKS + 63) / 64; ++i) {
-            const int idx = i * 64 + lane;
-            if ((i + 1) * 64 <= OUT_CHUNKS || idx < OUT_CHUNKS) stream_store(lds32[idx], dst + idx);
-        }
-    }
+    };
+    if (partial) copy_out(std::true_type{});
+    else copy_out(std::false_type{});
 }
 
 // Launch helper, defined once per row length in softmax_rows_<cols>.hip so that the
@@ -367,10 +392,17 @@ hipError_t launch_softmax_rows(const SoftmaxBatch &B, unsigned total_wgs, bool h
 // distillation token), Swin 7x7 and 12x12 windows (49, 144), ViT-L/14 (257), 384^2 / 16 (577).
 // Each is instantiated in its own softmax_rows_<cols>.hip.
 #define IPTQ_ROWS_SHAPES(X) X(197, 4) X(49, 2) X(198, 4) X(144, 4) X(257, 8) X(577, 16)
+// More lanes per row shorten a wavefront's arithmetic chain (less exposed time at the start
+// and the end of a launch) and cost some idle lanes in steady state: measured on MI355X they
+// win for launches up to about 1.5 ViT-B layers and lose beyond, so launches of at most
+// kRowsAltMaxElements elements use these instead (softmax_rows_<cols>_k<K>.hip).
+#define IPTQ_ROWS_SHAPES_ALT(X) X(197, 8) X(198, 8)
+constexpr int64_t kRowsAltMaxElements = 90 * 1000 * 1000;
 #define IPTQ_DECLARE_ROWS_LAUNCHER(COLS, K)                                                       \
     template <>                                                                                   \
     hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &, unsigned, bool, int, int, hipStream_t);
 IPTQ_ROWS_SHAPES(IPTQ_DECLARE_ROWS_LAUNCHER)
+IPTQ_ROWS_SHAPES_ALT(IPTQ_DECLARE_ROWS_LAUNCHER)
 
 #define IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM)                                                 \
     hipLaunchKernelGGL((softmax_rows_kernel<COLS, K, MODE, BIAS, PM>), grid, block, 0, stream, B)

@@ -79,3 +79,27 @@ def test_batched_launch_configuration_at_full_size():
         gc = workloads.gelu_case("swin_b", i)
         gp = prepare.gelu_prepare(gc.s_in, gc.s_out, gc.zp_in, gc.zp_out, gc.variant)
         assert np.array_equal(u.d_y.cpu().numpy(), ref.gelu_i8(gc.x.reshape(-1), gp)), i
+
+
+def test_batched_vit_b_layers_at_full_size():
+    """Two ViT-B layers and a 21-row problem in one call: a launch long enough for the
+    steady-state lane layout (the single-layer calls above use the short-launch one), with
+    a partial last slab."""
+    import torch
+    import paper_2511_15369_amd as ip
+    units = [bench.Unit("vit_b", 0), bench.Unit("vit_b", 11)]
+    small_rows = 21
+    d_small = torch.full((small_rows * units[0].cols + 32,), 0x5A, dtype=torch.uint8, device="cuda")
+    probs = [ip.softmax_problem(u.d_scores, None, 0, u.d_probs, u.rows, u.cols, u.sp) for u in units]
+    probs.append(ip.softmax_problem(units[0].d_scores, None, 0, d_small, small_rows, units[0].cols, units[1].sp))
+    ip.softmax_i32_batch(probs, len(probs), units[0].cols)
+    torch.cuda.synchronize()
+    cases = [workloads.softmax_case("vit_b", 0), workloads.softmax_case("vit_b", 11)]
+    for u, sc in zip(units, cases):
+        p = prepare.softmax_prepare(sc.s_delta, u.cols, sc.variant)
+        assert np.array_equal(u.d_probs.cpu().numpy(), ref.softmax_i32(sc.scores, p))
+    p = prepare.softmax_prepare(cases[1].s_delta, units[0].cols, cases[1].variant)
+    got = d_small.cpu().numpy()
+    n = small_rows * units[0].cols
+    assert np.array_equal(got[:n].reshape(small_rows, -1), ref.softmax_i32(cases[0].scores[:small_rows], p))
+    assert (got[n:] == 0x5A).all()

@@ -104,6 +104,35 @@ def test_softmax_any_row_length(cols):
         assert np.array_equal(gpu_softmax(scores, p), want)
 
 
+@pytest.mark.parametrize("cols", [197, 49, 198, 144, 257, 577])
+def test_softmax_partial_last_slab(cols):
+    """Row counts that leave a partial slab for the compiled row lengths: every row is right
+    and nothing is written past the last one."""
+    import torch
+    import paper_2511_15369_amd as ip
+    rng = np.random.default_rng(7000 + cols)
+    max_rows = 75
+    scores = np.rint(rng.standard_normal((max_rows, cols)) * 700).astype(np.int32)
+    scores[::5, 1] = INT32_MIN
+    bias = np.rint(rng.standard_normal((64, cols)) * 30).astype(np.int32)
+    d_scores = torch.from_numpy(scores).cuda()
+    d_bias = torch.from_numpy(bias).cuda()
+    cases = [(prepare.softmax_prepare(2.0 ** -7.2, cols, 1), False),
+             (prepare.softmax_prepare(2.0 ** -6.1, cols, 0, out_is_signed=1), True),
+             (ref.SoftmaxParams(variant=1, i0=300, n_shift=6, post=ref.Dyadic(3, 1, 10, 0, 255)), True)]
+    for rows in (1, 2, 3, 5, 7, 8, 9, 15, 16, 17, 31, 33, 63, 65, 75):
+        for p, with_bias in cases:
+            dt = torch.int8 if p.out_is_signed else torch.uint8
+            d_out = torch.full((rows * cols + 64,), 0x5A, dtype=dt, device="cuda")
+            ip.softmax_i32(d_scores, d_bias if with_bias else None, 64 if with_bias else 0, d_out, rows,
+                           cols, lib_softmax(p))
+            torch.cuda.synchronize()
+            got = d_out.cpu().numpy()
+            want = ref.softmax_i32(scores[:rows], p, bias if with_bias else None, 64 if with_bias else 0)
+            assert np.array_equal(got[:rows * cols].reshape(rows, cols), want), (rows, with_bias)
+            assert (got[rows * cols:] == 0x5A).all(), (rows, with_bias)
+
+
 def test_softmax_max_cols():
     cols = 65536
     rng = np.random.default_rng(3)
