@@ -22,7 +22,8 @@ struct FlexArgs {
     const int32_t *scores;
     const int32_t *bias;
     uint8_t *out;
-    int64_t n_slabs;
+    int64_t n_slabs;      // the last one may be partial
+    int32_t tail_rows;    // rows of the last slab if it is partial, else 0
     int32_t cols;
     int32_t log2_lanes;   // lanes per row = 1 << log2_lanes
     int32_t post_mode;    // PM_*
@@ -120,7 +121,12 @@ softmax_flex_kernel(FlexArgs A)
     const int slab_el = rpw * cols;                   // multiple of 4 (host)
     uint8_t *lds = flex_lds + wv * A.wave_lds;
     uint8_t *lds_out = lds + slab_el * 4;             // byte assembly area, 16-byte aligned
-    const i32x4 *src = reinterpret_cast<const i32x4 *>(A.scores + slab * slab_el);
+    const int32_t *src1 = A.scores + slab * slab_el;
+    const i32x4 *src = reinterpret_cast<const i32x4 *>(src1);
+    // a partial last slab reads and writes nothing beyond its last valid element; its
+    // surplus rows are zero-filled, computed and never stored
+    const bool partial = A.tail_rows != 0 && slab == A.n_slabs - 1;
+    const int valid_el = (partial ? A.tail_rows : rpw) * cols;
 
     // ---- flat copy into LDS; bias and pre-requantization on the way
     {
@@ -130,7 +136,15 @@ softmax_flex_kernel(FlexArgs A)
         if (has_bias) boff = row_mod_period((uint32_t)(slab * rpw), P) * (uint32_t)cols;
         const uint32_t pe = (uint32_t)P.bias_period_rows * (uint32_t)cols;
         for (int idx = lane; idx < (slab_el >> 2); idx += 64) {
-            i32x4 v = stream_load(src + idx);
+            i32x4 v;
+            if (4 * idx + 3 < valid_el) {
+                v = stream_load(src + idx);
+            } else {
+                v = (i32x4){0, 0, 0, 0};
+                if (4 * idx < valid_el) v.x = src1[4 * idx];
+                if (4 * idx + 1 < valid_el) v.y = src1[4 * idx + 1];
+                if (4 * idx + 2 < valid_el) v.z = src1[4 * idx + 2];
+            }
             if (has_bias) {
                 uint32_t o = boff + 4u * (uint32_t)idx;
                 if (o >= pe) o -= pe;
@@ -209,11 +223,23 @@ softmax_flex_kernel(FlexArgs A)
     uint8_t *dst = A.out + slab * slab_el;
     if ((slab_el & 15) == 0) {
         const u32x4 *o4 = reinterpret_cast<const u32x4 *>(lds_out);
-        for (int idx = lane; idx < (slab_el >> 4); idx += 64)
-            stream_store(o4[idx], reinterpret_cast<u32x4 *>(dst) + idx);
+        for (int idx = lane; idx < (slab_el >> 4); idx += 64) {
+            if (16 * idx + 15 < valid_el) {
+                stream_store(o4[idx], reinterpret_cast<u32x4 *>(dst) + idx);
+            } else {
+#pragma unroll 1
+                for (int b = 16 * idx; b < valid_el && b < 16 * idx + 16; ++b) dst[b] = lds_out[b];
+            }
+        }
     } else {
-        for (int idx = lane; idx < (slab_el >> 2); idx += 64)
-            stream_store(out32[idx], reinterpret_cast<uint32_t *>(dst) + idx);
+        for (int idx = lane; idx < (slab_el >> 2); idx += 64) {
+            if (4 * idx + 3 < valid_el) {
+                stream_store(out32[idx], reinterpret_cast<uint32_t *>(dst) + idx);
+            } else {
+#pragma unroll 1
+                for (int b = 4 * idx; b < valid_el && b < 4 * idx + 4; ++b) dst[b] = lds_out[b];
+            }
+        }
     }
 }
 
@@ -250,7 +276,8 @@ bool flex_geometry(int32_t cols, int *log2_lanes, int *wave_lds)
     return true;
 }
 
-// Rows [0, n_slabs * rpw) of one call; returns the number of rows served through *done.
+// Every row of one call (a partial last slab included) if the call qualifies; returns the
+// number of rows served through *done.
 hipError_t softmax_flex_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
                                hipStream_t stream)
 {
@@ -263,10 +290,11 @@ hipError_t softmax_flex_launch(const SoftmaxCall &c, int32_t cols, int post_mode
     const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
                                        ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
                                        c.P.bias_period_rows >= rpw);
-    const int64_t n_slabs = c.rows / rpw;
+    const int64_t n_slabs = (c.rows + rpw - 1) / rpw;
     if (!aligned || !bias_ok || n_slabs == 0) return hipSuccess;
     FlexArgs A;
     A.scores = c.scores; A.bias = c.bias; A.out = c.out; A.n_slabs = n_slabs; A.cols = cols;
+    A.tail_rows = (int32_t)(c.rows % rpw);
     A.log2_lanes = log2l; A.post_mode = post_mode;
     A.has_pre = !(c.P.pre_m == 1 && c.P.pre_s == 0);
     A.wave_lds = wave_lds; A.P = c.P;
@@ -278,7 +306,7 @@ hipError_t softmax_flex_launch(const SoftmaxCall &c, int32_t cols, int post_mode
         hipLaunchKernelGGL(softmax_flex_kernel<2>, grid, block, lds, stream, A);
     else
         hipLaunchKernelGGL(softmax_flex_kernel<0>, grid, block, lds, stream, A);
-    *done = n_slabs * rpw;
+    *done = c.rows;
     return hipGetLastError();
 }
 

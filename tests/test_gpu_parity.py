@@ -104,10 +104,10 @@ def test_softmax_any_row_length(cols):
         assert np.array_equal(gpu_softmax(scores, p), want)
 
 
-@pytest.mark.parametrize("cols", [197, 49, 198, 144, 257, 577])
+@pytest.mark.parametrize("cols", [197, 49, 198, 144, 257, 577, 50, 64, 145, 800, 1025])
 def test_softmax_partial_last_slab(cols):
-    """Row counts that leave a partial slab for the compiled row lengths: every row is right
-    and nothing is written past the last one."""
+    """Row counts that leave a partial slab (compiled and run-time row lengths): every row is
+    right and nothing is written past the last one."""
     import torch
     import paper_2511_15369_amd as ip
     rng = np.random.default_rng(7000 + cols)
