@@ -120,6 +120,18 @@ int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int
     out->m_bits = p->m_bits;
     out->p_shift = p->m_bits - (p->out_bits - 1);
     out->pre_m = p->pre_m; out->pre_s = p->pre_s;
+    if (p->pre_m == 1 && p->pre_s == 0) {
+        out->pre_mode = 0;
+    } else if (p->pre_s >= 16) {
+        // (x m + 2^(s-1)) >> s == (x m 2^(32-s) + 2^31) >> 32 for s <= 32, and
+        // ((x m + 2^(s-1)) >> 32) >> (s - 32) beyond; |x m| < 2^46, so the result fits 32 bits
+        out->pre_mode = 1;
+        out->pre_mul = p->pre_s <= 32 ? p->pre_m << (32 - p->pre_s) : p->pre_m;
+        out->pre_rnd = p->pre_s <= 32 ? ((int64_t)1 << 31) : ((int64_t)1 << (p->pre_s - 1));
+        out->pre_sh2 = p->pre_s <= 32 ? 0 : p->pre_s - 32;
+    } else {
+        out->pre_mode = 2;
+    }
     out->post_m = p->post.m; out->post_s = p->post.s; out->post_zp = p->post.zp;
     out->qmin = p->post.qmin; out->qmax = p->post.qmax;
     out->variant = p->variant;

@@ -23,6 +23,12 @@ struct SoftmaxDev {
     int32_t m_bits;     // M
     int32_t p_shift;    // M - (b - 1)
     int32_t pre_m, pre_s;
+    // pre-requantization without a 64-bit shift (pre_mode 1, pre_s >= 16): the result is
+    // ((x * pre_mul + pre_rnd) >> 32) >> pre_sh2.  pre_mode 0: none, 2: general form only.
+    int32_t pre_mode;
+    int32_t pre_mul;
+    int32_t pre_sh2;
+    int64_t pre_rnd;
     int32_t post_m, post_s, post_zp, qmin, qmax;
     int32_t variant;
     // bias addressing: row index modulo the period by multiply-high

@@ -119,14 +119,13 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             const SoftmaxCall &c = calls[base + i];
             done[i] = 0;
             const bool has_bias = c.bias != nullptr;
-            const bool has_pre = !(c.P.pre_m == 1 && c.P.pre_s == 0);
             const bool aligned =
                 ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.out)) & 15) == 0;
             // the fused bias needs 16-byte aligned bias blocks and at most one wrap per slab
             const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
                                                ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
                                                c.P.bias_period_rows >= rpw);
-            if (rpw == 0 || c.algo != IPTQ_ALGO_AUTO || has_pre || !aligned || !bias_ok) continue;
+            if (rpw == 0 || c.algo != IPTQ_ALGO_AUTO || c.P.pre_mode == 2 || !aligned || !bias_ok) continue;
             const int64_t n_slabs = (c.rows + rpw - 1) / rpw;    // a partial last slab is served too
             if (n_slabs == 0) continue;
             const int pm = post_mode_of(c.P, c.out_bits);

@@ -54,6 +54,14 @@ struct SoftmaxBatch {
     SoftmaxItem item[kBatchMax];
 };
 
+// rshr_round(x * pre_m, pre_s) for pre_s >= 16 (SoftmaxDev::pre_mode 1): one 64-bit
+// multiply-add and a 32-bit shift of its high half.
+IPTQ_DEV int32_t pre_requant_narrow(int32_t x, int32_t pre_mul, int64_t pre_rnd, int32_t pre_sh2)
+{
+    const int64_t t = (int64_t)x * (int64_t)pre_mul + pre_rnd;
+    return (int32_t)(t >> 32) >> pre_sh2;
+}
+
 // One exponential in 32-bit lanes (Eq. 7-10 / 13-14).  x is the (biased) score, `lower`
 // is max(row) - D saturated, mx the row maximum.  Elements at or below `lower` get the
 // same all-zero result as their true value, which keeps every intermediate in 32 bits.
@@ -315,6 +323,21 @@ softmax_rows_kernel(SoftmaxBatch B)
         }
     }
     wave_lds_fence();                                 // the slab area is reused for the output
+
+    // ---- fused requantization of the scores (after the bias, before the maximum).  Done on
+    // the registers, not in the copy loop, so that every load of the slab stays in flight;
+    // computed for every element and selected, so that it compiles without branches.
+    if (P.pre_mode == 1) {
+        const int32_t pre_mul = P.pre_mul, pre_sh2 = P.pre_sh2;
+        const int64_t pre_rnd = P.pre_rnd;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int32_t r = pre_requant_narrow(x[s][e], pre_mul, pre_rnd, pre_sh2);
+                x[s][e] = x[s][e] == kI32Min ? kI32Min : r;
+            }
+    }
 
     // ---- Eq. 6: row maximum
     int32_t mx = kI32Min;

@@ -133,6 +133,29 @@ def test_softmax_partial_last_slab(cols):
             assert (got[rows * cols:] == 0x5A).all(), (rows, with_bias)
 
 
+@pytest.mark.parametrize("cols", [197, 49, 144])
+def test_softmax_fused_pre_requant_shifts(cols):
+    """The requantization in front of the softmax at every shift class: below 16 (general
+    form), 16..32 and above 32 (folded into one multiply-add in the slab kernel)."""
+    rng = np.random.default_rng(900 + cols)
+    rows = 70
+    wide = rng.integers(INT32_MIN, 2 ** 31, size=(rows, cols)).astype(np.int32)
+    wide[3, :5] = [INT32_MIN, 2 ** 31 - 1, INT32_MIN + 1, 0, -1]
+    bias = np.rint(rng.standard_normal((64, cols)) * 1e6).astype(np.int32)
+    for pre_s in (1, 15, 16, 17, 24, 31, 32, 33, 40, 45, 62):
+        for pre_m in (1, 2, 20000, 32767):
+            # scale the scores so that the requantized values span a few hundred codes
+            want_span = 300.0
+            scale = min(1.0, want_span * 2.0 ** pre_s / pre_m / 2.0 ** 31)
+            scores = np.where(wide == INT32_MIN, INT32_MIN, np.rint(wide * scale)).astype(np.int32)
+            for variant, signed in ((0, 0), (1, 1)):
+                p = prepare.softmax_prepare(2.0 ** -5.3, cols, variant, out_is_signed=signed)
+                p.pre_m, p.pre_s = pre_m, pre_s
+                want = ref.softmax_i32(scores, p, bias, 64)
+                assert np.array_equal(gpu_softmax(scores, p, bias, 64), want), (pre_s, pre_m, variant)
+                assert np.array_equal(gpu_softmax(scores, p), ref.softmax_i32(scores, p)), (pre_s, pre_m)
+
+
 def test_softmax_max_cols():
     cols = 65536
     rng = np.random.default_rng(3)

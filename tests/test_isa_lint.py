@@ -30,3 +30,7 @@ def test_no_floating_point_instructions(src, tmp_path):
     assert "s_endpgm" in text
     hits = FORBIDDEN.findall(text)
     assert not hits, hits[:5]
+    # no kernel may fall back to per-lane scratch memory (register spills, or a by-value
+    # argument struct the compiler had to copy to private memory to index it)
+    scratch = re.findall(r"\.amdhsa_private_segment_fixed_size (\d+)", text)
+    assert scratch and all(int(b) == 0 for b in scratch), scratch
