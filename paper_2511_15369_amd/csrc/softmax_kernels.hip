@@ -129,7 +129,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             const int64_t n_slabs = (c.rows + rpw - 1) / rpw;    // a partial last slab is served too
             if (n_slabs == 0) continue;
             const int pm = post_mode_of(c.P, c.out_bits);
-            const int mode = pm == PM_GENERAL ? 0 : c.P.mode16;
+            const int mode = c.P.mode16;
             const bool compatible = B.n_items == 0 || (has_bias == g_bias && pm == g_pm &&
                                                        (mode == 0) == (g_mode == 0));
             if (!compatible || B.n_items == kBatchMax) flush();

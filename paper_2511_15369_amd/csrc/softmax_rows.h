@@ -114,6 +114,17 @@ IPTQ_DEV uint32_t pack_top_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
 // per-byte min(v, 127) for bytes that are at most 128
 IPTQ_DEV uint32_t clamp127_bytes(uint32_t w) { return w - ((w >> 7) & 0x01010101u); }
 
+// The general post step through a table: a probability has at most 2^(b-1) + 1 <= 129
+// values, so a wavefront evaluates the dyadic requantization once per value into LDS
+// (kPostLutBytes per wavefront) and every output byte is one gather.
+constexpr int kPostLutBytes = 144;
+IPTQ_DEV uint32_t post_lut_gather(const uint8_t *lut, uint32_t w)
+{
+    const uint32_t y0 = lut[w & 0xffu], y1 = lut[(w >> 8) & 0xffu];
+    const uint32_t y2 = lut[(w >> 16) & 0xffu], y3 = lut[w >> 24];
+    return y0 | (y1 << 8) | (y2 << 16) | (y3 << 24);
+}
+
 // Eq. 15 for one block of four exponentials in 32-bit lanes -> four output bytes
 template <int POSTMODE>
 IPTQ_DEV uint32_t normalise4(uint32_t e0, uint32_t e1, uint32_t e2, uint32_t e3, uint32_t f,
@@ -168,7 +179,7 @@ IPTQ_DEV u16x2 bit_exp_pair(int32_t xa, int32_t xb, int32_t mx, const SoftmaxDev
 // sum, reciprocal, probabilities -> four output bytes per block in w[].
 template <int K, int SLOTS, int MODE, int VARIANT, int POSTMODE>
 IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], int32_t mx,
-                                int32_t lower, bool any_low, const SoftmaxDev &P)
+                                int32_t lower, bool any_low, const uint8_t *lut, const SoftmaxDev &P)
 {
     if (MODE != 0 && !any_low) {
         // ---- packed 16-bit path
@@ -190,6 +201,7 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
             const uint32_t c = __umul24(e2[s][1] & 0xffffu, f_top), d = __umul24(e2[s][1] >> 16, f_top);
             uint32_t ww = pack_top_bytes(a, b, c, d);
             if (POSTMODE == PM_CLAMP127) ww = clamp127_bytes(ww);
+            if (POSTMODE == PM_GENERAL) ww = post_lut_gather(lut, ww);
             w[s] = ww;
         }
     } else {
@@ -218,9 +230,14 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
         const uint32_t f = floor_pow2_div(P.m_bits, sum);
         const uint32_t f_top = P.p_shift <= 24 ? f << (24 - P.p_shift) : 0u;
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s)
-            w[s] = normalise4<POSTMODE>((uint32_t)x[s][0], (uint32_t)x[s][1], (uint32_t)x[s][2],
-                                        (uint32_t)x[s][3], f, f_top, P);
+        for (int s = 0; s < SLOTS; ++s) {
+            if (POSTMODE == PM_GENERAL && P.p_shift <= 24)
+                w[s] = post_lut_gather(lut, normalise4<PM_NONE>((uint32_t)x[s][0], (uint32_t)x[s][1],
+                                                                (uint32_t)x[s][2], (uint32_t)x[s][3], f, f_top, P));
+            else
+                w[s] = normalise4<POSTMODE>((uint32_t)x[s][0], (uint32_t)x[s][1], (uint32_t)x[s][2],
+                                            (uint32_t)x[s][3], f, f_top, P);
+        }
     }
 }
 
@@ -231,7 +248,6 @@ softmax_rows_kernel(SoftmaxBatch B)
     constexpr int RPW = 64 / K;                       // rows per wavefront
     constexpr int SLAB = RPW * COLS;                  // elements per slab
     static_assert(RPW % 4 == 0, "slab must start on a 16-byte boundary of the int32 input");
-    static_assert(MODE == 0 || POSTMODE != PM_GENERAL, "packed path has no general post step");
     // 16-byte blocks a row can touch: rows start at element offsets that are multiples of
     // gcd(COLS, 4) inside a block
     constexpr int NB = (COLS % 4 == 0) ? COLS / 4 : ((COLS % 2 == 0) ? (COLS + 2 + 3) / 4 : (COLS + 3 + 3) / 4);
@@ -240,6 +256,7 @@ softmax_rows_kernel(SoftmaxBatch B)
     constexpr bool OUT16 = SLAB % 16 == 0;            // output slab is whole 16-byte chunks
     constexpr int OUT_CHUNKS = OUT16 ? SLAB / 16 : SLAB / 4;   // else whole dwords
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[kRowsWpb][SLAB * 4];
+    __shared__ uint8_t lut_all[kRowsWpb][POSTMODE == PM_GENERAL ? kPostLutBytes : 4];
 
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
@@ -255,6 +272,11 @@ softmax_rows_kernel(SoftmaxBatch B)
     if (slab >= I.n_slabs) return;                    // no workgroup barrier below
 
     uint8_t *lds = lds_all[wv];
+    uint8_t *lut = lut_all[wv];
+    if (POSTMODE == PM_GENERAL) {                     // ordered before its use by the fences below
+        const int p_max = 1 << (P.m_bits - P.p_shift);    // 2^(b-1) <= 128
+        for (int p = lane; p <= p_max; p += 64) lut[p] = (uint8_t)post_dev<PM_GENERAL>((uint32_t)p, P);
+    }
     const i32x4 *src = reinterpret_cast<const i32x4 *>(scores + slab * SLAB);
     const int lr = lane / K;                          // row inside the slab
     const int j = lane % K;                           // lane inside the row
@@ -355,8 +377,8 @@ softmax_rows_kernel(SoftmaxBatch B)
     const bool any_low = __builtin_amdgcn_ballot_w64(low_row) != 0;
     uint32_t w[SLOTS];                                // four output bytes per block
 
-    if (P.variant == 0) softmax_slab_math<K, SLOTS, MODE, 0, POSTMODE>(x, w, mx, lower, any_low, P);
-    else softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE>(x, w, mx, lower, any_low, P);
+    if (P.variant == 0) softmax_slab_math<K, SLOTS, MODE, 0, POSTMODE>(x, w, mx, lower, any_low, lut, P);
+    else softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE>(x, w, mx, lower, any_low, lut, P);
 
     // ---- assemble the slab's bytes in LDS
     uint32_t *lds32 = reinterpret_cast<uint32_t *>(lds);
@@ -435,19 +457,16 @@ static hipError_t launch_rows_b(const SoftmaxBatch &B, unsigned total_wgs, int m
                                 hipStream_t stream)
 {
     const dim3 grid(total_wgs), block(64 * kRowsWpb);
-    if (post_mode == PM_GENERAL || mode == 0) {
-        switch (post_mode) {
-        case PM_NONE: IPTQ_ROWS_LAUNCH(COLS, K, 0, BIAS, PM_NONE); break;
-        case PM_CLAMP127: IPTQ_ROWS_LAUNCH(COLS, K, 0, BIAS, PM_CLAMP127); break;
-        default: IPTQ_ROWS_LAUNCH(COLS, K, 0, BIAS, PM_GENERAL); break;
-        }
-    } else if (mode == 1) {
-        if (post_mode == PM_NONE) IPTQ_ROWS_LAUNCH(COLS, K, 1, BIAS, PM_NONE);
-        else IPTQ_ROWS_LAUNCH(COLS, K, 1, BIAS, PM_CLAMP127);
-    } else {
-        if (post_mode == PM_NONE) IPTQ_ROWS_LAUNCH(COLS, K, 2, BIAS, PM_NONE);
-        else IPTQ_ROWS_LAUNCH(COLS, K, 2, BIAS, PM_CLAMP127);
+#define IPTQ_ROWS_LAUNCH_PM(MODE)                                                                 \
+    switch (post_mode) {                                                                          \
+    case PM_NONE: IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM_NONE); break;                          \
+    case PM_CLAMP127: IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM_CLAMP127); break;                  \
+    default: IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM_GENERAL); break;                            \
     }
+    if (mode == 0) { IPTQ_ROWS_LAUNCH_PM(0) }
+    else if (mode == 1) { IPTQ_ROWS_LAUNCH_PM(1) }
+    else { IPTQ_ROWS_LAUNCH_PM(2) }
+#undef IPTQ_ROWS_LAUNCH_PM
     return hipGetLastError();
 }
 
