@@ -163,7 +163,7 @@ def main():
     ap.add_argument("--workload", default="vit_b",
                     choices=["deit_t", "vit_s", "vit_b", "swin_b", "swin_s_det"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extra", action="store_true", help="skip the secondary Swin-B measurement")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other benchmark configurations")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: softmax rows and GELU elements are independent, so "
@@ -309,11 +309,21 @@ def main():
         "batched": main_res.get("batched"),
         "graph_replay": main_res.get("graph_replay"),
     }
-    if not args.no_extra and args.workload != "swin_b":
-        sw = measure("swin_b")
-        out["extra"] = {"swin_b": {k: sw[k] for k in ("value", "ms_per_step", "algorithmic_gbps",
-                                                      "softmax", "gelu", "batched", "graph_replay")}}
-        out["extra"]["swin_b"]["pct_of_hbm_peak"] = 100.0 * sw["algorithmic_gbps"] / HBM_PEAK_GBS
+    if not args.no_extra:
+        # the other benchmark configurations, same protocol, one compact entry each
+        out["extra"] = {}
+        for name in ("swin_b", "vit_s", "swin_s_det", "deit_t"):
+            if name == args.workload:
+                continue
+            r = measure(name)
+            e = {k: r[k] for k in ("value", "ms_per_step", "algorithmic_gbps", "softmax", "gelu")}
+            e["pct_of_hbm_peak"] = 100.0 * r["algorithmic_gbps"] / HBM_PEAK_GBS
+            if name == "swin_b":
+                e["batched"] = r.get("batched")
+                e["graph_replay"] = r.get("graph_replay")
+            elif "batched" in r:
+                e["batched_pct_of_hbm_peak"] = r["batched"]["pct_of_hbm_peak"]
+            out["extra"][name] = e
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(out))
