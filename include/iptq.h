@@ -47,8 +47,11 @@ extern "C" {
 /* algo field: which kernel family serves the call (results are identical) */
 #define IPTQ_ALGO_AUTO 0
 #define IPTQ_ALGO_GENERIC 1 /* softmax: one wavefront per row, any cols; GELU: polynomial per element */
-#define IPTQ_ALGO_FLEX 2    /* softmax only: the run-time-row-length slab kernel also where a
-                               compiled row length (197, 49) would be picked */
+#define IPTQ_ALGO_FLEX 2    /* softmax only: the LDS-pass kernel with run-time row length and lane
+                               layout, also where a faster kernel would serve */
+#define IPTQ_ALGO_DYNAMIC 3 /* softmax only: the register-resident kernel with run-time row length
+                               (rows up to about 1270 scores), also where a compiled row length
+                               would serve */
 
 /*
  * y = clamp(rshr_round(x * m, s) + zp, qmin, qmax)

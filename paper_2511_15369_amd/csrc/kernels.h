@@ -32,6 +32,10 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
 // *done receives how many rows it took (0 if the shape or the pointers do not qualify).
 hipError_t softmax_flex_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
                                hipStream_t stream);
+// Register-resident slab kernel with a run-time row length: every row of one call, or none
+// (*done == 0) if the row is too long or the pointers do not qualify.
+hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
+                                  hipStream_t stream);
 hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stream);
 hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,
                              bool force_direct, hipStream_t stream);

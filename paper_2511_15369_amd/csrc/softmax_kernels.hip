@@ -146,8 +146,11 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
         for (int i = 0; i < cnt && err == hipSuccess; ++i) {
             const SoftmaxCall &c = calls[base + i];
             const bool has_pre = !(c.P.pre_m == 1 && c.P.pre_s == 0);
-            // a call no compiled row length served goes to the run-time-row-length kernel
-            // (a short leftover of a served call is not worth a launch of its own)
+            // a call no compiled row length served goes to the run-time-row-length kernels
+            if (done[i] == 0 && (c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_DYNAMIC)) {
+                err = softmax_rowsdyn_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
+                if (err != hipSuccess) break;
+            }
             if (done[i] == 0 && c.algo != IPTQ_ALGO_GENERIC) {
                 err = softmax_flex_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
                 if (err != hipSuccess) break;

@@ -1,0 +1,294 @@
+// Integer softmax (Section 4.4, Eq. 6-15) for row lengths that have no compiled
+// instantiation: the slab scheme and the register-resident arithmetic of the
+// fixed-row-length kernel (softmax_rows.h) with the row length as a run-time value.  What is
+// fixed at compile time is the lane layout: K lanes per row and at most SLOTS 16-byte blocks
+// per lane, i.e. rows of up to about 4 K SLOTS columns; the host picks the smallest layout
+// that holds the row.  Slots beyond the row's last block are skipped by wavefront-uniform
+// branches, element masks are computed for every block, and the slab lives in dynamic LDS.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "device_common.h"
+#include "kernels.h"
+#include "plan.h"
+#include "softmax_rows.h"
+
+namespace iptq {
+
+struct DynArgs {
+    const int32_t *scores;
+    const int32_t *bias;
+    uint8_t *out;
+    int64_t n_slabs;      // the last one may be partial
+    int32_t tail_rows;    // rows of the last slab if it is partial, else 0
+    int32_t cols;
+    int32_t n_used;       // blocks per lane that can hold row data: ceil(max blocks per row / K)
+    int32_t wave_lds;     // LDS bytes per wavefront: slab (16-byte multiple) + post table
+    SoftmaxDev P;
+};
+
+template <int K, int SLOTS, int MODE, int POSTMODE>
+__global__ void __launch_bounds__(256)
+softmax_rowsdyn_kernel(DynArgs A)
+{
+    constexpr int RPW = 64 / K;                       // rows per wavefront, a multiple of 4
+    extern __shared__ __attribute__((aligned(16))) uint8_t dyn_lds[];
+    const SoftmaxDev &P = A.P;
+    const int lane = threadIdx.x & 63;
+    const int wv = threadIdx.x >> 6;
+    const int64_t slab = (int64_t)blockIdx.x * (blockDim.x >> 6) + wv;
+    if (slab >= A.n_slabs) return;                    // no workgroup barrier below
+
+    const int cols = A.cols;
+    const int n_used = A.n_used;                      // <= SLOTS (host)
+    const int slab_el = RPW * cols;                   // multiple of 4
+    const int in_chunks = slab_el >> 2;               // <= 64 * n_used
+    uint8_t *lds = dyn_lds + wv * A.wave_lds;
+    uint8_t *lut = lds + A.wave_lds - kPostLutBytes;
+    if (POSTMODE == PM_GENERAL) {                     // ordered before its use by the fences below
+        const int p_max = 1 << (P.m_bits - P.p_shift);
+        for (int p = lane; p <= p_max; p += 64) lut[p] = (uint8_t)post_dev<PM_GENERAL>((uint32_t)p, P);
+    }
+    const int32_t *src1 = A.scores + slab * slab_el;
+    const i32x4 *src = reinterpret_cast<const i32x4 *>(src1);
+    const int32_t *__restrict__ bias = A.bias;
+    const bool partial = A.tail_rows != 0 && slab == A.n_slabs - 1;
+    const int valid_el = (partial ? A.tail_rows : RPW) * cols;
+
+    // ---- flat copy of the slab into LDS, bias added on the way.  Every load is issued before
+    // the first LDS write: lanes beyond the slab's last chunk load its last chunk again (no
+    // lane-divergent branch around a load), whole unused passes are skipped by uniform
+    // branches, and the two wavefront-uniform choices are made outside the loops.
+    auto add_bias = [](i32x4 v, const i32x4 bv) {
+        v.x = v.x == kI32Min ? v.x : sat_add_i32(v.x, bv.x);
+        v.y = v.y == kI32Min ? v.y : sat_add_i32(v.y, bv.y);
+        v.z = v.z == kI32Min ? v.z : sat_add_i32(v.z, bv.z);
+        v.w = v.w == kI32Min ? v.w : sat_add_i32(v.w, bv.w);
+        return v;
+    };
+    auto copy_in = [&](auto bias_tag) {
+        constexpr bool BIAS = decltype(bias_tag)::value;
+        i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
+        uint32_t boff = 0;
+        if (BIAS) boff = row_mod_period((uint32_t)(slab * RPW), P) * (uint32_t)cols;
+        const uint32_t pe = (uint32_t)P.bias_period_rows * (uint32_t)cols;
+        // bias chunks come from L2: a ring of kAhead loads in flight behind the score loads
+        // keeps the staging registers at 4 * (SLOTS + kAhead)
+        constexpr int kAhead = 4;
+        auto bias_chunk = [&](int i) {
+            const int idx = min(i * 64 + lane, in_chunks - 1);
+            uint32_t o = boff + 4u * (uint32_t)idx;
+            if (o >= pe) o -= pe;
+            return *reinterpret_cast<const i32x4 *>(bias + o);
+        };
+        i32x4 v[SLOTS], bv[BIAS ? kAhead : 1];
+#pragma unroll
+        for (int i = 0; i < SLOTS; ++i)
+            if (i * 64 < in_chunks) v[i] = stream_load(src + min(i * 64 + lane, in_chunks - 1));
+        if (BIAS) {
+#pragma unroll
+            for (int i = 0; i < kAhead && i < SLOTS; ++i)
+                if (i * 64 < in_chunks) bv[i] = bias_chunk(i);
+        }
+#pragma unroll
+        for (int i = 0; i < SLOTS; ++i) {
+            if (i * 64 < in_chunks) {
+                const int idx = i * 64 + lane;
+                const i32x4 t = BIAS ? add_bias(v[i], bv[BIAS ? i % kAhead : 0]) : v[i];
+                if (BIAS && i + kAhead < SLOTS && (i + kAhead) * 64 < in_chunks) bv[i % kAhead] = bias_chunk(i + kAhead);
+                if (idx < in_chunks) lds4[idx] = t;
+            }
+        }
+        wave_lds_fence();
+    };
+    // the one partial slab of a launch: guarded loads, chunk by chunk
+    auto copy_in_partial = [&]() {
+        i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
+        uint32_t boff = 0;
+        if (bias != nullptr) boff = row_mod_period((uint32_t)(slab * RPW), P) * (uint32_t)cols;
+        const uint32_t pe = (uint32_t)P.bias_period_rows * (uint32_t)cols;
+        for (int idx = lane; idx < in_chunks; idx += 64) {
+            i32x4 v;
+            if (4 * idx + 3 < valid_el) {
+                v = stream_load(src + idx);
+            } else {
+                v = (i32x4){0, 0, 0, 0};
+                if (4 * idx < valid_el) v.x = src1[4 * idx];
+                if (4 * idx + 1 < valid_el) v.y = src1[4 * idx + 1];
+                if (4 * idx + 2 < valid_el) v.z = src1[4 * idx + 2];
+            }
+            if (bias != nullptr) {
+                uint32_t o = boff + 4u * (uint32_t)idx;
+                if (o >= pe) o -= pe;
+                v = add_bias(v, *reinterpret_cast<const i32x4 *>(bias + o));
+            }
+            lds4[idx] = v;
+        }
+        wave_lds_fence();
+    };
+    if (partial) copy_in_partial();
+    else if (bias != nullptr) copy_in(std::true_type{});
+    else copy_in(std::false_type{});
+
+    // ---- this lane's blocks; elements outside the row become "minus infinity"
+    const int lr = lane / K;                          // row inside the slab
+    const int j = lane % K;                           // lane inside the row
+    const int e_r = lr * cols;                        // first element of the row in the slab
+    const int b_r = e_r >> 2;                         // its 16-byte block
+    const int phi = e_r & 3;                          // and its offset inside that block
+    const int nb = (phi + cols + 3) >> 2;             // blocks the row touches
+    int32_t x[SLOTS][4];
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+        if (s >= n_used) {
+            x[s][0] = x[s][1] = x[s][2] = x[s][3] = kI32Min;
+            continue;
+        }
+        const int b = s * K + j;
+        // blocks beyond the row's last one are read from its last one and masked entirely below
+        // (4 b - phi >= cols there): no lane-divergent branch around the LDS read
+        const i32x4 v = reinterpret_cast<const i32x4 *>(lds)[b_r + min(b, nb - 1)];
+        x[s][0] = v.x; x[s][1] = v.y; x[s][2] = v.z; x[s][3] = v.w;
+        // only a row's first block and the slots that can reach its end need element masks
+        // (wavefront-uniform test)
+        if (s == 0 || 4 * (s * K + K - 1) + 3 >= cols) {
+            const int c0 = 4 * b - phi;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if ((unsigned)(c0 + e) >= (unsigned)cols) x[s][e] = kI32Min;
+        }
+    }
+    wave_lds_fence();                                 // the slab area is reused for the output
+
+    // ---- fused requantization of the scores (after the bias, before the maximum)
+    if (P.pre_mode == 1) {
+        const int32_t pre_mul = P.pre_mul, pre_sh2 = P.pre_sh2;
+        const int64_t pre_rnd = P.pre_rnd;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            if (s >= n_used) continue;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int32_t r = pre_requant_narrow(x[s][e], pre_mul, pre_rnd, pre_sh2);
+                x[s][e] = x[s][e] == kI32Min ? kI32Min : r;
+            }
+        }
+    }
+
+    // ---- Eq. 6: row maximum
+    int32_t mx = kI32Min;
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+        if (s >= n_used) continue;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mx = max(mx, x[s][e]);
+    }
+    mx = group_max_i32<K>(mx);
+
+    const int32_t D = P.d_clamp;
+    const bool low_row = mx < kI32Min + D;            // see softmax_rows_kernel
+    const int32_t lower = low_row ? kI32Min : mx - D;
+    const bool any_low = __builtin_amdgcn_ballot_w64(low_row) != 0;
+    uint32_t w[SLOTS];                                // four output bytes per block
+
+    if (P.variant == 0) softmax_slab_math<K, SLOTS, MODE, 0, POSTMODE, true>(x, w, mx, lower, any_low, lut, P, n_used);
+    else softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE, true>(x, w, mx, lower, any_low, lut, P, n_used);
+
+    // ---- assemble the slab's bytes in LDS
+    uint32_t *lds32 = reinterpret_cast<uint32_t *>(lds);
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+        if (s >= n_used) continue;
+        const int b = s * K + j;
+        if (s != 0 && 4 * (s * K + K - 1) + 3 < cols) {   // every lane's block lies inside its row
+            lds32[b_r + b] = w[s];
+        } else if (b < nb) {
+            const int c0 = 4 * b - phi;
+            if (c0 >= 0 && c0 + 3 < cols) {
+                lds32[b_r + b] = w[s];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if ((unsigned)(c0 + e) < (unsigned)cols)
+                        lds[4 * (b_r + b) + e] = (uint8_t)(w[s] >> (8 * e));
+            }
+        }
+    }
+    wave_lds_fence();
+
+    // ---- flat, fully coalesced store (byte stores at the end of a partial slab)
+    uint8_t *dst8 = A.out + slab * slab_el;
+    if ((slab_el & 15) == 0) {
+        const int n16 = slab_el >> 4;
+#pragma unroll
+        for (int i = 0; i < (SLOTS + 3) / 4; ++i) {
+            const int idx = i * 64 + lane;
+            if (idx < n16) {
+                if (16 * idx + 15 < valid_el) {
+                    stream_store(reinterpret_cast<const u32x4 *>(lds)[idx], reinterpret_cast<u32x4 *>(dst8) + idx);
+                } else {
+#pragma unroll 1
+                    for (int b = 16 * idx; b < valid_el && b < 16 * idx + 16; ++b) dst8[b] = lds[b];
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < SLOTS; ++i) {
+            const int idx = i * 64 + lane;
+            if (idx < in_chunks) {
+                if (4 * idx + 3 < valid_el) {
+                    stream_store(lds32[idx], reinterpret_cast<uint32_t *>(dst8) + idx);
+                } else {
+#pragma unroll 1
+                    for (int b = 4 * idx; b < valid_el && b < 4 * idx + 4; ++b) dst8[b] = lds[b];
+                }
+            }
+        }
+    }
+}
+
+template <int K, int SLOTS>
+static void rowsdyn_launch_ks(const DynArgs &A, int mode, int post_mode, dim3 grid, dim3 block, size_t lds,
+                              hipStream_t stream)
+{
+#define IPTQ_DYN_LAUNCH(MODE, PM)                                                                 \
+    hipLaunchKernelGGL((softmax_rowsdyn_kernel<K, SLOTS, MODE, PM>), grid, block, lds, stream, A)
+    if (mode == 0) {
+        if (post_mode == PM_NONE) IPTQ_DYN_LAUNCH(0, PM_NONE);
+        else if (post_mode == PM_CLAMP127) IPTQ_DYN_LAUNCH(0, PM_CLAMP127);
+        else IPTQ_DYN_LAUNCH(0, PM_GENERAL);
+    } else {                                          // 2 covers 1: t16 == 0 shifts by 0
+        if (post_mode == PM_NONE) IPTQ_DYN_LAUNCH(2, PM_NONE);
+        else if (post_mode == PM_CLAMP127) IPTQ_DYN_LAUNCH(2, PM_CLAMP127);
+        else IPTQ_DYN_LAUNCH(2, PM_GENERAL);
+    }
+#undef IPTQ_DYN_LAUNCH
+}
+
+// One launcher per lane count, each defined in its own translation unit so that the
+// instantiations compile in parallel: 8 blocks per lane for every lane count
+// (softmax_rowsdyn_k<K>.hip), 13, 16 and 20 for 16 lanes per row (softmax_rowsdyn_k16_s<N>.hip).
+template <int K>
+void rowsdyn_launch_k(const DynArgs &A, int mode, int post_mode, dim3 grid, dim3 block, size_t lds,
+                      hipStream_t stream);
+template <> void rowsdyn_launch_k<2>(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
+template <> void rowsdyn_launch_k<4>(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
+template <> void rowsdyn_launch_k<8>(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
+template <> void rowsdyn_launch_k<16>(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
+void rowsdyn_launch_k16_s13(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
+void rowsdyn_launch_k16_s16(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
+void rowsdyn_launch_k16_s20(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
+
+#define IPTQ_DEFINE_ROWSDYN_LAUNCHER(K)                                                           \
+    template <>                                                                                   \
+    void rowsdyn_launch_k<K>(const DynArgs &A, int mode, int post_mode, dim3 grid, dim3 block, size_t lds, \
+                             hipStream_t stream)                                                  \
+    {                                                                                             \
+        rowsdyn_launch_ks<K, 8>(A, mode, post_mode, grid, block, lds, stream);                    \
+    }
+
+}  // namespace iptq

@@ -1,0 +1,65 @@
+// Host side of the run-time-row-length slab kernel (softmax_rowsdyn.h): lane layout for a
+// row length and the launch.
+#include <hip/hip_runtime.h>
+
+#include "softmax_rowsdyn.h"
+
+namespace iptq {
+
+// Lane layout for a row length: the fewest lanes per row that keep the blocks per lane at or
+// below 8 (91 VGPRs, 5 wavefronts per SIMD; measured equal or better than up to 13 blocks on
+// fewer lanes), else 16 lanes per row with up to 20 blocks per lane.  Returns false if the row
+// is longer than that.
+bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used)
+{
+    const int nb_max = (cols % 4 == 0) ? cols / 4 : ((cols % 2 == 0) ? (cols + 2 + 3) / 4 : (cols + 3 + 3) / 4);
+    int k = 2;
+    while (k < 16 && (nb_max + k - 1) / k > 8) k *= 2;
+    const int n = (nb_max + k - 1) / k;
+    if (n > 20) return false;
+    *lanes = k;
+    *n_used = n;
+    *slots = n <= 8 ? 8 : (n <= 13 ? 13 : (n <= 16 ? 16 : 20));
+    return true;
+}
+
+// Every row of one call if the call qualifies; returns the number of rows served through
+// *done (0: not served, nothing enqueued).
+hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
+                                  hipStream_t stream)
+{
+    *done = 0;
+    int k = 0, slots = 0, n_used = 0;
+    if (!rowsdyn_geometry(cols, &k, &slots, &n_used)) return hipSuccess;
+    const int rpw = 64 / k;
+    const bool has_bias = c.bias != nullptr;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.out)) & 15) == 0;
+    const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
+                                       ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
+                                       c.P.bias_period_rows >= rpw);
+    const int64_t n_slabs = (c.rows + rpw - 1) / rpw;
+    if (!aligned || !bias_ok || n_slabs == 0 || c.P.pre_mode == 2) return hipSuccess;
+    DynArgs A;
+    A.scores = c.scores; A.bias = c.bias; A.out = c.out;
+    A.n_slabs = n_slabs; A.tail_rows = (int32_t)(c.rows % rpw);
+    A.cols = cols; A.n_used = n_used;
+    A.wave_lds = (int32_t)((((int64_t)rpw * cols * 4 + 15) & ~(int64_t)15) + kPostLutBytes);
+    A.P = c.P;
+    int wpb = 65536 / A.wave_lds;                     // wavefronts per workgroup: 1..4
+    if (wpb > 4) wpb = 4;
+    if (wpb < 1) return hipSuccess;
+    const dim3 grid((unsigned)((n_slabs + wpb - 1) / wpb)), block(64 * wpb);
+    const size_t lds = (size_t)A.wave_lds * wpb;
+    const int mode = (post_mode == PM_GENERAL && c.P.p_shift > 24) ? 0 : c.P.mode16;
+    if (slots == 13) rowsdyn_launch_k16_s13(A, mode, post_mode, grid, block, lds, stream);
+    else if (slots == 16) rowsdyn_launch_k16_s16(A, mode, post_mode, grid, block, lds, stream);
+    else if (slots == 20) rowsdyn_launch_k16_s20(A, mode, post_mode, grid, block, lds, stream);
+    else if (k == 2) rowsdyn_launch_k<2>(A, mode, post_mode, grid, block, lds, stream);
+    else if (k == 4) rowsdyn_launch_k<4>(A, mode, post_mode, grid, block, lds, stream);
+    else if (k == 8) rowsdyn_launch_k<8>(A, mode, post_mode, grid, block, lds, stream);
+    else rowsdyn_launch_k<16>(A, mode, post_mode, grid, block, lds, stream);
+    *done = c.rows;
+    return hipGetLastError();
+}
+
+}  // namespace iptq

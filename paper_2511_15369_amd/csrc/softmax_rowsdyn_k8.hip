@@ -1,0 +1,6 @@
+// Run-time-row-length softmax slab kernel, 8 lanes per row.
+#include "softmax_rowsdyn.h"
+
+namespace iptq {
+IPTQ_DEFINE_ROWSDYN_LAUNCHER(8)
+}
