@@ -306,28 +306,33 @@ softmax_rows_kernel(SoftmaxBatch B)
 #pragma unroll
         for (int i = 0; i < (IN_CHUNKS + 63) / 64; ++i) {
             const int idx = i * 64 + lane;
-            if ((i + 1) * 64 <= IN_CHUNKS || idx < IN_CHUNKS) {
-                i32x4 v;
-                if (!PARTIAL || 4 * idx + 3 < valid_el) {
-                    v = stream_load(src + idx);
-                } else {
-                    const int32_t *s = scores + slab * SLAB + 4 * idx;
-                    v = (i32x4){0, 0, 0, 0};
-                    if (4 * idx < valid_el) v.x = s[0];
-                    if (4 * idx + 1 < valid_el) v.y = s[1];
-                    if (4 * idx + 2 < valid_el) v.z = s[2];
-                }
-                if (BIAS) {
-                    uint32_t o = boff + 4u * (uint32_t)idx;
-                    if (o >= pe) o -= pe;
-                    const i32x4 bv = *reinterpret_cast<const i32x4 *>(bias + o);
-                    v.x = v.x == kI32Min ? v.x : sat_add_i32(v.x, bv.x);
-                    v.y = v.y == kI32Min ? v.y : sat_add_i32(v.y, bv.y);
-                    v.z = v.z == kI32Min ? v.z : sat_add_i32(v.z, bv.z);
-                    v.w = v.w == kI32Min ? v.w : sat_add_i32(v.w, bv.w);
-                }
-                lds4[idx] = v;
+            const bool full_pass = (i + 1) * 64 <= IN_CHUNKS;
+            if (PARTIAL && !(full_pass || idx < IN_CHUNKS)) continue;
+            // In the last, partly filled pass the lanes beyond the slab load its last chunk again
+            // and write it to the same LDS address again (same data): a load behind a
+            // lane-divergent branch would be issued after all the others had returned, a second
+            // memory round trip per wavefront.
+            const int li = (PARTIAL || full_pass) ? idx : min(idx, IN_CHUNKS - 1);
+            i32x4 v;
+            if (!PARTIAL || 4 * idx + 3 < valid_el) {
+                v = stream_load(src + li);
+            } else {
+                const int32_t *s = scores + slab * SLAB + 4 * idx;
+                v = (i32x4){0, 0, 0, 0};
+                if (4 * idx < valid_el) v.x = s[0];
+                if (4 * idx + 1 < valid_el) v.y = s[1];
+                if (4 * idx + 2 < valid_el) v.z = s[2];
             }
+            if (BIAS) {
+                uint32_t o = boff + 4u * (uint32_t)li;
+                if (o >= pe) o -= pe;
+                const i32x4 bv = *reinterpret_cast<const i32x4 *>(bias + o);
+                v.x = v.x == kI32Min ? v.x : sat_add_i32(v.x, bv.x);
+                v.y = v.y == kI32Min ? v.y : sat_add_i32(v.y, bv.y);
+                v.z = v.z == kI32Min ? v.z : sat_add_i32(v.z, bv.z);
+                v.w = v.w == kI32Min ? v.w : sat_add_i32(v.w, bv.w);
+            }
+            lds4[li] = v;
         }
         wave_lds_fence();
     };
@@ -340,8 +345,10 @@ softmax_rows_kernel(SoftmaxBatch B)
     for (int s = 0; s < SLOTS; ++s) {
         const int b = s * K + j;
         const bool always_inside = 4 * (s * K + K - 1) < COLS;
-        i32x4 v = {kI32Min, kI32Min, kI32Min, kI32Min};
-        if (always_inside || 4 * b < phi + COLS) v = reinterpret_cast<const i32x4 *>(lds)[b_r + b];
+        // a block beyond the row's last one is read from the last one and masked entirely below
+        // (no lane-divergent branch around the LDS read)
+        const int bb = always_inside ? b : min(b, ((phi + COLS + 3) >> 2) - 1);
+        const i32x4 v = reinterpret_cast<const i32x4 *>(lds)[b_r + bb];
         x[s][0] = v.x; x[s][1] = v.y; x[s][2] = v.z; x[s][3] = v.w;
         const bool may_cut = (s == 0) || (4 * (s * K + K - 1) + 3 >= COLS);
         if (may_cut) {
