@@ -272,7 +272,7 @@ softmax_rows_kernel(SoftmaxBatch B)
     for (int i = 1; i < B.n_items; ++i)
         if (blockIdx.x >= B.item[i].first_wg) it = i;
     const SoftmaxItem &I = B.item[it];
-    const SoftmaxDev &P = I.P;
+    const SoftmaxDev P = I.P;                         // by value: every field loaded once, up front
     const int32_t *__restrict__ scores = I.scores;
     const int32_t *__restrict__ bias = I.bias;
     uint8_t *__restrict__ out = I.out;
