@@ -50,8 +50,10 @@ extern "C" {
 #define IPTQ_ALGO_FLEX 2    /* softmax only: the LDS-pass kernel with run-time row length and lane
                                layout, also where a faster kernel would serve */
 #define IPTQ_ALGO_DYNAMIC 3 /* softmax only: the register-resident kernel with run-time row length
-                               (rows up to about 1270 scores), also where a compiled row length
+                               (rows up to about 830 scores), also where a compiled row length
                                would serve */
+#define IPTQ_ALGO_WIDE 4    /* softmax only: one wavefront per row, row in registers, no LDS staging
+                               (rows up to 5117 scores), also where another kernel would serve */
 
 /*
  * y = clamp(rshr_round(x * m, s) + zp, qmin, qmax)

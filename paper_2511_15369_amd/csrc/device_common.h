@@ -133,7 +133,8 @@ IPTQ_DEV int32_t dpp_i32(int32_t v)
     return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
 }
 
-// All-reduce over aligned groups of K lanes (K in {1,2,4,8,16}); every lane gets the result.
+// All-reduce over aligned groups of K lanes (K a power of two up to 64); every lane gets the
+// result.  Up to 16 lanes stay on the DPP path; 32 and 64 add steps through the permute network.
 template <int K>
 IPTQ_DEV int32_t group_max_i32(int32_t v)
 {
@@ -141,6 +142,8 @@ IPTQ_DEV int32_t group_max_i32(int32_t v)
     if (K >= 4) v = max(v, dpp_i32<0x4E>(v));
     if (K >= 8) v = max(v, dpp_i32<0x141>(v));
     if (K >= 16) v = max(v, dpp_i32<0x140>(v));
+    if (K >= 32) v = max(v, __shfl_xor(v, 16));
+    if (K >= 64) v = max(v, __shfl_xor(v, 32));
     return v;
 }
 
@@ -151,6 +154,8 @@ IPTQ_DEV uint32_t group_sum_u32(uint32_t v)
     if (K >= 4) v += (uint32_t)dpp_i32<0x4E>((int32_t)v);
     if (K >= 8) v += (uint32_t)dpp_i32<0x141>((int32_t)v);
     if (K >= 16) v += (uint32_t)dpp_i32<0x140>((int32_t)v);
+    if (K >= 32) v += (uint32_t)__shfl_xor((int32_t)v, 16);
+    if (K >= 64) v += (uint32_t)__shfl_xor((int32_t)v, 32);
     return v;
 }
 

@@ -36,6 +36,10 @@ hipError_t softmax_flex_launch(const SoftmaxCall &c, int32_t cols, int post_mode
 // (*done == 0) if the row is too long or the pointers do not qualify.
 hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
                                   hipStream_t stream);
+// One wavefront per row, row in registers, no LDS staging (rows of up to 5117 scores): the
+// leading rows of one call (all of them unless the tensor ends off a 16-byte boundary).
+hipError_t softmax_wide_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
+                               hipStream_t stream);
 hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stream);
 hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,
                              bool force_direct, hipStream_t stream);

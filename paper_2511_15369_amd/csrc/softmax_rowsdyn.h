@@ -2,7 +2,7 @@
 // instantiation: the slab scheme and the register-resident arithmetic of the
 // fixed-row-length kernel (softmax_rows.h) with the row length as a run-time value.  What is
 // fixed at compile time is the lane layout: K lanes per row and at most SLOTS 16-byte blocks
-// per lane, i.e. rows of up to about 4 K SLOTS columns; the host picks the smallest layout
+// per lane, i.e. rows of up to about 4 K SLOTS columns (830 at most); the host picks the smallest layout
 // that holds the row.  Slots beyond the row's last block are skipped by wavefront-uniform
 // branches, element masks are computed for every block, and the slab lives in dynamic LDS.
 #pragma once
@@ -271,7 +271,7 @@ static void rowsdyn_launch_ks(const DynArgs &A, int mode, int post_mode, dim3 gr
 
 // One launcher per lane count, each defined in its own translation unit so that the
 // instantiations compile in parallel: 8 blocks per lane for every lane count
-// (softmax_rowsdyn_k<K>.hip), 13, 16 and 20 for 16 lanes per row (softmax_rowsdyn_k16_s<N>.hip).
+// (softmax_rowsdyn_k<K>.hip), 13 for 16 lanes per row (softmax_rowsdyn_k16_s13.hip).
 template <int K>
 void rowsdyn_launch_k(const DynArgs &A, int mode, int post_mode, dim3 grid, dim3 block, size_t lds,
                       hipStream_t stream);
@@ -280,8 +280,6 @@ template <> void rowsdyn_launch_k<4>(const DynArgs &, int, int, dim3, dim3, size
 template <> void rowsdyn_launch_k<8>(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
 template <> void rowsdyn_launch_k<16>(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
 void rowsdyn_launch_k16_s13(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
-void rowsdyn_launch_k16_s16(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
-void rowsdyn_launch_k16_s20(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
 
 #define IPTQ_DEFINE_ROWSDYN_LAUNCHER(K)                                                           \
     template <>                                                                                   \

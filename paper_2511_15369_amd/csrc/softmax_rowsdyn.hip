@@ -8,18 +8,19 @@ namespace iptq {
 
 // Lane layout for a row length: the fewest lanes per row that keep the blocks per lane at or
 // below 8 (91 VGPRs, 5 wavefronts per SIMD; measured equal or better than up to 13 blocks on
-// fewer lanes), else 16 lanes per row with up to 20 blocks per lane.  Returns false if the row
-// is longer than that.
+// fewer lanes), else 16 lanes per row with up to 13 blocks per lane (rows of up to about 830
+// scores).  Returns false for longer rows: one wavefront per row serves those better
+// (softmax_wide.h; measured 58 % against 32 % of the HBM roofline at 1025 columns).
 bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used)
 {
     const int nb_max = (cols % 4 == 0) ? cols / 4 : ((cols % 2 == 0) ? (cols + 2 + 3) / 4 : (cols + 3 + 3) / 4);
     int k = 2;
     while (k < 16 && (nb_max + k - 1) / k > 8) k *= 2;
     const int n = (nb_max + k - 1) / k;
-    if (n > 20) return false;
+    if (n > 13) return false;
     *lanes = k;
     *n_used = n;
-    *slots = n <= 8 ? 8 : (n <= 13 ? 13 : (n <= 16 ? 16 : 20));
+    *slots = n <= 8 ? 8 : 13;
     return true;
 }
 
@@ -52,8 +53,6 @@ hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_m
     const size_t lds = (size_t)A.wave_lds * wpb;
     const int mode = (post_mode == PM_GENERAL && c.P.p_shift > 24) ? 0 : c.P.mode16;
     if (slots == 13) rowsdyn_launch_k16_s13(A, mode, post_mode, grid, block, lds, stream);
-    else if (slots == 16) rowsdyn_launch_k16_s16(A, mode, post_mode, grid, block, lds, stream);
-    else if (slots == 20) rowsdyn_launch_k16_s20(A, mode, post_mode, grid, block, lds, stream);
     else if (k == 2) rowsdyn_launch_k<2>(A, mode, post_mode, grid, block, lds, stream);
     else if (k == 4) rowsdyn_launch_k<4>(A, mode, post_mode, grid, block, lds, stream);
     else if (k == 8) rowsdyn_launch_k<8>(A, mode, post_mode, grid, block, lds, stream);
