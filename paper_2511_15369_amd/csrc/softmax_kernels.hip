@@ -124,6 +124,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             // the fused bias needs 16-byte aligned bias blocks and at most one wrap per slab
             const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
                                                ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
+                                       (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 31) &&
                                                c.P.bias_period_rows >= rpw);
             if (rpw == 0 || c.algo != IPTQ_ALGO_AUTO || c.P.pre_mode == 2 || !aligned || !bias_ok) continue;
             const int64_t n_slabs = (c.rows + rpw - 1) / rpw;    // a partial last slab is served too

@@ -37,6 +37,7 @@ hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_m
     const bool aligned = ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.out)) & 15) == 0;
     const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
                                        ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
+                                       (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 31) &&
                                        c.P.bias_period_rows >= rpw);
     const int64_t n_slabs = (c.rows + rpw - 1) / rpw;
     if (!aligned || !bias_ok || n_slabs == 0 || c.P.pre_mode == 2) return hipSuccess;
