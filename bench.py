@@ -106,6 +106,46 @@ def time_region(fn, reps):
     return start.elapsed_time(stop) / reps
 
 
+def measure_fused(steps):
+    """The requantization fused in front of both layers, on ViT-B-sized tensors: softmax with
+    the scores requantized to about 8 bits first (dyadic 20000 / 2^24), and the GELU taking
+    int32 accumulators requantized to int8 codes (dyadic 20000 / 2^26, |q| <= 127)."""
+    import torch
+
+    import paper_2511_15369_amd as ip
+    units = [Unit("vit_b", u) for u in range(4)]
+    sps, gps = [], []
+    for u in units:
+        sp = ip.softmax_prepare(2.0 ** -4, u.cols, u.sp.variant, 0)
+        sp.pre_m, sp.pre_s = 20000, 24
+        sps.append(sp)
+        gp = ip.gelu_prepare(2.0 ** -5, 2.0 ** -5, 0, 0, u.gp.variant, 127)
+        gp.pre_m, gp.pre_s = 20000, 26
+        gps.append(gp)
+    d_y32 = [torch.empty(u.softmax_elements, dtype=torch.int8, device="cuda") for u in units]
+
+    def softmax_pre():
+        for u, sp in zip(units, sps):
+            ip.softmax_i32(u.d_scores, None, 0, u.d_probs, u.rows, u.cols, sp)
+
+    def gelu_i32():
+        for u, gp, y in zip(units, gps, d_y32):
+            ip.gelu_i32(u.d_scores.view(-1), y, u.softmax_elements, gp)
+
+    res = {}
+    for name, fn in (("softmax_pre_requant", softmax_pre), ("gelu_i32", gelu_i32)):
+        for _ in range(3):
+            fn()
+        ms = time_region(fn, steps) / len(units)
+        el = units[0].softmax_elements
+        res[name] = {"elements": el, "avg_launch_us": ms * 1e3,
+                     "gbps": SOFTMAX_BYTES_PER_EL * el / (ms * 1e-3) / 1e9,
+                     "pct_of_hbm_peak": 100.0 * SOFTMAX_BYTES_PER_EL * el / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    del units, d_y32
+    torch.cuda.empty_cache()
+    return res
+
+
 def cpu_baseline(name, budget_units=12):
     """The CPU oracle on the first layers of the same workload: once on one thread, then the
     same calls row-partitioned over every host core (threads; the C calls release the GIL)."""
@@ -324,6 +364,8 @@ def main():
             elif "batched" in r:
                 e["batched_pct_of_hbm_peak"] = r["batched"]["pct_of_hbm_peak"]
             out["extra"][name] = e
+    if not args.no_extra:
+        out["extra"]["fused_requant"] = measure_fused(args.steps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(out))
