@@ -88,6 +88,7 @@ struct GeluBatch {
     int32_t n_items;
     GeluItem item[kGeluBatchMax];
 };
+static_assert(sizeof(GeluBatch) <= 4096, "kernel arguments are limited to 4 KiB");
 
 __global__ void __launch_bounds__(256)
 gelu_i8_table_kernel(GeluBatch B)

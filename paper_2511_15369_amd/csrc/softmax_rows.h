@@ -53,6 +53,7 @@ struct SoftmaxBatch {
     int32_t n_items;
     SoftmaxItem item[kBatchMax];
 };
+static_assert(sizeof(SoftmaxBatch) <= 4096, "kernel arguments are limited to 4 KiB");
 
 // rshr_round(x * pre_m, pre_s) for pre_s >= 16 (SoftmaxDev::pre_mode 1): one 64-bit
 // multiply-add and a 32-bit shift of its high half.
