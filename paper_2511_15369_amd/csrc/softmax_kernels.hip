@@ -126,7 +126,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
                                                ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
                                        (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 31) &&
                                                c.P.bias_period_rows >= rpw);
-            if (rpw == 0 || c.algo != IPTQ_ALGO_AUTO || c.P.pre_mode == 2 || !aligned || !bias_ok) continue;
+            if (rpw == 0 || c.algo != IPTQ_ALGO_AUTO || !aligned || !bias_ok) continue;
             const int64_t n_slabs = (c.rows + rpw - 1) / rpw;    // a partial last slab is served too
             if (n_slabs == 0) continue;
             const int pm = post_mode_of(c.P, c.out_bits);

@@ -375,6 +375,15 @@ softmax_rows_kernel(SoftmaxBatch B)
                 const int32_t r = pre_requant_narrow(x[s][e], pre_mul, pre_rnd, pre_sh2);
                 x[s][e] = x[s][e] == kI32Min ? kI32Min : r;
             }
+    } else if (P.pre_mode == 2) {                     // shifts below 16: the general 64-bit form
+        const int32_t pre_m = P.pre_m, pre_s = P.pre_s;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int32_t r = pre_requant_dev(x[s][e], pre_m, pre_s);
+                x[s][e] = x[s][e] == kI32Min ? kI32Min : r;
+            }
     }
 
     // ---- Eq. 6: row maximum

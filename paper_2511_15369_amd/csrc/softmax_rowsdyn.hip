@@ -40,7 +40,7 @@ hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_m
                                        (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 31) &&
                                        c.P.bias_period_rows >= rpw);
     const int64_t n_slabs = (c.rows + rpw - 1) / rpw;
-    if (!aligned || !bias_ok || n_slabs == 0 || c.P.pre_mode == 2) return hipSuccess;
+    if (!aligned || !bias_ok || n_slabs == 0) return hipSuccess;
     DynArgs A;
     A.scores = c.scores; A.bias = c.bias; A.out = c.out;
     A.n_slabs = n_slabs; A.tail_rows = (int32_t)(c.rows % rpw);

@@ -105,6 +105,17 @@ softmax_wide_kernel(WideArgs A)
                 x[s][e] = x[s][e] == kI32Min ? kI32Min : r;
             }
         }
+    } else if (P.pre_mode == 2) {                     // shifts below 16: the general 64-bit form
+        const int32_t pre_m = P.pre_m, pre_s = P.pre_s;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            if (s >= n_used) continue;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int32_t r = pre_requant_dev(x[s][e], pre_m, pre_s);
+                x[s][e] = x[s][e] == kI32Min ? kI32Min : r;
+            }
+        }
     }
 
     // ---- Eq. 6: row maximum

@@ -19,7 +19,7 @@ hipError_t softmax_wide_launch(const SoftmaxCall &c, int32_t cols, int post_mode
     const bool aligned = ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.out)) & 15) == 0;
     const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
                                        ((int64_t)c.P.bias_period_rows * cols) % 4 == 0);
-    if (!aligned || !bias_ok || c.P.pre_mode == 2) return hipSuccess;
+    if (!aligned || !bias_ok) return hipSuccess;
     const int64_t rows = ((c.rows * cols) % 4 == 0) ? c.rows : c.rows - 1;
     if (rows <= 0) return hipSuccess;
     WideArgs A;
