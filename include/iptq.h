@@ -150,6 +150,10 @@ int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t out_is_sig
  * bias_period_rows = heads * window_tokens; d_out: rows * cols bytes (device), uint8_t or
  * int8_t per p->out_is_signed, must not overlap d_scores.
  * 0 <= rows < 2^31 (0 is a no-op), 1 <= cols <= IPTQ_COLS_MAX.
+ * Every shape gives the same bytes; speed depends on it.  Fastest: 16-byte aligned d_scores and
+ * d_out (and d_bias, with bias_period_rows * cols a multiple of 4) and a row length of 197, 49,
+ * 198, 144, 257 or 577; any other row length up to 5117 runs in the register-resident kernels
+ * with a run-time row length, longer or unaligned ones in slower multi-pass kernels.
  */
 int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias, int64_t bias_period_rows,
                      void *d_out, int64_t rows, int32_t cols, const iptq_softmax_params_t *p,

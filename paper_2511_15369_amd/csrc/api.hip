@@ -220,6 +220,25 @@ extern "C" int iptq_debug_softmax_plan(const iptq_softmax_params_t *p, int64_t r
     return rc;
 }
 
+// Layout the run-time-row-length kernels would use for a row length:
+// out9 = {dyn ok, dyn lanes, dyn slots, dyn blocks per lane, wide ok, wide passes, wide slots,
+//         flex ok, flex log2 lanes}.
+extern "C" int iptq_debug_softmax_layout(int32_t cols, int32_t *out9)
+{
+    if (!out9) return IPTQ_ERR_NULL;
+    if (cols < 1 || cols > IPTQ_COLS_MAX) return IPTQ_ERR_SHAPE;
+    int a = 0, b = 0, c = 0;
+    out9[0] = rowsdyn_geometry(cols, &a, &b, &c) ? 1 : 0;
+    out9[1] = a; out9[2] = b; out9[3] = c;
+    a = b = 0;
+    out9[4] = wide_geometry(cols, &a, &b) ? 1 : 0;
+    out9[5] = a; out9[6] = b;
+    a = b = 0;
+    out9[7] = flex_geometry(cols, &a, &b) ? 1 : 0;
+    out9[8] = a;
+    return IPTQ_OK;
+}
+
 // Exponentials of an array of stabilised scores (row maximum 0) through both arithmetic
 // paths of the softmax kernels: out32 from the 32-bit lanes, out16 from the packed 16-bit
 // lanes (pairs (2i, 2i+1); 0xFFFFFFFF where the plan does not enable that path).  n even.

@@ -235,3 +235,48 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(b, "_LIB_PATH", os.path.join(ROOT, "no_such_dir", "libiptq.so"))
     with pytest.raises(ImportError):
         b.load()
+
+
+def test_run_time_row_length_layouts_fit_what_the_kernels_assume():
+    """For every row length: the lane layout the host picks for the run-time-row-length
+    kernels satisfies what their indexing relies on (blocks per lane within the compiled
+    slot count, chunk passes within the unrolled loop, LDS within a workgroup's 64 KB)."""
+    import ctypes
+    fn = ip.load().iptq_debug_softmax_layout
+    fn.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
+    fn.restype = ctypes.c_int
+    out = (ctypes.c_int32 * 9)()
+    served_by_registers = 0
+    for cols in list(range(1, 6200)) + [8191, 8192, 13000, 13107, 13108, 20000, 65535, 65536]:
+        assert fn(cols, out) == 0
+        dyn_ok, k, slots, n_used, wide_ok, passes, wslots, flex_ok, log2l = list(out)
+        # blocks a row can touch at its worst alignment inside a 16-byte grid
+        if cols % 4 == 0:
+            nb_max = cols // 4
+        elif cols % 2 == 0:
+            nb_max = (cols + 2 + 3) // 4
+        else:
+            nb_max = (cols + 3 + 3) // 4
+        assert nb_max >= max(((phi + cols + 3) >> 2) for phi in range(0, 4, 4 if cols % 4 == 0 else (2 if cols % 2 == 0 else 1)))
+        if dyn_ok:
+            assert k in (2, 4, 8, 16) and slots in (8, 13) and (slots == 8 or k == 16)
+            assert 1 <= n_used <= slots and k * n_used >= nb_max
+            rpw = 64 // k
+            assert (rpw * cols) % 4 == 0                     # a slab starts on a 16-byte boundary
+            in_chunks = rpw * cols // 4
+            assert in_chunks <= 64 * n_used                  # the unrolled copy loop covers the slab
+            wave_lds = ((rpw * cols * 4 + 15) & ~15) + 144
+            assert wave_lds <= 65536
+        else:
+            assert nb_max > 16 * 13
+        if wide_ok:
+            assert wslots in (8, 13, 16, 20) and 1 <= passes <= wslots and 64 * passes >= nb_max
+        else:
+            assert nb_max > 64 * 20
+        if flex_ok:
+            lanes, rpw = 1 << log2l, 64 >> log2l
+            assert (rpw * cols) % 4 == 0 and rpw * cols * 5 <= 65536
+        else:
+            assert cols * 5 > 65536 or cols % 4 != 0 and cols * 4 * 5 > 65536 or cols % 2 != 0
+        served_by_registers += bool(dyn_ok or wide_ok)
+    assert served_by_registers >= 5117
