@@ -52,8 +52,9 @@ extern "C" {
 #define IPTQ_ALGO_DYNAMIC 3 /* softmax only: the register-resident kernel with run-time row length
                                (rows up to about 830 scores), also where a compiled row length
                                would serve */
-#define IPTQ_ALGO_WIDE 4    /* softmax only: one wavefront per row, row in registers, no LDS staging
-                               (rows up to 5117 scores), also where another kernel would serve */
+#define IPTQ_ALGO_WIDE 4    /* softmax only: one wavefront (rows up to 4093 scores) or one workgroup
+                               (up to 40957) per row, row in registers, no LDS staging, also where
+                               another kernel would serve */
 
 /*
  * y = clamp(rshr_round(x * m, s) + zp, qmin, qmax)
@@ -152,7 +153,7 @@ int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t out_is_sig
  * 0 <= rows < 2^31 (0 is a no-op), 1 <= cols <= IPTQ_COLS_MAX.
  * Every shape gives the same bytes; speed depends on it.  Fastest: 16-byte aligned d_scores and
  * d_out (and d_bias, with bias_period_rows * cols a multiple of 4) and a row length of 197, 49,
- * 198, 144, 257 or 577; any other row length up to 5117 runs in the register-resident kernels
+ * 198, 144, 257 or 577; any other row length up to 40957 runs in the register-resident kernels
  * with a run-time row length, longer or unaligned ones in slower multi-pass kernels.
  */
 int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias, int64_t bias_period_rows,

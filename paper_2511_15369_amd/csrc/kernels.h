@@ -36,14 +36,18 @@ hipError_t softmax_flex_launch(const SoftmaxCall &c, int32_t cols, int post_mode
 // (*done == 0) if the row is too long or the pointers do not qualify.
 hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
                                   hipStream_t stream);
-// One wavefront per row, row in registers, no LDS staging (rows of up to 5117 scores): the
+// One wavefront per row, row in registers, no LDS staging (rows of up to 4093 scores): the
 // leading rows of one call (all of them unless the tensor ends off a 16-byte boundary).
 hipError_t softmax_wide_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
                                hipStream_t stream);
+// One workgroup per row, row in the workgroup's registers (rows of up to 40957 scores).
+hipError_t softmax_wgrow_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
+                                hipStream_t stream);
 // Host-side layout choices of the run-time-row-length kernels (false: the kernel does not
 // serve that row length).
 bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used);
 bool wide_geometry(int32_t cols, int *passes, int *slots);
+bool wgrow_geometry(int32_t cols, int *waves, int *slots);
 bool flex_geometry(int32_t cols, int *log2_lanes, int *wave_lds);
 hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stream);
 hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,

@@ -156,6 +156,10 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
                 err = softmax_wide_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
                 if (err != hipSuccess) break;
             }
+            if (done[i] == 0 && (c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_WIDE)) {
+                err = softmax_wgrow_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
+                if (err != hipSuccess) break;
+            }
             if (done[i] == 0 && c.algo != IPTQ_ALGO_GENERIC && c.algo != IPTQ_ALGO_WIDE) {
                 err = softmax_flex_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
                 if (err != hipSuccess) break;

@@ -178,12 +178,18 @@ IPTQ_DEV u16x2 bit_exp_pair(int32_t xa, int32_t xb, int32_t mx, const SoftmaxDev
 
 // The arithmetic of one wavefront's slab once its rows sit in registers: exponentials, row
 // sum, reciprocal, probabilities -> four output bytes per block in w[].
+// Row sum over the K lanes that share a row (the default reducer of softmax_slab_math).
+template <int K>
+struct LaneGroupSum {
+    IPTQ_DEV uint32_t operator()(uint32_t v) const { return group_sum_u32<K>(v); }
+};
+
 // DYN: only the first n_used slots hold row data (n_used is wavefront-uniform); the others
-// are skipped.
-template <int K, int SLOTS, int MODE, int VARIANT, int POSTMODE, bool DYN = false>
+// are skipped.  SUM: how the per-lane partial sums of a row are combined.
+template <int K, int SLOTS, int MODE, int VARIANT, int POSTMODE, bool DYN = false, class SUM = LaneGroupSum<K>>
 IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], int32_t mx,
                                 int32_t lower, bool any_low, const uint8_t *lut, const SoftmaxDev &P,
-                                int n_used = SLOTS)
+                                int n_used = SLOTS, const SUM &row_sum = SUM())
 {
     if (MODE != 0 && !any_low) {
         // ---- packed 16-bit path
@@ -198,7 +204,7 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
                 sum = __builtin_amdgcn_udot2(qe, (u16x2){1, 1}, sum, false);
                 e2[s][h] = __builtin_bit_cast(uint32_t, qe);
             }
-        sum = group_sum_u32<K>(sum);
+        sum = row_sum(sum);
         const uint32_t f_top = floor_pow2_div(P.m_bits, sum) << (24 - P.p_shift);   // < 2^24
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
@@ -234,7 +240,7 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
                     sum += q;
                 }
         }
-        sum = group_sum_u32<K>(sum);
+        sum = row_sum(sum);
         const uint32_t f = floor_pow2_div(P.m_bits, sum);
         const uint32_t f_top = P.p_shift <= 24 ? f << (24 - P.p_shift) : 0u;
 #pragma unroll

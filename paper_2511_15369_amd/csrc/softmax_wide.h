@@ -177,6 +177,5 @@ static void wide_launch_s(const WideArgs &A, int mode, int post_mode, dim3 grid,
 void wide_launch_s8(const WideArgs &A, int mode, int post_mode, dim3 grid, hipStream_t stream);
 void wide_launch_s13(const WideArgs &A, int mode, int post_mode, dim3 grid, hipStream_t stream);
 void wide_launch_s16(const WideArgs &A, int mode, int post_mode, dim3 grid, hipStream_t stream);
-void wide_launch_s20(const WideArgs &A, int mode, int post_mode, dim3 grid, hipStream_t stream);
 
 }  // namespace iptq

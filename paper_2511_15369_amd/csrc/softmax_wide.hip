@@ -6,18 +6,20 @@
 namespace iptq {
 
 // Passes of 64 blocks a row of `cols` scores needs at its worst alignment, and the compiled
-// pass count that serves it.  Returns false beyond 20 passes.
+// pass count that serves it.  Returns false beyond 16 passes (rows of more than 4093 scores):
+// with more registers per lane than that a workgroup per row is faster (softmax_wgrow.h;
+// 5117 columns: 63 % against 55 % of the HBM roofline).
 bool wide_geometry(int32_t cols, int *passes, int *slots)
 {
     const int nb_max = (cols % 4 == 0) ? cols / 4 : ((cols % 2 == 0) ? (cols + 2 + 3) / 4 : (cols + 3 + 3) / 4);
     const int n = (nb_max + 63) / 64;
-    if (n > 20) return false;
+    if (n > 16) return false;
     *passes = n;
-    *slots = n <= 8 ? 8 : (n <= 13 ? 13 : (n <= 16 ? 16 : 20));
+    *slots = n <= 8 ? 8 : (n <= 13 ? 13 : 16);
     return true;
 }
 
-// Most rows of one call if the call qualifies: rows of up to 5117 scores, 16-byte aligned
+// Most rows of one call if the call qualifies: rows of up to 4093 scores, 16-byte aligned
 // tensors.  When the tensor does not end on a 16-byte boundary its last row is left out (its
 // final block would reach beyond the tensor); *done receives the number of leading rows served.
 hipError_t softmax_wide_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
@@ -39,8 +41,7 @@ hipError_t softmax_wide_launch(const SoftmaxCall &c, int32_t cols, int post_mode
     const int mode = c.P.mode16;
     if (slots == 8) wide_launch_s8(A, mode, post_mode, grid, stream);
     else if (slots == 13) wide_launch_s13(A, mode, post_mode, grid, stream);
-    else if (slots == 16) wide_launch_s16(A, mode, post_mode, grid, stream);
-    else wide_launch_s20(A, mode, post_mode, grid, stream);
+    else wide_launch_s16(A, mode, post_mode, grid, stream);
     *done = rows;
     return hipGetLastError();
 }
