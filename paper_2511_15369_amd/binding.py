@@ -18,6 +18,8 @@ _lib = None
 
 ALGO_AUTO = 0
 ALGO_GENERIC = 1
+ALGO_DYNAMIC = 2
+ALGO_WIDE = 3
 
 
 class IptqError(RuntimeError):

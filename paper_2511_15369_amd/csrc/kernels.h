@@ -28,10 +28,6 @@ struct GeluCall {
 };
 
 hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols, hipStream_t stream);
-// Run-time-row-length slab kernel on the leading rows of one call that fill whole slabs;
-// *done receives how many rows it took (0 if the shape or the pointers do not qualify).
-hipError_t softmax_flex_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
-                               hipStream_t stream);
 // Register-resident slab kernel with a run-time row length: every row of one call, or none
 // (*done == 0) if the row is too long or the pointers do not qualify.
 hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
@@ -48,7 +44,6 @@ hipError_t softmax_wgrow_launch(const SoftmaxCall &c, int32_t cols, int post_mod
 bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used);
 bool wide_geometry(int32_t cols, int *passes, int *slots);
 bool wgrow_geometry(int32_t cols, int *waves, int *slots);
-bool flex_geometry(int32_t cols, int *log2_lanes, int *wave_lds);
 hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stream);
 hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,
                              bool force_direct, hipStream_t stream);

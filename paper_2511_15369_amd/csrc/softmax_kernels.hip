@@ -160,10 +160,6 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
                 err = softmax_wgrow_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
                 if (err != hipSuccess) break;
             }
-            if (done[i] == 0 && c.algo != IPTQ_ALGO_GENERIC && c.algo != IPTQ_ALGO_WIDE) {
-                err = softmax_flex_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
-                if (err != hipSuccess) break;
-            }
             err = launch_generic(c.scores, c.bias, c.out, done[i], c.rows, cols, c.bias != nullptr,
                                  has_pre, c.P, stream);
         }

@@ -62,7 +62,7 @@ def test_softmax_random_domain(seed):
             bias = np.rint(rng.standard_normal((period, cols)) * 2.0 * i0).astype(np.int32)
             bias[rng.random((period, cols)) < 0.02] = I32_MIN
         want = ref.softmax_i32(x, p, bias, period)
-        for algo in (0, 1, 2, 3, 4):
+        for algo in (0, 1, 2, 3):
             got = gpu_softmax(x, p, bias, period, algo=algo)
             assert np.array_equal(got, want), (algo, cols, rows, p)
 

@@ -249,7 +249,7 @@ def test_run_time_row_length_layouts_fit_what_the_kernels_assume():
     served_by_registers = 0
     for cols in list(range(1, 6200)) + [8191, 8192, 13000, 13107, 13108, 20000, 65535, 65536]:
         assert fn(cols, out) == 0
-        dyn_ok, k, slots, n_used, wide_ok, passes, wslots, flex_ok, log2l, wg_ok, waves, gslots = list(out)
+        dyn_ok, k, slots, n_used, wide_ok, passes, wslots, _unused0, _unused1, wg_ok, waves, gslots = list(out)
         # blocks a row can touch at its worst alignment inside a 16-byte grid
         if cols % 4 == 0:
             nb_max = cols // 4
@@ -278,10 +278,5 @@ def test_run_time_row_length_layouts_fit_what_the_kernels_assume():
             assert 64 * waves * gslots >= nb_max             # the row fits the workgroup's registers
         else:
             assert nb_max > 512 * 20
-        if flex_ok:
-            lanes, rpw = 1 << log2l, 64 >> log2l
-            assert (rpw * cols) % 4 == 0 and rpw * cols * 5 <= 65536
-        else:
-            assert cols * 5 > 65536 or cols % 4 != 0 and cols * 4 * 5 > 65536 or cols % 2 != 0
         served_by_registers += bool(dyn_ok or wide_ok or wg_ok)
     assert served_by_registers >= 6199
