@@ -107,8 +107,9 @@ typedef struct {
  *   5. w = q * v
  *   6. y = clamp(rshr_round(w * post.m, post.s) + post.zp, post.qmin, post.qmax)
  * Domain: q_b < 0 (|q_b| < 2^15 for p = 4, <= 2^30 for p = 2); q_c < 0; 0 <= k <= 62;
- * max_abs_q >= 1; ((|q_b|^p + 2|q_c|) >> k) * max_abs_q < 2^31 and |q_b|^p < 2^61,
- * |q_c| < 2^60 (else IPTQ_ERR_RANGE); for the int8 entry |zp_in| <= 128.
+ * max_abs_q >= 1; ceil((|q_b|^p + 2|q_c|) / 2^k) * max_abs_q < 2^31 (so that q * v fits int32: a
+ * negative numerator is floored away from zero) and |q_b|^p < 2^61, |q_c| < 2^60 (else
+ * IPTQ_ERR_RANGE); for the int8 entry |zp_in| <= 128.
  */
 typedef struct {
     int32_t variant;

@@ -230,7 +230,8 @@ static int gelu_params_ok(const orc_gelu_params *p)
     if (p->k < 0 || p->k > 62) return 0;
     if (p->max_abs_q < 1) return 0;
     if (p->pre_m < 1 || p->pre_m >= 32768 || p->pre_s < 0 || p->pre_s > 62) return 0;
-    /* |q_b|^p + 2|q_c| must stay inside int64 and (that >> k) * max_abs_q inside int32 */
+    /* |q_b|^p + 2|q_c| must stay inside int64 and q * v inside int32: |v| is at most that sum
+       divided by 2^k and rounded UP (a negative numerator is floored away from zero) */
     const int64_t lim = (int64_t)1 << 62;
     int64_t t = -(int64_t)p->q_b;
     if (t > ((int64_t)1 << 30)) return 0;
@@ -240,7 +241,7 @@ static int gelu_params_ok(const orc_gelu_params *p)
         tp = tp * tp;
     }
     if (-p->q_c >= lim / 4 || tp >= lim / 2) return 0;
-    int64_t vmax = (tp + 2 * (-p->q_c)) >> p->k;
+    int64_t vmax = (tp + 2 * (-p->q_c) + (((int64_t)1 << p->k) - 1)) >> p->k;
     if (vmax >= ((int64_t)1 << 31)) return 0;
     if (vmax * (int64_t)p->max_abs_q >= ((int64_t)1 << 31)) return 0;
     return dyadic_ok(&p->post, 1);

@@ -61,7 +61,8 @@ def gelu_prepare(s_in: float, s_out: float, zp_in: int, zp_out: int, variant: in
                  max_abs_q: int = 255) -> GeluParams:
     """S_e = s_in / sqrt(2); q_b = floor(b / S_e); S_L = a * S_e^p with the power
     formed as (S_e*S_e) or (S_e*S_e)*(S_e*S_e); q_c = floor(1 / S_L);
-    k = smallest shift with ((|q_b|^p + 2|q_c|) >> k) * max_abs_q < 2^31;
+    k = smallest shift with ceil((|q_b|^p + 2|q_c|) / 2^k) * max_abs_q < 2^31 (the ceiling:
+    a negative numerator is floored away from zero, so |v| can reach it);
     output ratio = ((s_in * S_L) * 2^k / 2) / s_out -> dyadic (negative m)."""
     p, a, b = POLY[variant]
     s_e = s_in / math.sqrt(2.0)
@@ -71,7 +72,7 @@ def gelu_prepare(s_in: float, s_out: float, zp_in: int, zp_out: int, variant: in
     q_c = int(math.floor(1.0 / s_l))
     vmax = abs(q_b) ** p + 2 * abs(q_c)
     k = 0
-    while (vmax >> k) * max_abs_q >= (1 << 31):
+    while -((-vmax) >> k) * max_abs_q >= (1 << 31):
         k += 1
     ratio = ((s_in * s_l) * math.ldexp(1.0, k) / 2.0) / s_out
     m, s = make_dyadic(ratio)

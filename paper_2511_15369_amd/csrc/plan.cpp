@@ -187,7 +187,8 @@ int plan_gelu(const iptq_gelu_params_t *p, int is_i8_entry, GeluDev *out)
     int64_t tp = t * t;
     if (quartic) tp *= tp;
     if (tp >= ((int64_t)1 << 61) || -p->q_c >= ((int64_t)1 << 60)) return IPTQ_ERR_RANGE;
-    const int64_t vmax = (tp + 2 * (-p->q_c)) >> p->k;
+    // |v| <= ceil((|q_b|^p + 2|q_c|) / 2^k): a negative numerator is floored away from zero
+    const int64_t vmax = (tp + 2 * (-p->q_c) + (((int64_t)1 << p->k) - 1)) >> p->k;
     if (vmax >= ((int64_t)1 << 31)) return IPTQ_ERR_RANGE;
     if (vmax * (int64_t)p->max_abs_q >= ((int64_t)1 << 31)) return IPTQ_ERR_RANGE;
     out->quartic = quartic;
@@ -290,9 +291,9 @@ extern "C" int iptq_gelu_prepare(double s_in, double s_out, int32_t zp_in, int32
     if (p == 4) tp *= tp;
     const int64_t vmax = tp + 2 * (-q_c);
     int k = 0;
-    while (k < 62 && (unsigned __int128)(vmax >> k) * (unsigned __int128)max_abs_q >=
-                         ((unsigned __int128)1 << 31))
-        ++k;
+    // smallest k with ceil(vmax / 2^k) * max_abs_q < 2^31 (|v| can reach the ceiling)
+    auto v_bound = [&](int kk) { return (unsigned __int128)((vmax + (((int64_t)1 << kk) - 1)) >> kk); };
+    while (k < 62 && v_bound(k) * (unsigned __int128)max_abs_q >= ((unsigned __int128)1 << 31)) ++k;
     const double ratio = ((s_in * s_l) * ldexp(1.0, k) / 2.0) / s_out;
     int32_t m = 0, s = 0;
     int rc = iptq_make_dyadic(ratio, &m, &s);

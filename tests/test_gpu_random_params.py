@@ -81,7 +81,7 @@ def test_gelu_random_domain(seed):
         if tp >= 2 ** 61:
             continue
         k = 0
-        while ((tp + 2 * -q_c) >> k) * max_abs_q >= 2 ** 31:
+        while -(-(tp + 2 * -q_c) >> k) * max_abs_q >= 2 ** 31:     # ceiling: |v| can reach it
             k += 1
         if k > 62:
             continue

@@ -192,6 +192,12 @@ def test_gelu_and_requant_argument_errors_without_a_gpu():
         setattr(bad, field, val)
         assert lib.iptq_gelu_i8(None, None, 0, ctypes.byref(bad), None) == code, field
     assert lib.iptq_gelu_i32(ctypes.c_void_p(2), ctypes.c_void_p(64), 4, ctypes.byref(good), None) == -6
+    # the range condition uses the ceiling of (|q_b|^p + 2|q_c|) / 2^k: here the floor bound
+    # (2147 * 10^6 < 2^31) would pass while v reaches -2148
+    edge = ref.GeluParams(1, -13, -140711946, 17, 100, 10 ** 6, 1, 0, ref.Dyadic(18658, 45, -104, -128, 127))
+    assert lib.iptq_gelu_i32(None, None, 0, ctypes.byref(lib_gelu(edge)), None) == -4
+    edge.k = 18
+    assert lib.iptq_gelu_i32(None, None, 0, ctypes.byref(lib_gelu(edge)), None) == 0
     d = ip.Dyadic(1, 0, 0, 0, 255)
     assert lib.iptq_requant(None, None, 0, 0, ctypes.byref(d), None) == 0
     assert lib.iptq_requant(None, None, 3, 0, ctypes.byref(d), None) == -1

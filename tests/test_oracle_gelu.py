@@ -129,3 +129,49 @@ def test_rejects_bad_params():
             continue
         with pytest.raises(ref.OracleError):
             ref.gelu_i8(x, bad)
+
+
+def test_range_condition_bounds_the_product_for_floored_negative_values():
+    """v = (numerator >> k) floors a negative numerator away from zero, so |v| can be one more
+    than (|q_b|^p + 2|q_c|) >> k: the admissible k must be judged by the ceiling.  The first
+    parameter set is the boundary case a random GPU sweep found (floor bound 2147 * 10^6 <
+    2^31, but v = -2148 at q = 10^6)."""
+    post = ref.Dyadic(18658, 45, -104, -128, 127)
+    x = np.array([10 ** 6 + 100, -(10 ** 6), 0, 5], dtype=np.int32)
+    at_floor_bound = ref.GeluParams(1, -13, -140711946, 17, 100, 10 ** 6, 1, 0, post)
+    with pytest.raises(ref.OracleError):
+        ref.gelu_i32(x, at_floor_bound)
+    ok = ref.GeluParams(1, -13, -140711946, 18, 100, 10 ** 6, 1, 0, post)
+    ref.gelu_i32(x, ok)
+    # for accepted parameter sets q * v stays inside int32 at every q that can maximise it
+    rng = np.random.default_rng(77)
+    checked = 0
+    while checked < 300:
+        variant = int(rng.integers(0, 2))
+        q_b = -int(rng.integers(1, 2 ** int(rng.integers(2, 15 if variant else 30))))
+        q_c = -int(rng.integers(1, 2 ** int(rng.integers(2, 60))))
+        max_abs_q = int(rng.choice([1, 127, 255, 4000, 10 ** 6]))
+        tp = q_b ** (4 if variant else 2)
+        if tp >= 2 ** 61:
+            continue
+        k = 0
+        while ((tp + 2 * -q_c) >> k) * max_abs_q >= 2 ** 31:      # the floor bound on purpose
+            k += 1
+        if k > 62:
+            continue
+        p = ref.GeluParams(variant, q_b, q_c, k, 0, max_abs_q, 1, 0, ref.Dyadic(1, 0, 0, -128, 127))
+        try:
+            ref.gelu_i32(np.zeros(1, np.int32), p)
+        except ref.OracleError:
+            # rejected: the ceiling bound must be what failed
+            assert -(-(tp + 2 * -q_c) >> k) * max_abs_q >= 2 ** 31
+            checked += 1
+            continue
+        worst = 0
+        for q in (max_abs_q, -max_abs_q, min(max_abs_q, -q_b), -min(max_abs_q, -q_b), 1, -1):
+            t = min(abs(q), -q_b) + q_b
+            u = t ** (4 if variant else 2) + q_c
+            v = ((1 if q > 0 else -1) * u + q_c) >> k
+            worst = max(worst, abs(q * v))
+        assert worst < 2 ** 31
+        checked += 1

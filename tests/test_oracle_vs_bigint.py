@@ -118,7 +118,7 @@ def test_gelu_random_parameters(seed):
         if tp >= 2 ** 61:
             continue
         k = 0
-        while ((tp + 2 * -q_c) >> k) * max_abs_q >= 2 ** 31:
+        while -(-(tp + 2 * -q_c) >> k) * max_abs_q >= 2 ** 31:     # ceiling: |v| can reach it
             k += 1
         k = min(62, k + int(rng.integers(0, 3)))
         post = ref.Dyadic(int(rng.integers(-32767, 32768)), int(rng.integers(0, 63)),
