@@ -17,10 +17,10 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libiptq.so")
 # the slowest translation units first (the pool takes them in this order)
 SOURCES = ["softmax_wgrow_w8_s20.hip", "softmax_wgrow_w4_s20.hip", "softmax_wgrow_w8_s16.hip", "softmax_wgrow_w4_s13.hip",
-           "softmax_wide_s16.hip", "softmax_wide_s13.hip", "softmax_wide_s8.hip", "softmax_rowsdyn_k16_s13.hip",
+           "softmax_wide_s16.hip", "softmax_wide_s13.hip", "softmax_wide_s8.hip", "softmax_rowsdyn_k16_long.hip",
            "softmax_rows_577.hip", "softmax_rows_257.hip", "softmax_rows_197.hip", "softmax_rows_198.hip",
            "softmax_rows_144.hip", "softmax_rows_49.hip", "softmax_rows_197_k8.hip", "softmax_rows_198_k8.hip",
-           "softmax_rowsdyn_k2.hip", "softmax_rowsdyn_k4.hip", "softmax_rowsdyn_k8.hip",
+           "softmax_rowsdyn_k2.hip", "softmax_rowsdyn_k2_short.hip", "softmax_rowsdyn_k4.hip", "softmax_rowsdyn_k8.hip",
            "softmax_rowsdyn_k16.hip", "softmax_kernels.hip", "elementwise_kernels.hip",
            "softmax_rowsdyn.hip", "softmax_wide.hip", "softmax_wgrow.hip", "api.hip", "plan.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

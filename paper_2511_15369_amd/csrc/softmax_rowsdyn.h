@@ -1,10 +1,17 @@
 // Integer softmax (Section 4.4, Eq. 6-15) for row lengths that have no compiled
 // instantiation: the slab scheme and the register-resident arithmetic of the
 // fixed-row-length kernel (softmax_rows.h) with the row length as a run-time value.  What is
-// fixed at compile time is the lane layout: K lanes per row and at most SLOTS 16-byte blocks
-// per lane, i.e. rows of up to about 4 K SLOTS columns (830 at most); the host picks the smallest layout
-// that holds the row.  Slots beyond the row's last block are skipped by wavefront-uniform
-// branches, element masks are computed for every block, and the slab lives in dynamic LDS.
+// fixed at compile time is the lane layout: K lanes per row and exactly SLOTS 16-byte blocks
+// per lane, SLOTS = ceil(B / K) with B the most blocks a row of that length can touch.  That
+// pins down everything the code's shape depends on:
+//   * a row touches B or B - 1 blocks, so the blocks of slots 0 .. SLOTS-2 exist in every
+//     row and only the last slot's block index needs a clamp;
+//   * a row's last (possibly cut) block lies in slot SLOTS-2 or SLOTS-1, its first in slot 0:
+//     element masks and byte-wise output are confined to those three slots;
+//   * the slab is SLOTS or SLOTS-1 passes of 64 chunks, of which all but the last two are
+//     full: only those two clamp their chunk index.
+// So the kernel has no branch that depends on the row length apart from lane predicates on
+// LDS writes; the host instantiates one kernel per (K, SLOTS) and picks by row length.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -25,12 +32,12 @@ struct DynArgs {
     int64_t n_slabs;      // the last one may be partial
     int32_t tail_rows;    // rows of the last slab if it is partial, else 0
     int32_t cols;
-    int32_t n_used;       // blocks per lane that can hold row data: ceil(max blocks per row / K)
     int32_t wave_lds;     // LDS bytes per wavefront: slab (16-byte multiple) + post table
+    int32_t post_mode;    // PM_NONE / PM_CLAMP127 / PM_GENERAL, applied to the packed bytes
     SoftmaxDev P;
 };
 
-template <int K, int SLOTS, int MODE, int POSTMODE>
+template <int K, int SLOTS, int MODE>
 __global__ void __launch_bounds__(256)
 softmax_rowsdyn_kernel(DynArgs A)
 {
@@ -43,12 +50,12 @@ softmax_rowsdyn_kernel(DynArgs A)
     if (slab >= A.n_slabs) return;                    // no workgroup barrier below
 
     const int cols = A.cols;
-    const int n_used = A.n_used;                      // <= SLOTS (host)
     const int slab_el = RPW * cols;                   // multiple of 4
-    const int in_chunks = slab_el >> 2;               // <= 64 * n_used
+    const int in_chunks = slab_el >> 2;               // in (64 (SLOTS-2), 64 SLOTS]
     uint8_t *lds = dyn_lds + wv * A.wave_lds;
     uint8_t *lut = lds + A.wave_lds - kPostLutBytes;
-    if (POSTMODE == PM_GENERAL) {                     // ordered before its use by the fences below
+    const int post_mode = A.post_mode;
+    if (post_mode == PM_GENERAL) {                    // ordered before its use by the fences below
         const int p_max = 1 << (P.m_bits - P.p_shift);
         for (int p = lane; p <= p_max; p += 64) lut[p] = (uint8_t)post_dev<PM_GENERAL>((uint32_t)p, P);
     }
@@ -59,9 +66,8 @@ softmax_rowsdyn_kernel(DynArgs A)
     const int valid_el = (partial ? A.tail_rows : RPW) * cols;
 
     // ---- flat copy of the slab into LDS, bias added on the way.  Every load is issued before
-    // the first LDS write: lanes beyond the slab's last chunk load its last chunk again (no
-    // lane-divergent branch around a load), whole unused passes are skipped by uniform
-    // branches, and the two wavefront-uniform choices are made outside the loops.
+    // the first LDS write and none sits behind a branch: in the last two passes the lanes
+    // beyond the slab's last chunk load that chunk again and write it to its place again.
     auto add_bias = [](i32x4 v, const i32x4 bv) {
         v.x = v.x == kI32Min ? v.x : sat_add_i32(v.x, bv.x);
         v.y = v.y == kI32Min ? v.y : sat_add_i32(v.y, bv.y);
@@ -72,6 +78,11 @@ softmax_rowsdyn_kernel(DynArgs A)
     auto copy_in = [&](auto bias_tag) {
         constexpr bool BIAS = decltype(bias_tag)::value;
         i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
+        const int last = in_chunks - 1;
+        auto chunk_of = [&](int i) {
+            const int idx = i * 64 + lane;
+            return i >= SLOTS - 2 ? min(idx, last) : idx;
+        };
         uint32_t boff = 0;
         if (BIAS) boff = row_mod_period((uint32_t)(slab * RPW), P) * (uint32_t)cols;
         const uint32_t pe = (uint32_t)P.bias_period_rows * (uint32_t)cols;
@@ -79,28 +90,22 @@ softmax_rowsdyn_kernel(DynArgs A)
         // keeps the staging registers at 4 * (SLOTS + kAhead)
         constexpr int kAhead = 4;
         auto bias_chunk = [&](int i) {
-            const int idx = min(i * 64 + lane, in_chunks - 1);
-            uint32_t o = boff + 4u * (uint32_t)idx;
+            uint32_t o = boff + 4u * (uint32_t)chunk_of(i);
             if (o >= pe) o -= pe;
             return *reinterpret_cast<const i32x4 *>(bias + o);
         };
         i32x4 v[SLOTS], bv[BIAS ? kAhead : 1];
 #pragma unroll
-        for (int i = 0; i < SLOTS; ++i)
-            if (i * 64 < in_chunks) v[i] = stream_load(src + min(i * 64 + lane, in_chunks - 1));
+        for (int i = 0; i < SLOTS; ++i) v[i] = stream_load(src + chunk_of(i));
         if (BIAS) {
 #pragma unroll
-            for (int i = 0; i < kAhead && i < SLOTS; ++i)
-                if (i * 64 < in_chunks) bv[i] = bias_chunk(i);
+            for (int i = 0; i < kAhead && i < SLOTS; ++i) bv[i] = bias_chunk(i);
         }
 #pragma unroll
         for (int i = 0; i < SLOTS; ++i) {
-            if (i * 64 < in_chunks) {
-                const int idx = i * 64 + lane;
-                const i32x4 t = BIAS ? add_bias(v[i], bv[BIAS ? i % kAhead : 0]) : v[i];
-                if (BIAS && i + kAhead < SLOTS && (i + kAhead) * 64 < in_chunks) bv[i % kAhead] = bias_chunk(i + kAhead);
-                if (idx < in_chunks) lds4[idx] = t;
-            }
+            const i32x4 t = BIAS ? add_bias(v[i], bv[BIAS ? i % kAhead : 0]) : v[i];
+            if (BIAS && i + kAhead < SLOTS) bv[i % kAhead] = bias_chunk(i + kAhead);
+            lds4[chunk_of(i)] = t;
         }
         wave_lds_fence();
     };
@@ -140,21 +145,17 @@ softmax_rowsdyn_kernel(DynArgs A)
     const int b_r = e_r >> 2;                         // its 16-byte block
     const int phi = e_r & 3;                          // and its offset inside that block
     const int nb = (phi + cols + 3) >> 2;             // blocks the row touches
+    auto edge_slot = [](int s) { return s == 0 || s >= SLOTS - 2; };
     int32_t x[SLOTS][4];
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
-        if (s >= n_used) {
-            x[s][0] = x[s][1] = x[s][2] = x[s][3] = kI32Min;
-            continue;
-        }
         const int b = s * K + j;
-        // blocks beyond the row's last one are read from its last one and masked entirely below
-        // (4 b - phi >= cols there): no lane-divergent branch around the LDS read
-        const i32x4 v = reinterpret_cast<const i32x4 *>(lds)[b_r + min(b, nb - 1)];
+        // a block beyond the row's last one (last slot only) is read from the last one and
+        // masked entirely below: no lane-divergent branch around the LDS read
+        const int bb = s == SLOTS - 1 ? min(b, nb - 1) : b;
+        const i32x4 v = reinterpret_cast<const i32x4 *>(lds)[b_r + bb];
         x[s][0] = v.x; x[s][1] = v.y; x[s][2] = v.z; x[s][3] = v.w;
-        // only a row's first block and the slots that can reach its end need element masks
-        // (wavefront-uniform test)
-        if (s == 0 || 4 * (s * K + K - 1) + 3 >= cols) {
+        if (edge_slot(s)) {
             const int c0 = 4 * b - phi;
 #pragma unroll
             for (int e = 0; e < 4; ++e)
@@ -168,53 +169,55 @@ softmax_rowsdyn_kernel(DynArgs A)
         const int32_t pre_mul = P.pre_mul, pre_sh2 = P.pre_sh2;
         const int64_t pre_rnd = P.pre_rnd;
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) {
-            if (s >= n_used) continue;
+        for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int32_t r = pre_requant_narrow(x[s][e], pre_mul, pre_rnd, pre_sh2);
                 x[s][e] = x[s][e] == kI32Min ? kI32Min : r;
             }
-        }
     } else if (P.pre_mode == 2) {                     // shifts below 16: the general 64-bit form
         const int32_t pre_m = P.pre_m, pre_s = P.pre_s;
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) {
-            if (s >= n_used) continue;
+        for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int32_t r = pre_requant_dev(x[s][e], pre_m, pre_s);
                 x[s][e] = x[s][e] == kI32Min ? kI32Min : r;
             }
-        }
     }
 
     // ---- Eq. 6: row maximum
     int32_t mx = kI32Min;
 #pragma unroll
-    for (int s = 0; s < SLOTS; ++s) {
-        if (s >= n_used) continue;
+    for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
         for (int e = 0; e < 4; ++e) mx = max(mx, x[s][e]);
-    }
     mx = group_max_i32<K>(mx);
 
     const int32_t D = P.d_clamp;
     const bool low_row = mx < kI32Min + D;            // see softmax_rows_kernel
     const int32_t lower = low_row ? kI32Min : mx - D;
     const bool any_low = __builtin_amdgcn_ballot_w64(low_row) != 0;
-    uint32_t w[SLOTS];                                // four output bytes per block
+    uint32_t w[SLOTS];                                // four probabilities per block, one per byte
 
-    if (P.variant == 0) softmax_slab_math<K, SLOTS, MODE, 0, POSTMODE, true>(x, w, mx, lower, any_low, lut, P, n_used);
-    else softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE, true>(x, w, mx, lower, any_low, lut, P, n_used);
+    if (P.variant == 0) softmax_slab_math<K, SLOTS, MODE, 0, PM_NONE>(x, w, mx, lower, any_low, lut, P);
+    else softmax_slab_math<K, SLOTS, MODE, 1, PM_NONE>(x, w, mx, lower, any_low, lut, P);
+
+    // ---- post step on the packed bytes (a probability is at most 128)
+    if (post_mode == PM_CLAMP127) {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) w[s] = clamp127_bytes(w[s]);
+    } else if (post_mode == PM_GENERAL) {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) w[s] = post_lut_gather(lut, w[s]);
+    }
 
     // ---- assemble the slab's bytes in LDS
     uint32_t *lds32 = reinterpret_cast<uint32_t *>(lds);
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
-        if (s >= n_used) continue;
         const int b = s * K + j;
-        if (s != 0 && 4 * (s * K + K - 1) + 3 < cols) {   // every lane's block lies inside its row
+        if (!edge_slot(s)) {                          // every lane's block lies inside its row
             lds32[b_r + b] = w[s];
         } else if (b < nb) {
             const int c0 = 4 * b - phi;
@@ -262,42 +265,24 @@ softmax_rowsdyn_kernel(DynArgs A)
     }
 }
 
+// mode: SoftmaxDev::mode16 (2 covers 1: t16 == 0 shifts by 0)
 template <int K, int SLOTS>
-static void rowsdyn_launch_ks(const DynArgs &A, int mode, int post_mode, dim3 grid, dim3 block, size_t lds,
-                              hipStream_t stream)
+static void rowsdyn_launch_ks(const DynArgs &A, int mode, dim3 grid, dim3 block, size_t lds, hipStream_t stream)
 {
-#define IPTQ_DYN_LAUNCH(MODE, PM)                                                                 \
-    hipLaunchKernelGGL((softmax_rowsdyn_kernel<K, SLOTS, MODE, PM>), grid, block, lds, stream, A)
-    if (mode == 0) {
-        if (post_mode == PM_NONE) IPTQ_DYN_LAUNCH(0, PM_NONE);
-        else if (post_mode == PM_CLAMP127) IPTQ_DYN_LAUNCH(0, PM_CLAMP127);
-        else IPTQ_DYN_LAUNCH(0, PM_GENERAL);
-    } else {                                          // 2 covers 1: t16 == 0 shifts by 0
-        if (post_mode == PM_NONE) IPTQ_DYN_LAUNCH(2, PM_NONE);
-        else if (post_mode == PM_CLAMP127) IPTQ_DYN_LAUNCH(2, PM_CLAMP127);
-        else IPTQ_DYN_LAUNCH(2, PM_GENERAL);
-    }
-#undef IPTQ_DYN_LAUNCH
+    if (mode == 0) hipLaunchKernelGGL((softmax_rowsdyn_kernel<K, SLOTS, 0>), grid, block, lds, stream, A);
+    else hipLaunchKernelGGL((softmax_rowsdyn_kernel<K, SLOTS, 2>), grid, block, lds, stream, A);
 }
 
-// One launcher per lane count, each defined in its own translation unit so that the
-// instantiations compile in parallel: 8 blocks per lane for every lane count
-// (softmax_rowsdyn_k<K>.hip), 13 for 16 lanes per row (softmax_rowsdyn_k16_s13.hip).
-template <int K>
-void rowsdyn_launch_k(const DynArgs &A, int mode, int post_mode, dim3 grid, dim3 block, size_t lds,
-                      hipStream_t stream);
-template <> void rowsdyn_launch_k<2>(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
-template <> void rowsdyn_launch_k<4>(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
-template <> void rowsdyn_launch_k<8>(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
-template <> void rowsdyn_launch_k<16>(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
-void rowsdyn_launch_k16_s13(const DynArgs &, int, int, dim3, dim3, size_t, hipStream_t);
+// One launcher per group of layouts, each defined in its own translation unit so that the
+// instantiations compile in parallel.  Each returns false for a slot count it does not hold.
+bool rowsdyn_launch_k2_short(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);   // 1..4
+bool rowsdyn_launch_k2(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);         // 5..8
+bool rowsdyn_launch_k4(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);         // 5..8
+bool rowsdyn_launch_k8(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);         // 5..8
+bool rowsdyn_launch_k16(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);        // 5..8
+bool rowsdyn_launch_k16_long(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);   // 9..13
 
-#define IPTQ_DEFINE_ROWSDYN_LAUNCHER(K)                                                           \
-    template <>                                                                                   \
-    void rowsdyn_launch_k<K>(const DynArgs &A, int mode, int post_mode, dim3 grid, dim3 block, size_t lds, \
-                             hipStream_t stream)                                                  \
-    {                                                                                             \
-        rowsdyn_launch_ks<K, 8>(A, mode, post_mode, grid, block, lds, stream);                    \
-    }
+#define IPTQ_ROWSDYN_CASE(K, S)                                                                   \
+    case S: rowsdyn_launch_ks<K, S>(A, mode, grid, block, lds, stream); return true;
 
 }  // namespace iptq

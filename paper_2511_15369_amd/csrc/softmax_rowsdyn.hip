@@ -7,10 +7,10 @@
 namespace iptq {
 
 // Lane layout for a row length: the fewest lanes per row that keep the blocks per lane at or
-// below 8 (91 VGPRs, 5 wavefronts per SIMD; measured equal or better than up to 13 blocks on
-// fewer lanes), else 16 lanes per row with up to 13 blocks per lane (rows of up to about 830
-// scores).  Returns false for longer rows: one wavefront per row serves those better
-// (softmax_wide.h; measured 58 % against 32 % of the HBM roofline at 1025 columns).
+// below 8 (5 wavefronts per SIMD; measured equal or better than more blocks on fewer lanes),
+// else 16 lanes per row with up to 13 blocks per lane (rows of up to about 830 scores).
+// *slots is exactly ceil(most blocks a row can touch / lanes): the kernels rely on it.
+// Returns false for longer rows: one wavefront per row serves those better (softmax_wide.h).
 bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used)
 {
     const int nb_max = (cols % 4 == 0) ? cols / 4 : ((cols % 2 == 0) ? (cols + 2 + 3) / 4 : (cols + 3 + 3) / 4);
@@ -20,7 +20,7 @@ bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used)
     if (n > 13) return false;
     *lanes = k;
     *n_used = n;
-    *slots = n <= 8 ? 8 : 13;
+    *slots = n;
     return true;
 }
 
@@ -44,7 +44,7 @@ hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_m
     DynArgs A;
     A.scores = c.scores; A.bias = c.bias; A.out = c.out;
     A.n_slabs = n_slabs; A.tail_rows = (int32_t)(c.rows % rpw);
-    A.cols = cols; A.n_used = n_used;
+    A.cols = cols; A.post_mode = post_mode;
     A.wave_lds = (int32_t)((((int64_t)rpw * cols * 4 + 15) & ~(int64_t)15) + kPostLutBytes);
     A.P = c.P;
     int wpb = 65536 / A.wave_lds;                     // wavefronts per workgroup: 1..4
@@ -52,12 +52,14 @@ hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_m
     if (wpb < 1) return hipSuccess;
     const dim3 grid((unsigned)((n_slabs + wpb - 1) / wpb)), block(64 * wpb);
     const size_t lds = (size_t)A.wave_lds * wpb;
-    const int mode = (post_mode == PM_GENERAL && c.P.p_shift > 24) ? 0 : c.P.mode16;
-    if (slots == 13) rowsdyn_launch_k16_s13(A, mode, post_mode, grid, block, lds, stream);
-    else if (k == 2) rowsdyn_launch_k<2>(A, mode, post_mode, grid, block, lds, stream);
-    else if (k == 4) rowsdyn_launch_k<4>(A, mode, post_mode, grid, block, lds, stream);
-    else if (k == 8) rowsdyn_launch_k<8>(A, mode, post_mode, grid, block, lds, stream);
-    else rowsdyn_launch_k<16>(A, mode, post_mode, grid, block, lds, stream);
+    bool launched;
+    if (k == 2) launched = slots <= 4 ? rowsdyn_launch_k2_short(A, slots, c.P.mode16, grid, block, lds, stream)
+                                      : rowsdyn_launch_k2(A, slots, c.P.mode16, grid, block, lds, stream);
+    else if (k == 4) launched = rowsdyn_launch_k4(A, slots, c.P.mode16, grid, block, lds, stream);
+    else if (k == 8) launched = rowsdyn_launch_k8(A, slots, c.P.mode16, grid, block, lds, stream);
+    else launched = slots <= 8 ? rowsdyn_launch_k16(A, slots, c.P.mode16, grid, block, lds, stream)
+                               : rowsdyn_launch_k16_long(A, slots, c.P.mode16, grid, block, lds, stream);
+    if (!launched) return hipSuccess;                 // no such layout: the caller's next kernel serves it
     *done = c.rows;
     return hipGetLastError();
 }

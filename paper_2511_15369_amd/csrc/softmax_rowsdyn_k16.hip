@@ -1,6 +1,15 @@
-// Run-time-row-length softmax slab kernel, 16 lanes per row, up to 8 blocks per lane.
+// Run-time-row-length softmax slab kernel, 16 lanes per row, 5 to 8 blocks per lane.
 #include "softmax_rowsdyn.h"
 
 namespace iptq {
-IPTQ_DEFINE_ROWSDYN_LAUNCHER(16)
+bool rowsdyn_launch_k16(const DynArgs &A, int slots, int mode, dim3 grid, dim3 block, size_t lds, hipStream_t stream)
+{
+    switch (slots) {
+    IPTQ_ROWSDYN_CASE(16, 5)
+    IPTQ_ROWSDYN_CASE(16, 6)
+    IPTQ_ROWSDYN_CASE(16, 7)
+    IPTQ_ROWSDYN_CASE(16, 8)
+    default: return false;
+    }
 }
+}  // namespace iptq
