@@ -48,9 +48,9 @@ extern "C" {
 #define IPTQ_ALGO_AUTO 0
 #define IPTQ_ALGO_GENERIC 1 /* softmax: one wavefront per row, any cols; GELU: polynomial per element */
 #define IPTQ_ALGO_DYNAMIC 2 /* softmax only: the register-resident kernel with run-time row length
-                               (rows up to about 830 scores), also where a compiled row length
+                               (rows up to about 635 scores), also where a compiled row length
                                would serve */
-#define IPTQ_ALGO_WIDE 3    /* softmax only: one wavefront (rows up to 4093 scores) or one workgroup
+#define IPTQ_ALGO_WIDE 3    /* softmax only: one wavefront (rows up to 4096 scores) or one workgroup
                                (up to 40957) per row, row in registers, no LDS staging, also where
                                another kernel would serve */
 

@@ -16,8 +16,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libiptq.so")
 # the slowest translation units first (the pool takes them in this order)
-SOURCES = ["softmax_wgrow_w8_s20.hip", "softmax_wgrow_w4_s20.hip", "softmax_wgrow_w8_s16.hip", "softmax_wgrow_w4_s13.hip",
-           "softmax_wide_s16.hip", "softmax_wide_s13.hip", "softmax_wide_s8.hip", "softmax_rowsdyn_k16_long.hip",
+SOURCES = ["softmax_wgrow_w4_hi.hip", "softmax_wgrow_w8_hi.hip", "softmax_wgrow_w16.hip", "softmax_wgrow_w4_lo.hip", "softmax_wgrow_w8_lo.hip",
+           "softmax_wide_p14_16.hip", "softmax_wide_p11_13.hip", "softmax_wide_p7_10.hip", "softmax_wide_p1_6.hip", "softmax_rowsdyn_k16_long.hip",
            "softmax_rows_577.hip", "softmax_rows_257.hip", "softmax_rows_197.hip", "softmax_rows_198.hip",
            "softmax_rows_144.hip", "softmax_rows_49.hip", "softmax_rows_197_k8.hip", "softmax_rows_198_k8.hip",
            "softmax_rowsdyn_k2.hip", "softmax_rowsdyn_k2_short.hip", "softmax_rowsdyn_k4.hip", "softmax_rowsdyn_k8.hip",

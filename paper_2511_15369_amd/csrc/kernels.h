@@ -32,8 +32,8 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
 // (*done == 0) if the row is too long or the pointers do not qualify.
 hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
                                   hipStream_t stream);
-// One wavefront per row, row in registers, no LDS staging (rows of up to 4093 scores): the
-// leading rows of one call (all of them unless the tensor ends off a 16-byte boundary).
+// One wavefront per row, row in registers, no LDS staging (rows of up to 4093 scores at any
+// alignment, 4096 if a multiple of 4): every row of one call, or none.
 hipError_t softmax_wide_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
                                hipStream_t stream);
 // One workgroup per row, row in the workgroup's registers (rows of up to 40957 scores).

@@ -280,7 +280,7 @@ bool rowsdyn_launch_k2(const DynArgs &, int slots, int mode, dim3, dim3, size_t,
 bool rowsdyn_launch_k4(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);         // 5..8
 bool rowsdyn_launch_k8(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);         // 5..8
 bool rowsdyn_launch_k16(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);        // 5..8
-bool rowsdyn_launch_k16_long(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);   // 9..13
+bool rowsdyn_launch_k16_long(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);   // 9..10
 
 #define IPTQ_ROWSDYN_CASE(K, S)                                                                   \
     case S: rowsdyn_launch_ks<K, S>(A, mode, grid, block, lds, stream); return true;

@@ -8,16 +8,18 @@ namespace iptq {
 
 // Lane layout for a row length: the fewest lanes per row that keep the blocks per lane at or
 // below 8 (5 wavefronts per SIMD; measured equal or better than more blocks on fewer lanes),
-// else 16 lanes per row with up to 13 blocks per lane (rows of up to about 830 scores).
+// else 16 lanes per row with up to 10 blocks per lane (rows of up to about 635 scores).
 // *slots is exactly ceil(most blocks a row can touch / lanes): the kernels rely on it.
-// Returns false for longer rows: one wavefront per row serves those better (softmax_wide.h).
+// Returns false for longer rows: one wavefront per row serves those better (softmax_wide.h;
+// measured 70-75 % against 66-69 % of the HBM roofline at 650 to 829 columns, 57-67 % against
+// 69-75 % at 509 to 600).
 bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used)
 {
     const int nb_max = (cols % 4 == 0) ? cols / 4 : ((cols % 2 == 0) ? (cols + 2 + 3) / 4 : (cols + 3 + 3) / 4);
     int k = 2;
     while (k < 16 && (nb_max + k - 1) / k > 8) k *= 2;
     const int n = (nb_max + k - 1) / k;
-    if (n > 13) return false;
+    if (n > 10) return false;
     *lanes = k;
     *n_used = n;
     *slots = n;

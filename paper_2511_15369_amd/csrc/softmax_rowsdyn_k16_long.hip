@@ -1,4 +1,4 @@
-// Run-time-row-length softmax slab kernel, 16 lanes per row, 9 to 13 blocks per lane.
+// Run-time-row-length softmax slab kernel, 16 lanes per row, 9 or 10 blocks per lane.
 #include "softmax_rowsdyn.h"
 
 namespace iptq {
@@ -7,9 +7,6 @@ bool rowsdyn_launch_k16_long(const DynArgs &A, int slots, int mode, dim3 grid, d
     switch (slots) {
     IPTQ_ROWSDYN_CASE(16, 9)
     IPTQ_ROWSDYN_CASE(16, 10)
-    IPTQ_ROWSDYN_CASE(16, 11)
-    IPTQ_ROWSDYN_CASE(16, 12)
-    IPTQ_ROWSDYN_CASE(16, 13)
     default: return false;
     }
 }

@@ -5,20 +5,26 @@
 
 namespace iptq {
 
-// Wavefronts per workgroup and compiled pass count for a row length; false beyond 40957 scores.
+// Wavefronts per workgroup and pass count for a row length (exactly the passes a row needs at its
+// worst alignment: the kernels rely on it); false beyond 40957 scores.  Up to 13 passes keep a
+// lane within 128 registers, so two workgroups share a compute unit and one loads while the
+// other computes (66-78 % of the HBM roofline); the 14 to 20 passes that 8 wavefronts would
+// need beyond 26618 scores leave one workgroup per compute unit, and so do 16 wavefronts
+// (both 46-50 %; 16 wavefronts compile faster).
 bool wgrow_geometry(int32_t cols, int *waves, int *slots)
 {
     const int nb_max = (cols % 4 == 0) ? cols / 4 : ((cols % 2 == 0) ? (cols + 2 + 3) / 4 : (cols + 3 + 3) / 4);
-    const int n4 = (nb_max + 255) / 256, n8 = (nb_max + 511) / 512;
-    if (n4 <= 13) { *waves = 4; *slots = 13; }
-    else if (n4 <= 20) { *waves = 4; *slots = 20; }
-    else if (n8 <= 16) { *waves = 8; *slots = 16; }
-    else if (n8 <= 20) { *waves = 8; *slots = 20; }
-    else return false;
+    int w = 4;
+    if ((nb_max + 255) / 256 > 13) w = 8;
+    if ((nb_max + 511) / 512 > 13) w = 16;
+    const int n = (nb_max + 64 * w - 1) / (64 * w);
+    if (n > (w == 16 ? 10 : 13)) return false;
+    *waves = w;
+    *slots = n;
     return true;
 }
 
-// Most rows of one call if the call qualifies (same conditions as softmax_wide_launch).
+// Every row of one call if the call qualifies (same conditions as softmax_wide_launch).
 hipError_t softmax_wgrow_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
                                 hipStream_t stream)
 {
@@ -30,16 +36,21 @@ hipError_t softmax_wgrow_launch(const SoftmaxCall &c, int32_t cols, int post_mod
     const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
                                        ((int64_t)c.P.bias_period_rows * cols) % 4 == 0);
     if (!aligned || !bias_ok) return hipSuccess;
-    const int64_t rows = ((c.rows * cols) % 4 == 0) ? c.rows : c.rows - 1;
-    if (rows <= 0) return hipSuccess;
+    // A tensor that ends off the 16-byte grid: the kernel loads the last row's final block
+    // element by element, which takes rows of at least 8 scores (a whole block before it).
+    const int cut_el = (int)((c.rows * cols) & 3);
+    if (c.rows <= 0 || (cut_el != 0 && cols < 8)) return hipSuccess;
+    const int64_t rows = c.rows;
     WideArgs A;
-    A.scores = c.scores; A.bias = c.bias; A.out = c.out; A.rows = rows; A.cols = cols; A.P = c.P;
+    A.scores = c.scores; A.bias = c.bias; A.out = c.out; A.rows = rows; A.cols = cols; A.post_mode = post_mode; A.P = c.P;
+    A.cut_el = cut_el;
     const dim3 grid((unsigned)rows);                  // one workgroup per row, exactly
     const int mode = c.P.mode16;
-    if (waves == 4 && slots == 13) wgrow_launch_w4_s13(A, mode, post_mode, grid, stream);
-    else if (waves == 4) wgrow_launch_w4_s20(A, mode, post_mode, grid, stream);
-    else if (slots == 16) wgrow_launch_w8_s16(A, mode, post_mode, grid, stream);
-    else wgrow_launch_w8_s20(A, mode, post_mode, grid, stream);
+    bool launched;
+    if (waves == 4) launched = slots <= 9 ? wgrow_launch_w4_lo(A, slots, mode, grid, stream) : wgrow_launch_w4_hi(A, slots, mode, grid, stream);
+    else if (waves == 8) launched = slots <= 10 ? wgrow_launch_w8_lo(A, slots, mode, grid, stream) : wgrow_launch_w8_hi(A, slots, mode, grid, stream);
+    else launched = wgrow_launch_w16(A, slots, mode, grid, stream);
+    if (!launched) return hipSuccess;
     *done = rows;
     return hipGetLastError();
 }

@@ -4,8 +4,13 @@
 // fully coalesced 1 KiB load.  A row that does not start on a 16-byte boundary shares its first
 // and last block with its neighbours: their elements are masked on the way in and those
 // blocks are written back with byte stores, every other block with one dword store.  The
-// arithmetic is the slab kernels' (softmax_slab_math with 64 lanes per row).  Rows of up to
-// 256 * SLOTS - 3 scores.
+// arithmetic is the slab kernels' (softmax_slab_math with 64 lanes per row).
+// SLOTS is exactly the number of passes a row of this length needs at its worst alignment,
+// ceil(B / 64) with B the most blocks it can touch: a row touches B or B - 1 blocks, so the
+// blocks of passes 0 .. SLOTS-2 exist in every row, only the last pass clamps its block
+// index (the last two do: one instruction), and only passes 0, SLOTS-2 and SLOTS-1 can hold a
+// row's first or last block (element masks, byte stores).  No branch depends on the row
+// length.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -21,17 +26,19 @@ struct WideArgs {
     const int32_t *scores;   // 16-byte aligned
     const int32_t *bias;     // NULL or 16-byte aligned, period * cols a multiple of 4
     uint8_t *out;            // 4-byte aligned
-    int64_t rows;            // rows served by this launch (the host keeps a last row whose final
-                             // block would reach beyond the tensor out of it)
-    int32_t cols;
+    int64_t rows;
+    int32_t cols;            // >= 8 when cut_el != 0 (host)
+    int32_t cut_el;          // scores in the tensor's final 16-byte block if the tensor ends off the
+                             // 16-byte grid (the last row must not load that block whole), else 0
+    int32_t post_mode;       // PM_NONE / PM_CLAMP127 / PM_GENERAL, applied to the packed bytes
     SoftmaxDev P;
 };
 
-template <int SLOTS, int MODE, int POSTMODE>
+template <int SLOTS, int MODE>
 __global__ void __launch_bounds__(256)
 softmax_wide_kernel(WideArgs A)
 {
-    __shared__ uint8_t lut_all[4][POSTMODE == PM_GENERAL ? kPostLutBytes : 4];
+    __shared__ uint8_t lut_all[4][kPostLutBytes];
     const SoftmaxDev P = A.P;
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
@@ -39,7 +46,8 @@ softmax_wide_kernel(WideArgs A)
     if (row >= A.rows) return;                        // no workgroup barrier below
 
     uint8_t *lut = lut_all[wv];
-    if (POSTMODE == PM_GENERAL) {
+    const int post_mode = A.post_mode;
+    if (post_mode == PM_GENERAL) {
         const int p_max = 1 << (P.m_bits - P.p_shift);
         for (int p = lane; p <= p_max; p += 64) lut[p] = (uint8_t)post_dev<PM_GENERAL>((uint32_t)p, P);
         wave_lds_fence();
@@ -49,42 +57,53 @@ softmax_wide_kernel(WideArgs A)
     const int64_t e0 = row * cols;                    // the row's first element in the tensor
     const int phi = (int)(e0 & 3);                    // its offset inside its 16-byte block
     const int nb = (phi + cols + 3) >> 2;             // blocks the row touches (wavefront-uniform)
-    const int n_used = (nb + 63) >> 6;                // passes that hold row data, <= SLOTS (host)
     const i32x4 *src = reinterpret_cast<const i32x4 *>(A.scores) + (e0 >> 2);
+    // the last row of a tensor that ends off the 16-byte grid: its final block is loaded
+    // element by element below (wavefront-uniform case)
+    const bool cut = A.cut_el != 0 && row == A.rows - 1;
+    const int nb_whole = cut ? nb - 1 : nb;           // blocks that can be loaded whole, >= 1
+    auto block_of = [&](int s, int n) {               // lanes beyond block n - 1 load it again
+        const int b = s * 64 + lane;
+        return s >= SLOTS - 2 ? min(b, n - 1) : b;
+    };
+    auto edge_slot = [](int s) { return s == 0 || s >= SLOTS - 2; };
 
-    // ---- the row's blocks; every load is issued before the first use, lanes beyond the last
-    // block load it again (no lane-divergent branch around a load)
+    // ---- the row's blocks; every load is issued before the first use and none sits behind a
+    // branch
     i32x4 v[SLOTS];
 #pragma unroll
-    for (int s = 0; s < SLOTS; ++s)
-        if (s < n_used) v[s] = stream_load(src + min(s * 64 + lane, nb - 1));
+    for (int s = 0; s < SLOTS; ++s) v[s] = stream_load(src + block_of(s, nb_whole));
+    if (cut) {
+        const int32_t *last = reinterpret_cast<const int32_t *>(src + (nb - 1));
+#pragma unroll
+        for (int s = SLOTS >= 2 ? SLOTS - 2 : 0; s < SLOTS; ++s) {
+            if (s * 64 + lane == nb - 1) {            // elements beyond cut_el are masked below
+                v[s].x = last[0];
+                if (A.cut_el > 1) v[s].y = last[1];
+                if (A.cut_el > 2) v[s].z = last[2];
+            }
+        }
+    }
     if (A.bias != nullptr) {
         // the bias row starts at the same offset inside a block (period * cols % 4 == 0)
         const int64_t eb = (int64_t)row_mod_period((uint32_t)row, P) * cols;
         const i32x4 *bsrc = reinterpret_cast<const i32x4 *>(A.bias) + (eb >> 2);
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
-            if (s < n_used) {
-                const i32x4 bv = bsrc[min(s * 64 + lane, nb - 1)];
-                v[s].x = v[s].x == kI32Min ? kI32Min : sat_add_i32(v[s].x, bv.x);
-                v[s].y = v[s].y == kI32Min ? kI32Min : sat_add_i32(v[s].y, bv.y);
-                v[s].z = v[s].z == kI32Min ? kI32Min : sat_add_i32(v[s].z, bv.z);
-                v[s].w = v[s].w == kI32Min ? kI32Min : sat_add_i32(v[s].w, bv.w);
-            }
+            const i32x4 bv = bsrc[block_of(s, nb)];
+            v[s].x = v[s].x == kI32Min ? kI32Min : sat_add_i32(v[s].x, bv.x);
+            v[s].y = v[s].y == kI32Min ? kI32Min : sat_add_i32(v[s].y, bv.y);
+            v[s].z = v[s].z == kI32Min ? kI32Min : sat_add_i32(v[s].z, bv.z);
+            v[s].w = v[s].w == kI32Min ? kI32Min : sat_add_i32(v[s].w, bv.w);
         }
     }
 
-    // ---- elements outside the row become "minus infinity" (only a row's first block and the
-    // passes that can reach its end need the test)
+    // ---- elements outside the row become "minus infinity"
     int32_t x[SLOTS][4];
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
-        if (s >= n_used) {
-            x[s][0] = x[s][1] = x[s][2] = x[s][3] = kI32Min;
-            continue;
-        }
         x[s][0] = v[s].x; x[s][1] = v[s].y; x[s][2] = v[s].z; x[s][3] = v[s].w;
-        if (s == 0 || 4 * (s * 64 + 63) + 3 >= cols) {
+        if (edge_slot(s)) {
             const int c0 = 4 * (s * 64 + lane) - phi;
 #pragma unroll
             for (int e = 0; e < 4; ++e)
@@ -97,52 +116,54 @@ softmax_wide_kernel(WideArgs A)
         const int32_t pre_mul = P.pre_mul, pre_sh2 = P.pre_sh2;
         const int64_t pre_rnd = P.pre_rnd;
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) {
-            if (s >= n_used) continue;
+        for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int32_t r = pre_requant_narrow(x[s][e], pre_mul, pre_rnd, pre_sh2);
                 x[s][e] = x[s][e] == kI32Min ? kI32Min : r;
             }
-        }
     } else if (P.pre_mode == 2) {                     // shifts below 16: the general 64-bit form
         const int32_t pre_m = P.pre_m, pre_s = P.pre_s;
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s) {
-            if (s >= n_used) continue;
+        for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int32_t r = pre_requant_dev(x[s][e], pre_m, pre_s);
                 x[s][e] = x[s][e] == kI32Min ? kI32Min : r;
             }
-        }
     }
 
     // ---- Eq. 6: row maximum
     int32_t mx = kI32Min;
 #pragma unroll
-    for (int s = 0; s < SLOTS; ++s) {
-        if (s >= n_used) continue;
+    for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
         for (int e = 0; e < 4; ++e) mx = max(mx, x[s][e]);
-    }
     mx = group_max_i32<64>(mx);
 
     const int32_t D = P.d_clamp;
     const bool low_row = mx < kI32Min + D;            // wavefront-uniform here; see softmax_rows_kernel
     const int32_t lower = low_row ? kI32Min : mx - D;
-    uint32_t w[SLOTS];                                // four output bytes per block
-    if (P.variant == 0) softmax_slab_math<64, SLOTS, MODE, 0, POSTMODE, true>(x, w, mx, lower, low_row, lut, P, n_used);
-    else softmax_slab_math<64, SLOTS, MODE, 1, POSTMODE, true>(x, w, mx, lower, low_row, lut, P, n_used);
+    uint32_t w[SLOTS];                                // four probabilities per block, one per byte
+    if (P.variant == 0) softmax_slab_math<64, SLOTS, MODE, 0, PM_NONE>(x, w, mx, lower, low_row, lut, P);
+    else softmax_slab_math<64, SLOTS, MODE, 1, PM_NONE>(x, w, mx, lower, low_row, lut, P);
+
+    // ---- post step on the packed bytes (a probability is at most 128)
+    if (post_mode == PM_CLAMP127) {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) w[s] = clamp127_bytes(w[s]);
+    } else if (post_mode == PM_GENERAL) {
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) w[s] = post_lut_gather(lut, w[s]);
+    }
 
     // ---- write back: whole blocks as dwords, the two shared edge blocks byte by byte
     uint8_t *dst8 = A.out + (e0 - phi);               // the byte of the row's first block, 4-byte aligned
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
-        if (s >= n_used) continue;
         const int b = s * 64 + lane;
         const int c0 = 4 * b - phi;
-        if (s != 0 && 4 * (s * 64 + 63) + 3 < cols) {     // every lane's block lies inside the row
+        if (!edge_slot(s)) {                          // every lane's block lies inside the row
             stream_store(w[s], reinterpret_cast<uint32_t *>(dst8) + b);
         } else if (b < nb) {
             if (c0 >= 0 && c0 + 3 < cols) {
@@ -156,26 +177,21 @@ softmax_wide_kernel(WideArgs A)
     }
 }
 
+// mode: SoftmaxDev::mode16 (2 covers 1: t16 == 0 shifts by 0)
 template <int SLOTS>
-static void wide_launch_s(const WideArgs &A, int mode, int post_mode, dim3 grid, hipStream_t stream)
+static void wide_launch_s(const WideArgs &A, int mode, dim3 grid, hipStream_t stream)
 {
-#define IPTQ_WIDE_LAUNCH(MODE, PM)                                                                \
-    hipLaunchKernelGGL((softmax_wide_kernel<SLOTS, MODE, PM>), grid, dim3(256), 0, stream, A)
-    if (mode == 0) {
-        if (post_mode == PM_NONE) IPTQ_WIDE_LAUNCH(0, PM_NONE);
-        else if (post_mode == PM_CLAMP127) IPTQ_WIDE_LAUNCH(0, PM_CLAMP127);
-        else IPTQ_WIDE_LAUNCH(0, PM_GENERAL);
-    } else {                                          // 2 covers 1: t16 == 0 shifts by 0
-        if (post_mode == PM_NONE) IPTQ_WIDE_LAUNCH(2, PM_NONE);
-        else if (post_mode == PM_CLAMP127) IPTQ_WIDE_LAUNCH(2, PM_CLAMP127);
-        else IPTQ_WIDE_LAUNCH(2, PM_GENERAL);
-    }
-#undef IPTQ_WIDE_LAUNCH
+    if (mode == 0) hipLaunchKernelGGL((softmax_wide_kernel<SLOTS, 0>), grid, dim3(256), 0, stream, A);
+    else hipLaunchKernelGGL((softmax_wide_kernel<SLOTS, 2>), grid, dim3(256), 0, stream, A);
 }
 
-// one translation unit per block count (softmax_wide_s<N>.hip)
-void wide_launch_s8(const WideArgs &A, int mode, int post_mode, dim3 grid, hipStream_t stream);
-void wide_launch_s13(const WideArgs &A, int mode, int post_mode, dim3 grid, hipStream_t stream);
-void wide_launch_s16(const WideArgs &A, int mode, int post_mode, dim3 grid, hipStream_t stream);
+// one translation unit per group of pass counts; each returns false for a count it does not hold
+bool wide_launch_p1_6(const WideArgs &A, int passes, int mode, dim3 grid, hipStream_t stream);
+bool wide_launch_p7_10(const WideArgs &A, int passes, int mode, dim3 grid, hipStream_t stream);
+bool wide_launch_p11_13(const WideArgs &A, int passes, int mode, dim3 grid, hipStream_t stream);
+bool wide_launch_p14_16(const WideArgs &A, int passes, int mode, dim3 grid, hipStream_t stream);
+
+#define IPTQ_WIDE_CASE(S)                                                                         \
+    case S: wide_launch_s<S>(A, mode, grid, stream); return true;
 
 }  // namespace iptq

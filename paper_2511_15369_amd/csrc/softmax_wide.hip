@@ -5,23 +5,22 @@
 
 namespace iptq {
 
-// Passes of 64 blocks a row of `cols` scores needs at its worst alignment, and the compiled
-// pass count that serves it.  Returns false beyond 16 passes (rows of more than 4093 scores):
-// with more registers per lane than that a workgroup per row is faster (softmax_wgrow.h;
-// 5117 columns: 63 % against 55 % of the HBM roofline).
+// Passes of 64 blocks a row of `cols` scores needs at its worst alignment (exactly: the kernel
+// compiled for that count serves it and relies on it).  Returns false beyond 16 passes (rows of
+// more than 4093 scores, 4096 if a multiple of 4): with more registers per lane than that a
+// workgroup per row is faster (softmax_wgrow.h).
 bool wide_geometry(int32_t cols, int *passes, int *slots)
 {
     const int nb_max = (cols % 4 == 0) ? cols / 4 : ((cols % 2 == 0) ? (cols + 2 + 3) / 4 : (cols + 3 + 3) / 4);
     const int n = (nb_max + 63) / 64;
     if (n > 16) return false;
     *passes = n;
-    *slots = n <= 8 ? 8 : (n <= 13 ? 13 : 16);
+    *slots = n;
     return true;
 }
 
-// Most rows of one call if the call qualifies: rows of up to 4093 scores, 16-byte aligned
-// tensors.  When the tensor does not end on a 16-byte boundary its last row is left out (its
-// final block would reach beyond the tensor); *done receives the number of leading rows served.
+// Every row of one call if the call qualifies: rows of up to 16 passes, 16-byte aligned
+// tensors; *done receives the number of rows served (0: not served, nothing enqueued).
 hipError_t softmax_wide_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
                                hipStream_t stream)
 {
@@ -33,15 +32,21 @@ hipError_t softmax_wide_launch(const SoftmaxCall &c, int32_t cols, int post_mode
     const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
                                        ((int64_t)c.P.bias_period_rows * cols) % 4 == 0);
     if (!aligned || !bias_ok) return hipSuccess;
-    const int64_t rows = ((c.rows * cols) % 4 == 0) ? c.rows : c.rows - 1;
-    if (rows <= 0) return hipSuccess;
+    // A tensor that ends off the 16-byte grid: the kernel loads the last row's final block
+    // element by element, which takes rows of at least 8 scores (a whole block before it).
+    const int cut_el = (int)((c.rows * cols) & 3);
+    if (c.rows <= 0 || (cut_el != 0 && cols < 8)) return hipSuccess;
+    const int64_t rows = c.rows;
     WideArgs A;
-    A.scores = c.scores; A.bias = c.bias; A.out = c.out; A.rows = rows; A.cols = cols; A.P = c.P;
+    A.scores = c.scores; A.bias = c.bias; A.out = c.out; A.rows = rows; A.cols = cols; A.post_mode = post_mode; A.P = c.P;
+    A.cut_el = cut_el;
     const dim3 grid((unsigned)((rows + 3) / 4));
     const int mode = c.P.mode16;
-    if (slots == 8) wide_launch_s8(A, mode, post_mode, grid, stream);
-    else if (slots == 13) wide_launch_s13(A, mode, post_mode, grid, stream);
-    else wide_launch_s16(A, mode, post_mode, grid, stream);
+    const bool launched = n <= 6 ? wide_launch_p1_6(A, n, mode, grid, stream)
+                        : n <= 10 ? wide_launch_p7_10(A, n, mode, grid, stream)
+                        : n <= 13 ? wide_launch_p11_13(A, n, mode, grid, stream)
+                                  : wide_launch_p14_16(A, n, mode, grid, stream);
+    if (!launched) return hipSuccess;
     *done = rows;
     return hipGetLastError();
 }

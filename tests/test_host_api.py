@@ -265,7 +265,7 @@ def test_run_time_row_length_layouts_fit_what_the_kernels_assume():
             nb_max = (cols + 3 + 3) // 4
         assert nb_max >= max(((phi + cols + 3) >> 2) for phi in range(0, 4, 4 if cols % 4 == 0 else (2 if cols % 2 == 0 else 1)))
         if dyn_ok:
-            assert k in (2, 4, 8, 16) and 1 <= slots <= 13 and (slots <= 8 or k == 16)
+            assert k in (2, 4, 8, 16) and 1 <= slots <= 10 and (slots <= 8 or k == 16)
             assert (k == 2 or slots >= 5) and n_used == slots    # the layouts that are instantiated
             assert slots == -(-nb_max // k)                  # exactly: the kernel's slot roles rely on it
             nb_min = min(((phi + cols + 3) >> 2) for phi in range(0, 4, 4 if cols % 4 == 0 else (2 if cols % 2 == 0 else 1)))
@@ -277,14 +277,17 @@ def test_run_time_row_length_layouts_fit_what_the_kernels_assume():
             wave_lds = ((rpw * cols * 4 + 15) & ~15) + 144
             assert wave_lds <= 65536
         else:
-            assert nb_max > 16 * 13
+            assert nb_max > 16 * 10
+        nb_lo = min(((phi + cols + 3) >> 2) for phi in range(4))     # a row may start anywhere in its block
         if wide_ok:
-            assert wslots in (8, 13, 16) and 1 <= passes <= wslots and 64 * passes >= nb_max
+            assert wslots == passes == -(-nb_max // 64) and 1 <= passes <= 16     # exactly, as for the slab layouts
+            assert nb_lo >= 64 * (passes - 1)                # passes 0 .. passes-2 exist in every row
         else:
             assert nb_max > 64 * 16
         if wg_ok:
-            assert (waves, gslots) in ((4, 13), (4, 20), (8, 16), (8, 20))
-            assert 64 * waves * gslots >= nb_max             # the row fits the workgroup's registers
+            assert waves in (4, 8, 16) and gslots == -(-nb_max // (64 * waves))     # exactly
+            assert {4: 5, 8: 7, 16: 7}[waves] <= gslots <= {4: 13, 8: 13, 16: 10}[waves] or wide_ok    # instantiated wherever one wavefront per row does not serve
+            assert nb_lo >= 64 * waves * (gslots - 1)        # passes 0 .. gslots-2 exist in every row
         else:
             assert nb_max > 512 * 20
         served_by_registers += bool(dyn_ok or wide_ok or wg_ok)
