@@ -5,6 +5,7 @@ import os
 import re
 import shutil
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 import pytest
 
@@ -18,15 +19,33 @@ FORBIDDEN = re.compile(r"^\s+(v_[a-z0-9_]*_(f16|f32|f64|bf16)\b|v_cvt_(?!pk_[iu]
 SOURCES = sorted(f for f in os.listdir(CSRC) if f.endswith(".hip") and f != "api.hip")
 
 
-@pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not installed")
-@pytest.mark.parametrize("src", SOURCES)
-def test_no_floating_point_instructions(src, tmp_path):
-    out = tmp_path / (src + ".s")
+def _compile(src, out_dir):
+    out = os.path.join(out_dir, src + ".s")
     subprocess.check_call(["hipcc", "-x", "hip", "--offload-arch=gfx950", "-O3", "-std=c++17",
                            "--cuda-device-only", "-S", "-Xclang", "-target-feature", "-Xclang",
-                           "-packed-fp32-ops", os.path.join(CSRC, src), "-o", str(out)],
+                           "-packed-fp32-ops", os.path.join(CSRC, src), "-o", out],
                           stderr=subprocess.DEVNULL)
-    text = out.read_text()
+    with open(out) as f:
+        return f.read()
+
+
+@pytest.fixture(scope="session")
+def assembly(tmp_path_factory):
+    """src -> assembly text.  In a single process every translation unit is compiled up front on
+    all cores (one after the other they take minutes); a pytest-xdist worker compiles only the
+    files of the tests it was given."""
+    out_dir = str(tmp_path_factory.mktemp("isa"))
+    if os.environ.get("PYTEST_XDIST_WORKER"):
+        return lambda src: _compile(src, out_dir)
+    pool = ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1))
+    futures = {src: pool.submit(_compile, src, out_dir) for src in SOURCES}
+    return lambda src: futures[src].result()
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not installed")
+@pytest.mark.parametrize("src", SOURCES)
+def test_no_floating_point_instructions(src, assembly):
+    text = assembly(src)
     if ".amdhsa_kernel" not in text:                   # a host-only translation unit
         assert "__global__" not in open(os.path.join(CSRC, src)).read()
         return
