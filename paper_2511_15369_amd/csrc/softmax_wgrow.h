@@ -57,7 +57,7 @@ softmax_wgrow_kernel(WideArgs A)
     }
 
     const int cols = A.cols;
-    const int64_t e0 = row * cols;                    // the row's first element in the tensor
+    const int64_t e0 = row * cols + A.base_off;       // the row's first element on the 16-byte grid
     const int phi = (int)(e0 & 3);                    // its offset inside its 16-byte block
     const int nb = (phi + cols + 3) >> 2;             // blocks the row touches
     const i32x4 *src = reinterpret_cast<const i32x4 *>(A.scores) + (e0 >> 2);

@@ -3,7 +3,8 @@
 // 16-byte block s * 64 + l of the aligned block range that covers the row, so a pass is one
 // fully coalesced 1 KiB load.  A row that does not start on a 16-byte boundary shares its first
 // and last block with its neighbours: their elements are masked on the way in and those
-// blocks are written back with byte stores, every other block with one dword store.  The
+// blocks are written back with byte stores, every other block with one dword store (so the
+// tensor itself may start anywhere on the 4-byte grid, the output at the same offset).  The
 // arithmetic is the slab kernels' (softmax_slab_math with 64 lanes per row).
 // SLOTS is exactly the number of passes a row of this length needs at its worst alignment,
 // ceil(B / 64) with B the most blocks it can touch: a row touches B or B - 1 blocks, so the
@@ -23,10 +24,11 @@
 namespace iptq {
 
 struct WideArgs {
-    const int32_t *scores;   // 16-byte aligned
-    const int32_t *bias;     // NULL or 16-byte aligned, period * cols a multiple of 4
-    uint8_t *out;            // 4-byte aligned
+    const int32_t *scores;   // the tensor's address rounded down to 16 bytes
+    const int32_t *bias;     // NULL or 16-byte aligned, period * cols a multiple of 4 (base_off == 0 then)
+    uint8_t *out;            // the output's address minus base_off, 4-byte aligned
     int64_t rows;
+    int32_t base_off;        // scores between the rounded-down address and the tensor: 0..3
     int32_t cols;            // >= 8 when cut_el != 0 (host)
     int32_t cut_el;          // scores in the tensor's final 16-byte block if the tensor ends off the
                              // 16-byte grid (the last row must not load that block whole), else 0
@@ -54,7 +56,7 @@ softmax_wide_kernel(WideArgs A)
     }
 
     const int cols = A.cols;
-    const int64_t e0 = row * cols;                    // the row's first element in the tensor
+    const int64_t e0 = row * cols + A.base_off;       // the row's first element on the 16-byte grid
     const int phi = (int)(e0 & 3);                    // its offset inside its 16-byte block
     const int nb = (phi + cols + 3) >> 2;             // blocks the row touches (wavefront-uniform)
     const i32x4 *src = reinterpret_cast<const i32x4 *>(A.scores) + (e0 >> 2);

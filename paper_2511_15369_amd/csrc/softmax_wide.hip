@@ -27,18 +27,23 @@ hipError_t softmax_wide_launch(const SoftmaxCall &c, int32_t cols, int post_mode
     *done = 0;
     int n = 0, slots = 0;
     if (!wide_geometry(cols, &n, &slots)) return hipSuccess;
+    // The tensor may start anywhere on the 4-byte grid if the output starts at the same offset
+    // from its own 4-byte grid (views cut at the same element of both tensors do); the additive
+    // table is indexed block by block and needs both on the 16-byte grid.
+    const uintptr_t sa = reinterpret_cast<uintptr_t>(c.scores), oa = reinterpret_cast<uintptr_t>(c.out);
+    const int base_off = (int)((sa & 15) >> 2);
+    if ((sa & 3) != 0 || ((oa - (uintptr_t)base_off) & 3) != 0) return hipSuccess;
     const bool has_bias = c.bias != nullptr;
-    const bool aligned = ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.out)) & 15) == 0;
-    const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
+    const bool bias_ok = !has_bias || (base_off == 0 && (reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
                                        ((int64_t)c.P.bias_period_rows * cols) % 4 == 0);
-    if (!aligned || !bias_ok) return hipSuccess;
+    if (!bias_ok) return hipSuccess;
     // A tensor that ends off the 16-byte grid: the kernel loads the last row's final block
     // element by element, which takes rows of at least 8 scores (a whole block before it).
-    const int cut_el = (int)((c.rows * cols) & 3);
+    const int cut_el = (int)((base_off + c.rows * cols) & 3);
     if (c.rows <= 0 || (cut_el != 0 && cols < 8)) return hipSuccess;
     const int64_t rows = c.rows;
     WideArgs A;
-    A.scores = c.scores; A.bias = c.bias; A.out = c.out; A.rows = rows; A.cols = cols; A.post_mode = post_mode; A.P = c.P;
+    A.scores = c.scores - base_off; A.bias = c.bias; A.out = c.out - base_off; A.base_off = base_off; A.rows = rows; A.cols = cols; A.post_mode = post_mode; A.P = c.P;
     A.cut_el = cut_el;
     const dim3 grid((unsigned)((rows + 3) / 4));
     const int mode = c.P.mode16;

@@ -139,6 +139,39 @@ def test_softmax_partial_last_slab(cols):
             assert (got[rows * cols:] == 0x5A).all(), (rows, with_bias)
 
 
+@pytest.mark.parametrize("cols", [49, 197, 800, 1025, 5117])
+def test_softmax_views_off_the_16_byte_grid(cols):
+    """Score and output tensors that are views into larger buffers, cut at the same element (so
+    the scores start off the 16-byte grid and the output at the matching byte), and views cut
+    at different elements: every row is right and no byte outside the view is written."""
+    import torch
+    import paper_2511_15369_amd as ip
+    rng = np.random.default_rng(8100 + cols)
+    rows = 21 if cols < 2000 else 6
+    scores = np.rint(rng.standard_normal((rows, cols)) * 500).astype(np.int32)
+    scores[1, ::3] = INT32_MIN
+    bias = np.rint(rng.standard_normal((4, cols)) * 40).astype(np.int32)
+    d_bias = torch.from_numpy(bias).cuda()
+    n = rows * cols
+    p = prepare.softmax_prepare(2.0 ** -7.1, cols, 1)
+    for in_off, out_off, with_bias in ((1, 1, False), (2, 2, False), (3, 3, False), (3, 7, False),
+                                       (1, 2, False), (0, 3, False), (2, 2, True), (5, 1, False)):
+        d_in = torch.zeros(n + 16, dtype=torch.int32, device="cuda")
+        d_in[in_off:in_off + n] = torch.from_numpy(scores.reshape(-1)).cuda()
+        d_out = torch.full((n + 32,), 0x5A, dtype=torch.uint8, device="cuda")
+        want = ref.softmax_i32(scores, p, bias if with_bias else None, 4 if with_bias else 0)
+        for algo in (0, 3):
+            d_out.fill_(0x5A)
+            lp = lib_softmax(p)
+            lp.algo = algo
+            ip.softmax_i32(d_in[in_off:in_off + n], d_bias if with_bias else None, 4 if with_bias else 0,
+                           d_out[out_off:out_off + n], rows, cols, lp)
+            torch.cuda.synchronize()
+            got = d_out.cpu().numpy()
+            assert np.array_equal(got[out_off:out_off + n].reshape(rows, cols), want), (in_off, out_off, algo)
+            assert (got[:out_off] == 0x5A).all() and (got[out_off + n:] == 0x5A).all(), (in_off, out_off, algo)
+
+
 @pytest.mark.parametrize("cols", [197, 49, 144])
 def test_softmax_fused_pre_requant_shifts(cols):
     """The requantization in front of the softmax at every shift class: below 16 (general
