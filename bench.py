@@ -146,6 +146,38 @@ def measure_fused(steps):
     return res
 
 
+def measure_row_lengths(steps):
+    """Row lengths outside the five benchmark configurations, about 60 M scores per launch
+    (a ViT-B layer's worth), four rotating tensor sets: which kernel family serves each and at
+    what fraction of the HBM roofline.  Scores round(N(0, 5000)), scale 2^-7, variant 1."""
+    import torch
+
+    import paper_2511_15369_amd as ip
+    res = {}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(0)
+    for cols in (50, 64, 145, 196, 401, 600, 785, 1025, 2048, 4097, 8192, 16384, 32768):
+        rows = 60_000_000 // cols
+        ins = [(torch.randn((rows, cols), device="cuda", generator=gen) * 5000).round().to(torch.int32)
+               for _ in range(4)]
+        outs = [torch.empty((rows, cols), dtype=torch.uint8, device="cuda") for _ in range(4)]
+        sp = ip.softmax_prepare(2.0 ** -7, cols, 1, 0)
+
+        def fn():
+            for x, y in zip(ins, outs):
+                ip.softmax_i32(x, None, 0, y, rows, cols, sp)
+
+        fn()
+        ms = time_region(fn, max(1, steps // 2)) / len(ins)
+        el = rows * cols
+        res[str(cols)] = {"rows": rows, "kernel": ip.softmax_kernel_family(cols),
+                          "avg_launch_us": ms * 1e3,
+                          "pct_of_hbm_peak": 100.0 * SOFTMAX_BYTES_PER_EL * el / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del ins, outs
+    torch.cuda.empty_cache()
+    return res
+
+
 def cpu_baseline(name, budget_units=12):
     """The CPU oracle on the first layers of the same workload: once on one thread, then the
     same calls row-partitioned over every host core (threads; the C calls release the GIL)."""
@@ -366,6 +398,7 @@ def main():
             out["extra"][name] = e
     if not args.no_extra:
         out["extra"]["fused_requant"] = measure_fused(args.steps)
+        out["extra"]["row_lengths"] = measure_row_lengths(args.steps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(out))

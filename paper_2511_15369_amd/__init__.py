@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     softmax_i32,
     softmax_i32_batch,
     softmax_i32_layers,
+    softmax_kernel_family,
     softmax_problem,
     softmax_prepare,
     strerror,

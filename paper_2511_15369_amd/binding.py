@@ -163,6 +163,24 @@ def gelu_prepare(s_in: float, s_out: float, zp_in: int, zp_out: int, variant: in
 
 
 # ----------------------------------------------------------------------------- device calls
+def softmax_kernel_family(cols: int) -> str:
+    """Which softmax kernel serves 16-byte aligned tensors of this row length."""
+    fn = load().iptq_debug_softmax_layout
+    fn.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
+    fn.restype = ctypes.c_int
+    out = (ctypes.c_int32 * 12)()
+    _check(fn(cols, out), "iptq_debug_softmax_layout")
+    if out[7]:
+        return "compiled row length"
+    if out[0]:
+        return "slab, %d lanes x %d blocks per row" % (out[1], out[2])
+    if out[4]:
+        return "wavefront per row, %d passes" % out[5]
+    if out[9]:
+        return "workgroup of %d wavefronts per row, %d passes" % (out[10], out[11])
+    return "three-pass"
+
+
 def requant(d_in, d_out, n: int, out_is_signed: int, p: Dyadic):
     import torch
     _need(d_in, torch.int32, "d_in")

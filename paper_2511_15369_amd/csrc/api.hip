@@ -222,7 +222,8 @@ extern "C" int iptq_debug_softmax_plan(const iptq_softmax_params_t *p, int64_t r
 
 // Layout the run-time-row-length kernels would use for a row length:
 // out12 = {dyn ok, dyn lanes, dyn slots, dyn blocks per lane, wide ok, wide passes, wide slots,
-//          0, 0, workgroup-per-row ok, its wavefronts, its slots}.
+//          1 if the row length has a compiled kernel, 0, workgroup-per-row ok, its wavefronts,
+//          its slots}.
 extern "C" int iptq_debug_softmax_layout(int32_t cols, int32_t *out9)
 {
     if (!out9) return IPTQ_ERR_NULL;
@@ -234,7 +235,8 @@ extern "C" int iptq_debug_softmax_layout(int32_t cols, int32_t *out9)
     out9[4] = wide_geometry(cols, &a, &b) ? 1 : 0;
     out9[5] = a; out9[6] = b;
     a = b = 0;
-    out9[7] = out9[8] = 0;
+    out9[7] = softmax_rows_compiled(cols) ? 1 : 0;
+    out9[8] = 0;
     a = b = 0;
     out9[9] = wgrow_geometry(cols, &a, &b) ? 1 : 0;
     out9[10] = a; out9[11] = b;

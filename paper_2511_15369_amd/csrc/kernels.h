@@ -41,6 +41,7 @@ hipError_t softmax_wgrow_launch(const SoftmaxCall &c, int32_t cols, int post_mod
                                 hipStream_t stream);
 // Host-side layout choices of the run-time-row-length kernels (false: the kernel does not
 // serve that row length).
+bool softmax_rows_compiled(int32_t cols);         // a kernel with this row length compiled in exists
 bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used);
 bool wide_geometry(int32_t cols, int *passes, int *slots);
 bool wgrow_geometry(int32_t cols, int *waves, int *slots);

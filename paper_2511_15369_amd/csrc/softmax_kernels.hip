@@ -87,6 +87,14 @@ static hipError_t launch_generic(const int32_t *scores, const int32_t *bias, uin
 // fixed-row-length kernel are grouped, up to kBatchMax per launch, while they agree on what
 // the kernel instantiation fixes (bias or not, post step, packed or 32-bit arithmetic); the
 // rows a slab decomposition leaves over, and calls it cannot serve, go to the generic kernel.
+bool softmax_rows_compiled(int32_t cols)
+{
+#define IPTQ_IS_ROWS_SHAPE(COLS, K) if (cols == COLS) return true;
+    IPTQ_ROWS_SHAPES(IPTQ_IS_ROWS_SHAPE)
+#undef IPTQ_IS_ROWS_SHAPE
+    return false;
+}
+
 hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols, hipStream_t stream)
 {
     int rpw = 0;                                      // rows per wavefront of the compiled row length
