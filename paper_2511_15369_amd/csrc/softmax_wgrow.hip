@@ -11,9 +11,10 @@ namespace iptq {
 // other computes (66-78 % of the HBM roofline); the 14 to 20 passes that 8 wavefronts would
 // need beyond 26618 scores leave one workgroup per compute unit, and so do 16 wavefronts
 // (both 46-50 %; 16 wavefronts compile faster).
-bool wgrow_geometry(int32_t cols, int *waves, int *slots)
+bool wgrow_geometry(int32_t cols, int *waves, int *slots, bool off_grid)
 {
-    const int nb_max = (cols % 4 == 0) ? cols / 4 : ((cols % 2 == 0) ? (cols + 2 + 3) / 4 : (cols + 3 + 3) / 4);
+    // off_grid: as for wide_geometry
+    const int nb_max = (off_grid || cols % 2 != 0) ? (cols + 3 + 3) / 4 : ((cols % 4 == 0) ? cols / 4 : (cols + 2 + 3) / 4);
     int w = 4;
     if ((nb_max + 255) / 256 > 13) w = 8;
     if ((nb_max + 511) / 512 > 13) w = 16;
@@ -30,13 +31,13 @@ hipError_t softmax_wgrow_launch(const SoftmaxCall &c, int32_t cols, int post_mod
 {
     *done = 0;
     int waves = 0, slots = 0;
-    if (!wgrow_geometry(cols, &waves, &slots)) return hipSuccess;
     // The tensor may start anywhere on the 4-byte grid if the output starts at the same offset
     // from its own 4-byte grid (views cut at the same element of both tensors do); the additive
     // table is indexed block by block and needs both on the 16-byte grid.
     const uintptr_t sa = reinterpret_cast<uintptr_t>(c.scores), oa = reinterpret_cast<uintptr_t>(c.out);
     const int base_off = (int)((sa & 15) >> 2);
     if ((sa & 3) != 0 || ((oa - (uintptr_t)base_off) & 3) != 0) return hipSuccess;
+    if (!wgrow_geometry(cols, &waves, &slots, base_off != 0)) return hipSuccess;
     const bool has_bias = c.bias != nullptr;
     const bool bias_ok = !has_bias || (base_off == 0 && (reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
                                        ((int64_t)c.P.bias_period_rows * cols) % 4 == 0);

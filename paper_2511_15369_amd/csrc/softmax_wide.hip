@@ -9,9 +9,11 @@ namespace iptq {
 // compiled for that count serves it and relies on it).  Returns false beyond 16 passes (rows of
 // more than 4093 scores, 4096 if a multiple of 4): with more registers per lane than that a
 // workgroup per row is faster (softmax_wgrow.h).
-bool wide_geometry(int32_t cols, int *passes, int *slots)
+bool wide_geometry(int32_t cols, int *passes, int *slots, bool off_grid)
 {
-    const int nb_max = (cols % 4 == 0) ? cols / 4 : ((cols % 2 == 0) ? (cols + 2 + 3) / 4 : (cols + 3 + 3) / 4);
+    // off_grid: the tensor itself starts off the 16-byte grid, so a row can start at any element of
+    // a block whatever the row length
+    const int nb_max = (off_grid || cols % 2 != 0) ? (cols + 3 + 3) / 4 : ((cols % 4 == 0) ? cols / 4 : (cols + 2 + 3) / 4);
     const int n = (nb_max + 63) / 64;
     if (n > 16) return false;
     *passes = n;
@@ -19,20 +21,20 @@ bool wide_geometry(int32_t cols, int *passes, int *slots)
     return true;
 }
 
-// Every row of one call if the call qualifies: rows of up to 16 passes, 16-byte aligned
-// tensors; *done receives the number of rows served (0: not served, nothing enqueued).
+// Every row of one call if the call qualifies (rows of up to 16 passes, pointers as checked
+// below); *done receives the number of rows served (0: not served, nothing enqueued).
 hipError_t softmax_wide_launch(const SoftmaxCall &c, int32_t cols, int post_mode, int64_t *done,
                                hipStream_t stream)
 {
     *done = 0;
     int n = 0, slots = 0;
-    if (!wide_geometry(cols, &n, &slots)) return hipSuccess;
     // The tensor may start anywhere on the 4-byte grid if the output starts at the same offset
     // from its own 4-byte grid (views cut at the same element of both tensors do); the additive
     // table is indexed block by block and needs both on the 16-byte grid.
     const uintptr_t sa = reinterpret_cast<uintptr_t>(c.scores), oa = reinterpret_cast<uintptr_t>(c.out);
     const int base_off = (int)((sa & 15) >> 2);
     if ((sa & 3) != 0 || ((oa - (uintptr_t)base_off) & 3) != 0) return hipSuccess;
+    if (!wide_geometry(cols, &n, &slots, base_off != 0)) return hipSuccess;
     const bool has_bias = c.bias != nullptr;
     const bool bias_ok = !has_bias || (base_off == 0 && (reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
                                        ((int64_t)c.P.bias_period_rows * cols) % 4 == 0);

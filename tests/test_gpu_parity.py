@@ -139,11 +139,13 @@ def test_softmax_partial_last_slab(cols):
             assert (got[rows * cols:] == 0x5A).all(), (rows, with_bias)
 
 
-@pytest.mark.parametrize("cols", [49, 197, 800, 1025, 5117])
+@pytest.mark.parametrize("cols", [49, 197, 256, 768, 800, 1025, 4096, 5117, 13312])
 def test_softmax_views_off_the_16_byte_grid(cols):
     """Score and output tensors that are views into larger buffers, cut at the same element (so
     the scores start off the 16-byte grid and the output at the matching byte), and views cut
-    at different elements: every row is right and no byte outside the view is written."""
+    at different elements: every row is right and no byte outside the view is written.  (256,
+    768, 4096 and 13312 columns: off the grid a row touches one block more than on it, which
+    takes one pass more.)"""
     import torch
     import paper_2511_15369_amd as ip
     rng = np.random.default_rng(8100 + cols)
