@@ -5,7 +5,8 @@ import numpy as np
 import pytest
 
 from oracle import ref
-from tests.helpers import gpu_gelu_i8, gpu_gelu_i32, gpu_softmax
+from oracle import prepare
+from tests.helpers import gpu_gelu_i8, gpu_gelu_i32, gpu_softmax, lib_softmax
 
 pytestmark = pytest.mark.gpu
 I32_MIN, I32_MAX = -(2 ** 31), 2 ** 31 - 1
@@ -66,6 +67,58 @@ def test_softmax_random_domain(seed):
         for algo in (0, 1, 2, 3):
             got = gpu_softmax(x, p, bias, period, algo=algo)
             assert np.array_equal(got, want), (algo, cols, rows, p)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_softmax_random_row_lengths_and_views(seed):
+    """Row lengths drawn from 1 to 41000 (every layout of the run-time-length kernels), row
+    counts that leave partial slabs, additive tables of several periods, and views that start
+    off the 16-byte grid at the same element of the score and output buffers: bit-exact, and no
+    byte outside the view written."""
+    import torch
+    import paper_2511_15369_amd as ip
+    rng = np.random.default_rng(3000 + seed)
+    for it in range(250):
+        cols = int(np.exp(rng.uniform(0, np.log(41000)))) if rng.integers(0, 4) else int(rng.integers(1, 900))
+        cols = max(1, min(cols, 41000))
+        rows = int(rng.integers(1, 300)) if cols < 1000 else int(rng.integers(1, 7))
+        signed = int(rng.integers(0, 2))
+        p = prepare.softmax_prepare(2.0 ** rng.uniform(-10, -4), cols, int(rng.integers(0, 2)), out_is_signed=signed)
+        if rng.integers(0, 4) == 0:
+            p.post = ref.Dyadic(int(rng.integers(1, 300)), int(rng.integers(0, 9)), int(rng.integers(-5, 6)),
+                                -128 if signed else 0, 127 if signed else 255)
+        if rng.integers(0, 4) == 0:
+            p.pre_m, p.pre_s = int(rng.integers(1, 32768)), int(rng.integers(8, 30))
+        kind = rng.integers(0, 3)
+        scale = (3.0 if kind == 0 else 40.0) * p.i0
+        if (p.pre_m, p.pre_s) != (1, 0):
+            scale *= 2.0 ** p.pre_s / p.pre_m
+        x = np.rint(rng.standard_normal((rows, cols)) * min(scale, 2.0 ** 30))
+        if kind == 2:
+            x += rng.integers(-2 ** 30, 2 ** 30)
+        x = np.clip(x, I32_MIN, I32_MAX).astype(np.int32)
+        x[rng.random((rows, cols)) < 0.03] = I32_MIN
+        if rng.integers(0, 8) == 0:
+            x[rng.integers(0, rows)] = I32_MIN
+        bias, period, off = None, 0, 0
+        if rng.integers(0, 3) == 0:
+            period = int(rng.choice([1, 2, 3, 4, 8, 64]))
+            bias = np.rint(rng.standard_normal((period, cols)) * 2.0 * p.i0).astype(np.int32)
+            bias[rng.random((period, cols)) < 0.02] = I32_MIN
+        elif rng.integers(0, 2):
+            off = int(rng.integers(1, 8))
+        want = ref.softmax_i32(x, p, bias, period).view(np.uint8).reshape(-1)
+        n = rows * cols
+        d_in = torch.zeros(n + 16, dtype=torch.int32, device="cuda")
+        d_in[off:off + n] = torch.from_numpy(x.reshape(-1)).cuda()
+        d_bias = torch.from_numpy(bias).cuda() if bias is not None else None
+        for algo in (0, 2, 3):
+            d_out = torch.full((n + 32,), 0x5A, dtype=torch.uint8, device="cuda").view(torch.int8 if signed else torch.uint8)
+            ip.softmax_i32(d_in[off:off + n], d_bias, period, d_out[off:off + n], rows, cols, lib_softmax(p, algo))
+            torch.cuda.synchronize()
+            got = d_out.view(torch.uint8).cpu().numpy()
+            assert np.array_equal(got[off:off + n], want), (it, cols, rows, algo, off, period, p)
+            assert (got[:off] == 0x5A).all() and (got[off + n:] == 0x5A).all(), (it, cols, rows, algo, off)
 
 
 @pytest.mark.parametrize("seed", range(3))
