@@ -103,3 +103,77 @@ def test_batched_vit_b_layers_at_full_size():
     n = small_rows * units[0].cols
     assert np.array_equal(got[:n].reshape(small_rows, -1), ref.softmax_i32(cases[0].scores[:small_rows], p))
     assert (got[n:] == 0x5A).all()
+
+
+@pytest.mark.parametrize("cols", [197, 64, 1025])
+def test_softmax_of_more_than_2_31_scores(cols):
+    """One call over more than 2^31 scores (64-bit element offsets in every kernel family:
+    compiled row length, run-time-length slab, wavefront per row).  The tensor repeats a block
+    of 1009 rows (a prime, so slabs meet it at every phase); the whole output is compared on
+    the GPU with the oracle's result for that block, repeated."""
+    import torch
+    import paper_2511_15369_amd as ip
+    from tests.helpers import lib_softmax
+    block_rows = 1009
+    reps = (2 ** 31) // (block_rows * cols) + 1
+    rows = block_rows * reps
+    assert rows * cols > 2 ** 31
+    print("softmax of", rows, "x", cols, flush=True)
+    rng = np.random.default_rng(cols)
+    base = np.rint(rng.standard_normal((block_rows, cols)) * 900).astype(np.int32)
+    base[5, : cols // 2] = -(2 ** 31)
+    p = prepare.softmax_prepare(2.0 ** -7.4, cols, 1)
+    want = torch.from_numpy(ref.softmax_i32(base, p).reshape(-1)).cuda()
+    d_in = torch.from_numpy(base).cuda().repeat(reps, 1)
+    d_out = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda")
+    ip.softmax_i32(d_in, None, 0, d_out, rows, cols, lib_softmax(p))
+    torch.cuda.synchronize()
+    del d_in
+    tiles = d_out.view(reps, block_rows * cols)
+    for lo in range(0, reps, 512):                   # in pieces: the comparison's temporaries stay small
+        assert bool((tiles[lo:lo + 512] == want.view(1, -1)).all()), lo
+
+
+def test_elementwise_calls_of_more_than_2_31_elements():
+    """GELU over more than 2^32 int8 codes and requantization over more than 2^31 int32
+    values: periodic inputs (period 1021), the whole output compared with the oracle's period."""
+    import torch
+    import paper_2511_15369_amd as ip
+    from tests.helpers import lib_dyadic, lib_gelu
+    period = 1021
+    rng = np.random.default_rng(77)
+
+    n = 2 ** 32 + 4099
+    pat = rng.integers(-128, 128, size=period, dtype=np.int8)
+    gp = prepare.gelu_prepare(2.0 ** -4.6, 2.0 ** -5.1, 3, -4, 1)
+    want = torch.from_numpy(ref.gelu_i8(pat, gp)).cuda()
+    reps = n // period + 1
+    d_x = torch.from_numpy(pat).cuda().repeat(reps)[:n].contiguous()
+    d_y = torch.zeros(n, dtype=torch.int8, device="cuda")
+    print("gelu of", n, flush=True)
+    ip.gelu_i8(d_x, d_y, n, lib_gelu(gp))
+    torch.cuda.synchronize()
+    del d_x
+    full = (n // period) * period
+    tiles = d_y[:full].view(-1, period)
+    for lo in range(0, tiles.shape[0], 1 << 18):
+        assert bool((tiles[lo:lo + (1 << 18)] == want.view(1, -1)).all()), lo
+    assert bool((d_y[full:] == want[: n - full]).all())
+    del d_y, tiles
+
+    n = 2 ** 31 + 1031
+    pat32 = rng.integers(-(2 ** 31), 2 ** 31, size=period).astype(np.int32)
+    dy = ref.Dyadic(23170, 38, -3, -128, 127)
+    want = torch.from_numpy(ref.requant(pat32, dy, 1)).cuda()
+    reps = n // period + 1
+    d_x = torch.from_numpy(pat32).cuda().repeat(reps)[:n].contiguous()
+    d_y = torch.zeros(n, dtype=torch.int8, device="cuda")
+    print("requant of", n, flush=True)
+    ip.requant(d_x, d_y, n, 1, lib_dyadic(dy))
+    torch.cuda.synchronize()
+    del d_x
+    full = (n // period) * period
+    tiles = d_y[:full].view(-1, period)
+    for lo in range(0, tiles.shape[0], 1 << 18):
+        assert bool((tiles[lo:lo + (1 << 18)] == want.view(1, -1)).all()), lo
+    assert bool((d_y[full:] == want[: n - full]).all())
