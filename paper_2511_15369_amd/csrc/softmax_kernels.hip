@@ -148,7 +148,19 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             it.scores = c.scores; it.bias = c.bias; it.out = c.out;
             it.n_slabs = n_slabs; it.first_wg = total_wgs; it.P = c.P;
             it.tail_rows = (int32_t)(c.rows % rpw);
-            total_wgs += (unsigned)((n_slabs + kRowsWpb - 1) / kRowsWpb);
+            it.share_q = 0; it.share_magic = 0; it.share_sh = 0;
+            int64_t n_wgs = (n_slabs + kRowsWpb - 1) / kRowsWpb;
+            if (has_bias) {
+                int64_t a = c.P.bias_period_rows, b = rpw;
+                while (b != 0) { const int64_t t = a % b; a = b; b = t; }      // a = gcd
+                const int64_t q = c.P.bias_period_rows / a;
+                if (q >= 2 && q < 65536 && q * kRowsWpb <= n_slabs &&
+                    make_magic_u32((uint32_t)q, 31, &it.share_magic, &it.share_sh)) {
+                    it.share_q = (uint32_t)q;
+                    n_wgs = (n_slabs + kRowsWpb * q - 1) / (kRowsWpb * q) * q;
+                }
+            }
+            total_wgs += (unsigned)n_wgs;
             done[i] = c.rows;
         }
         flush();

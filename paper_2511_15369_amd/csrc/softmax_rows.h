@@ -47,6 +47,14 @@ struct SoftmaxItem {
     int64_t n_slabs;      // the last one may be partial
     uint32_t first_wg;
     int32_t tail_rows;    // rows of the last slab if it is partial, else 0
+    // Slabs whose first rows are congruent modulo the bias period read the same rows of the
+    // additive table.  share_q = period / gcd(period, rows per slab) is the distance, in slabs,
+    // between two such slabs; with share_q != 0 the wavefronts of a workgroup take slabs
+    // share_q apart (workgroup w, wavefront v: slab (w / q) * WPB * q + v * q + w % q), so that
+    // the table rows reach the compute unit's L1 once per workgroup instead of once per
+    // wavefront.  0: consecutive slabs.
+    uint32_t share_q, share_magic;
+    int32_t share_sh;     // w / share_q == mulhi(w, share_magic) >> share_sh
     SoftmaxDev P;
 };
 struct SoftmaxBatch {
@@ -283,7 +291,12 @@ softmax_rows_kernel(SoftmaxBatch B)
     const int32_t *__restrict__ scores = I.scores;
     const int32_t *__restrict__ bias = I.bias;
     uint8_t *__restrict__ out = I.out;
-    const int64_t slab = (int64_t)(blockIdx.x - I.first_wg) * kRowsWpb + wv;
+    const uint32_t lw = blockIdx.x - I.first_wg;
+    int64_t slab = (int64_t)lw * kRowsWpb + wv;
+    if (BIAS && I.share_q != 0) {
+        const uint32_t g = mulhi_u32(lw, I.share_magic) >> I.share_sh;
+        slab = (int64_t)g * (kRowsWpb * I.share_q) + (uint32_t)wv * I.share_q + (lw - g * I.share_q);
+    }
     if (slab >= I.n_slabs) return;                    // no workgroup barrier below
 
     uint8_t *lds = lds_all[wv];
