@@ -34,6 +34,10 @@ struct DynArgs {
     int32_t cols;
     int32_t wave_lds;     // LDS bytes per wavefront: slab (16-byte multiple) + post table
     int32_t post_mode;    // PM_NONE / PM_CLAMP127 / PM_GENERAL, applied to the packed bytes
+    // with an additive table: the wavefronts of a workgroup take slabs share_q apart, which read
+    // the same table rows (see SoftmaxItem); 0: consecutive slabs
+    uint32_t share_q, share_magic;
+    int32_t share_sh;
     SoftmaxDev P;
 };
 
@@ -46,7 +50,12 @@ softmax_rowsdyn_kernel(DynArgs A)
     const SoftmaxDev &P = A.P;
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
-    const int64_t slab = (int64_t)blockIdx.x * (blockDim.x >> 6) + wv;
+    const uint32_t wpb = blockDim.x >> 6;
+    int64_t slab = (int64_t)blockIdx.x * wpb + wv;
+    if (A.share_q != 0) {
+        const uint32_t g = mulhi_u32(blockIdx.x, A.share_magic) >> A.share_sh;
+        slab = (int64_t)g * (wpb * A.share_q) + (uint32_t)wv * A.share_q + (blockIdx.x - g * A.share_q);
+    }
     if (slab >= A.n_slabs) return;                    // no workgroup barrier below
 
     const int cols = A.cols;

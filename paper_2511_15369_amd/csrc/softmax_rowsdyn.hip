@@ -52,7 +52,19 @@ hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_m
     int wpb = 65536 / A.wave_lds;                     // wavefronts per workgroup: 1..4
     if (wpb > 4) wpb = 4;
     if (wpb < 1) return hipSuccess;
-    const dim3 grid((unsigned)((n_slabs + wpb - 1) / wpb)), block(64 * wpb);
+    int64_t n_wgs = (n_slabs + wpb - 1) / wpb;
+    A.share_q = 0; A.share_magic = 0; A.share_sh = 0;
+    if (has_bias && wpb > 1) {
+        int64_t a = c.P.bias_period_rows, b = rpw;
+        while (b != 0) { const int64_t t = a % b; a = b; b = t; }              // a = gcd
+        const int64_t q = c.P.bias_period_rows / a;
+        if (q >= 2 && q < 65536 && q * wpb <= n_slabs &&
+            make_magic_u32((uint32_t)q, 31, &A.share_magic, &A.share_sh)) {
+            A.share_q = (uint32_t)q;
+            n_wgs = (n_slabs + (int64_t)wpb * q - 1) / ((int64_t)wpb * q) * q;
+        }
+    }
+    const dim3 grid((unsigned)n_wgs), block(64 * wpb);
     const size_t lds = (size_t)A.wave_lds * wpb;
     bool launched;
     if (k == 2) launched = slots <= 4 ? rowsdyn_launch_k2_short(A, slots, c.P.mode16, grid, block, lds, stream)

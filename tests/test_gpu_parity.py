@@ -139,6 +139,25 @@ def test_softmax_partial_last_slab(cols):
             assert (got[rows * cols:] == 0x5A).all(), (rows, with_bias)
 
 
+@pytest.mark.parametrize("cols,period", [(49, 196), (49, 392), (49, 12544), (197, 197), (197, 2364), (64, 256),
+                                         (64, 200), (100, 96), (100, 45), (256, 1024), (576, 2304), (33, 7)])
+def test_softmax_additive_table_with_workgroups_that_share_its_rows(cols, period):
+    """With an additive table the wavefronts of a workgroup take slabs that start at congruent
+    rows modulo the table's period (so that they read the same table rows): every slab must
+    still be served exactly once, for periods that divide the slab, share a factor with it or
+    are coprime to it, with a row count that leaves the last group of slabs incomplete."""
+    rng = np.random.default_rng(cols * 100003 + period)
+    for rows in (period * 9 + 5, 4111, 257):
+        scores = np.rint(rng.standard_normal((rows, cols)) * 400).astype(np.int32)
+        scores[rng.random((rows, cols)) < 0.01] = INT32_MIN
+        bias = np.rint(rng.standard_normal((period, cols)) * 60).astype(np.int32)
+        bias[rng.random((period, cols)) < 0.01] = INT32_MIN
+        p = prepare.softmax_prepare(2.0 ** -6.7, cols, 1)
+        want = ref.softmax_i32(scores, p, bias, period)
+        for algo in (0, 2):
+            assert np.array_equal(gpu_softmax(scores, p, bias, period, algo=algo), want), (rows, algo)
+
+
 @pytest.mark.parametrize("cols", [49, 197, 256, 768, 800, 1025, 4096, 5117, 13312])
 def test_softmax_views_off_the_16_byte_grid(cols):
     """Score and output tensors that are views into larger buffers, cut at the same element (so
