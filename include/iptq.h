@@ -150,6 +150,9 @@ int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t out_is_sig
  * bias_period_rows = heads * window_tokens; d_out: rows * cols bytes (device), uint8_t or
  * int8_t per p->out_is_signed, must not overlap d_scores.
  * 0 <= rows < 2^31 (0 is a no-op), 1 <= cols <= IPTQ_COLS_MAX.
+ * The post step runs at full speed when it is the identity, the int8 clip at 127, or the shift to
+ * signed codes p - 128 (post = {1, 0, -128, -128, qmax >= 0}: the operand form of a signed 8-bit
+ * matrix instruction for the product with V); any other post step goes through a small table.
  * Every shape gives the same bytes; speed depends on it.  Fastest: 16-byte aligned d_scores and
  * d_out (and d_bias, with bias_period_rows * cols a multiple of 4) and a row length of 197, 49,
  * 198, 144, 257 or 577; any other row length up to 40957 runs in the register-resident kernels

@@ -135,6 +135,8 @@ int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int
     }
     out->post_m = p->post.m; out->post_s = p->post.s; out->post_zp = p->post.zp;
     out->qmin = p->post.qmin; out->qmax = p->post.qmax;
+    out->post_xor = (p->out_is_signed == 1 && p->post.m == 1 && p->post.s == 0 && p->post.zp == -128 &&
+                     p->post.qmin == -128 && p->post.qmax >= 0) ? 0x80808080u : 0u;
     out->variant = p->variant;
     // Packed 16-bit path: clamped delta, n and (i0 << N) must fit 16 bits, the per-row factor
     // shifted to the top byte must fit 24 bits, and a 24-bit divider multiplier must be exact.

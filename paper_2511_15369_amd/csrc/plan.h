@@ -30,6 +30,10 @@ struct SoftmaxDev {
     int32_t pre_sh2;
     int64_t pre_rnd;
     int32_t post_m, post_s, post_zp, qmin, qmax;
+    // The post step "minus 128, no clip inside [-128, 0]" (signed int8 probabilities around a
+    // zero-point of -128, the operand form of a signed 8-bit matrix instruction): on bytes that
+    // are at most 128 it is one exclusive-or.  0x80808080 then, else 0.
+    uint32_t post_xor;
     int32_t variant;
     // bias addressing: row index modulo the period by multiply-high
     int32_t bias_period_rows;

@@ -61,6 +61,7 @@ softmax_generic_kernel(const int32_t *__restrict__ scores, const int32_t *__rest
 
 static int post_mode_of(const SoftmaxDev &P, int out_bits)
 {
+    if (P.post_xor != 0) return PM_NONE;              // p - 128: one exclusive-or on the packed bytes
     const bool identity = P.post_m == 1 && P.post_s == 0 && P.post_zp == 0 && P.qmin <= 0;
     if (!identity) return PM_GENERAL;
     if (P.qmax >= (1 << (out_bits - 1))) return PM_NONE;

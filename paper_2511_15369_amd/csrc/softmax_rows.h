@@ -423,6 +423,10 @@ softmax_rows_kernel(SoftmaxBatch B)
 
     if (P.variant == 0) softmax_slab_math<K, SLOTS, MODE, 0, POSTMODE>(x, w, mx, lower, any_low, lut, P);
     else softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE>(x, w, mx, lower, any_low, lut, P);
+    if (POSTMODE == PM_NONE && P.post_xor != 0) {     // signed output around the zero-point -128
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) w[s] ^= P.post_xor;
+    }
 
     // ---- assemble the slab's bytes in LDS
     uint32_t *lds32 = reinterpret_cast<uint32_t *>(lds);

@@ -157,6 +157,9 @@ softmax_wide_kernel(WideArgs A)
     } else if (post_mode == PM_GENERAL) {
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) w[s] = post_lut_gather(lut, w[s]);
+    } else if (P.post_xor != 0) {                     // signed output around the zero-point -128
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) w[s] ^= P.post_xor;
     }
 
     // ---- write back: whole blocks as dwords, the two shared edge blocks byte by byte

@@ -139,6 +139,31 @@ def test_softmax_partial_last_slab(cols):
             assert (got[rows * cols:] == 0x5A).all(), (rows, with_bias)
 
 
+@pytest.mark.parametrize("cols", [49, 197, 64, 600, 1025, 4097])
+def test_softmax_signed_output_around_zero_point_minus_128(cols):
+    """post = (1, 0, -128, -128, 127): probabilities as int8 codes p - 128, the operand form of a
+    signed 8-bit matrix instruction.  One exclusive-or on the packed bytes in the kernels; the
+    oracle evaluates the general step.  One-hot rows (p = 128 -> 0) and fully masked rows
+    (p = 0 -> -128) included; a narrower clip must still take the general route."""
+    rng = np.random.default_rng(4300 + cols)
+    rows = 150 if cols < 1000 else 9
+    scores = np.rint(rng.standard_normal((rows, cols)) * 500).astype(np.int32)
+    scores[0, :] = -1000000
+    scores[0, cols // 2] = 1000000                    # one-hot
+    scores[1, :] = INT32_MIN                          # fully masked
+    bias = np.rint(rng.standard_normal((4, cols)) * 30).astype(np.int32)
+    for variant, out_bits in ((0, 8), (1, 8), (1, 6)):
+        p = prepare.softmax_prepare(2.0 ** -7.0, cols, variant, out_is_signed=1)
+        p.out_bits = out_bits
+        for qmax in (127, 0, -1):
+            p.post = ref.Dyadic(1, 0, -128, -128, qmax)
+            for b, period in ((None, 0), (bias, 4)):
+                want = ref.softmax_i32(scores, p, b, period)
+                assert want[0, cols // 2] == min(2 ** (out_bits - 1) - 128, qmax) and (want[1] == -128).all()
+                for algo in (0, 1, 2, 3):
+                    assert np.array_equal(gpu_softmax(scores, p, b, period, algo=algo), want), (variant, qmax, algo)
+
+
 @pytest.mark.parametrize("cols,period", [(49, 196), (49, 392), (49, 12544), (197, 197), (197, 2364), (64, 256),
                                          (64, 200), (100, 96), (100, 45), (256, 1024), (576, 2304), (33, 7)])
 def test_softmax_additive_table_with_workgroups_that_share_its_rows(cols, period):
