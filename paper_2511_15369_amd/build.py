@@ -20,7 +20,7 @@ SOURCES = ["softmax_wgrow_w4_hi.hip", "softmax_wgrow_w8_hi.hip", "softmax_wgrow_
            "softmax_wide_p14_16.hip", "softmax_wide_p11_13.hip", "softmax_wide_p7_10.hip", "softmax_wide_p1_6.hip", "softmax_rowsdyn_k16_long.hip",
            "softmax_rows_577.hip", "softmax_rows_257.hip", "softmax_rows_197.hip", "softmax_rows_198.hip",
            "softmax_rows_144.hip", "softmax_rows_49.hip", "softmax_rows_197_k8.hip", "softmax_rows_198_k8.hip",
-           "softmax_rowsdyn_k2.hip", "softmax_rowsdyn_k2_short.hip", "softmax_rowsdyn_k4.hip", "softmax_rowsdyn_k8.hip",
+           "softmax_rowsdyn_k2.hip", "softmax_rowsdyn_k1.hip", "softmax_rowsdyn_k4.hip", "softmax_rowsdyn_k8.hip",
            "softmax_rowsdyn_k16.hip", "softmax_kernels.hip", "elementwise_kernels.hip",
            "softmax_rowsdyn.hip", "softmax_wide.hip", "softmax_wgrow.hip", "api.hip", "plan.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

@@ -287,7 +287,7 @@ static void rowsdyn_launch_ks(const DynArgs &A, int mode, dim3 grid, dim3 block,
 
 // One launcher per group of layouts, each defined in its own translation unit so that the
 // instantiations compile in parallel.  Each returns false for a slot count it does not hold.
-bool rowsdyn_launch_k2_short(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);   // 1..4
+bool rowsdyn_launch_k1(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);         // 1..8
 bool rowsdyn_launch_k2(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);         // 5..8
 bool rowsdyn_launch_k4(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);         // 5..8
 bool rowsdyn_launch_k8(const DynArgs &, int slots, int mode, dim3, dim3, size_t, hipStream_t);         // 5..8

@@ -16,7 +16,7 @@ namespace iptq {
 bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used)
 {
     const int nb_max = (cols % 4 == 0) ? cols / 4 : ((cols % 2 == 0) ? (cols + 2 + 3) / 4 : (cols + 3 + 3) / 4);
-    int k = 2;
+    int k = 1;
     while (k < 16 && (nb_max + k - 1) / k > 8) k *= 2;
     const int n = (nb_max + k - 1) / k;
     if (n > 10) return false;
@@ -67,8 +67,8 @@ hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_m
     const dim3 grid((unsigned)n_wgs), block(64 * wpb);
     const size_t lds = (size_t)A.wave_lds * wpb;
     bool launched;
-    if (k == 2) launched = slots <= 4 ? rowsdyn_launch_k2_short(A, slots, c.P.mode16, grid, block, lds, stream)
-                                      : rowsdyn_launch_k2(A, slots, c.P.mode16, grid, block, lds, stream);
+    if (k == 1) launched = rowsdyn_launch_k1(A, slots, c.P.mode16, grid, block, lds, stream);
+    else if (k == 2) launched = rowsdyn_launch_k2(A, slots, c.P.mode16, grid, block, lds, stream);
     else if (k == 4) launched = rowsdyn_launch_k4(A, slots, c.P.mode16, grid, block, lds, stream);
     else if (k == 8) launched = rowsdyn_launch_k8(A, slots, c.P.mode16, grid, block, lds, stream);
     else launched = slots <= 8 ? rowsdyn_launch_k16(A, slots, c.P.mode16, grid, block, lds, stream)

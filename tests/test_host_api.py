@@ -265,8 +265,8 @@ def test_run_time_row_length_layouts_fit_what_the_kernels_assume():
             nb_max = (cols + 3 + 3) // 4
         assert nb_max >= max(((phi + cols + 3) >> 2) for phi in range(0, 4, 4 if cols % 4 == 0 else (2 if cols % 2 == 0 else 1)))
         if dyn_ok:
-            assert k in (2, 4, 8, 16) and 1 <= slots <= 10 and (slots <= 8 or k == 16)
-            assert (k == 2 or slots >= 5) and n_used == slots    # the layouts that are instantiated
+            assert k in (1, 2, 4, 8, 16) and 1 <= slots <= 10 and (slots <= 8 or k == 16)
+            assert (k == 1 or slots >= 5) and n_used == slots    # the layouts that are instantiated
             assert slots == -(-nb_max // k)                  # exactly: the kernel's slot roles rely on it
             nb_min = min(((phi + cols + 3) >> 2) for phi in range(0, 4, 4 if cols % 4 == 0 else (2 if cols % 2 == 0 else 1)))
             assert nb_min >= k * (slots - 1)                 # slots 0 .. slots-2 exist in every row
