@@ -26,7 +26,7 @@ SOFTMAX_BYTES_PER_EL = 5       # int32 in, one byte out
 GELU_BYTES_PER_EL = 2          # int8 in, int8 out
 # HBM bytes per softmax launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script, keyed by workload (per single-layer / stage-1 launch); None where not measured.
-MEASURED_TRAFFIC = {"vit_b": 301.4e6, "swin_b": 197.7e6}
+MEASURED_TRAFFIC = {"vit_b": 301.4e6, "swin_b": 197.2e6}
 
 
 class Unit:
