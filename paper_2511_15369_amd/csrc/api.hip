@@ -221,16 +221,16 @@ extern "C" int iptq_debug_softmax_plan(const iptq_softmax_params_t *p, int64_t r
 }
 
 // Layout the run-time-row-length kernels would use for a row length:
-// out12 = {dyn ok, dyn lanes, dyn slots, dyn blocks per lane, wide ok, wide passes, wide slots,
+// out12 = {slab ok, its lanes per row, its blocks per lane, the same again, wide ok, wide passes, wide slots,
 //          1 if the row length has a compiled kernel, 0, workgroup-per-row ok, its wavefronts,
 //          its slots}.
 extern "C" int iptq_debug_softmax_layout(int32_t cols, int32_t *out9)
 {
     if (!out9) return IPTQ_ERR_NULL;
     if (cols < 1 || cols > IPTQ_COLS_MAX) return IPTQ_ERR_SHAPE;
-    int a = 0, b = 0, c = 0;
-    out9[0] = rowsdyn_geometry(cols, &a, &b, &c) ? 1 : 0;
-    out9[1] = a; out9[2] = b; out9[3] = c;
+    int a = 0, b = 0;
+    out9[0] = rowsdyn_geometry(cols, &a, &b) ? 1 : 0;
+    out9[1] = a; out9[2] = b; out9[3] = b;
     a = b = 0;
     out9[4] = wide_geometry(cols, &a, &b) ? 1 : 0;
     out9[5] = a; out9[6] = b;

@@ -42,7 +42,7 @@ hipError_t softmax_wgrow_launch(const SoftmaxCall &c, int32_t cols, int post_mod
 // Host-side layout choices of the run-time-row-length kernels (false: the kernel does not
 // serve that row length).
 bool softmax_rows_compiled(int32_t cols);         // a kernel with this row length compiled in exists
-bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used);
+bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots);
 bool wide_geometry(int32_t cols, int *passes, int *slots, bool off_grid = false);
 bool wgrow_geometry(int32_t cols, int *waves, int *slots, bool off_grid = false);
 hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stream);

@@ -192,12 +192,11 @@ struct LaneGroupSum {
     IPTQ_DEV uint32_t operator()(uint32_t v) const { return group_sum_u32<K>(v); }
 };
 
-// DYN: only the first n_used slots hold row data (n_used is wavefront-uniform); the others
-// are skipped.  SUM: how the per-lane partial sums of a row are combined.
-template <int K, int SLOTS, int MODE, int VARIANT, int POSTMODE, bool DYN = false, class SUM = LaneGroupSum<K>>
+// SUM: how the per-lane partial sums of a row are combined.
+template <int K, int SLOTS, int MODE, int VARIANT, int POSTMODE, class SUM = LaneGroupSum<K>>
 IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], int32_t mx,
                                 int32_t lower, bool any_low, const uint8_t *lut, const SoftmaxDev &P,
-                                int n_used = SLOTS, const SUM &row_sum = SUM())
+                                const SUM &row_sum = SUM())
 {
     if (MODE != 0 && !any_low) {
         // ---- packed 16-bit path
@@ -207,7 +206,6 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
         for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (DYN && s >= n_used) continue;
                 const u16x2 qe = bit_exp_pair<VARIANT, MODE == 2>(x[s][2 * h], x[s][2 * h + 1], mx, P);
                 sum = __builtin_amdgcn_udot2(qe, (u16x2){1, 1}, sum, false);
                 e2[s][h] = __builtin_bit_cast(uint32_t, qe);
@@ -216,7 +214,6 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
         const uint32_t f_top = floor_pow2_div(P.m_bits, sum) << (24 - P.p_shift);   // < 2^24
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
-            if (DYN && s >= n_used) continue;
             const uint32_t a = __umul24(e2[s][0] & 0xffffu, f_top), b = __umul24(e2[s][0] >> 16, f_top);
             const uint32_t c = __umul24(e2[s][1] & 0xffffu, f_top), d = __umul24(e2[s][1] >> 16, f_top);
             uint32_t ww = pack_top_bytes(a, b, c, d);
@@ -232,7 +229,6 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
             for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    if (DYN && s >= n_used) continue;
                     const uint32_t q = bit_exp_dev<VARIANT, false>(x[s][e], lower, mx, P);
                     x[s][e] = (int32_t)q;
                     sum += q;
@@ -242,7 +238,6 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
             for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    if (DYN && s >= n_used) continue;
                     const uint32_t q = bit_exp_dev<VARIANT, true>(x[s][e], lower, mx, P);
                     x[s][e] = (int32_t)q;
                     sum += q;
@@ -253,7 +248,6 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
         const uint32_t f_top = P.p_shift <= 24 ? f << (24 - P.p_shift) : 0u;
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
-            if (DYN && s >= n_used) continue;
             if (POSTMODE == PM_GENERAL && P.p_shift <= 24)
                 w[s] = post_lut_gather(lut, normalise4<PM_NONE>((uint32_t)x[s][0], (uint32_t)x[s][1],
                                                                 (uint32_t)x[s][2], (uint32_t)x[s][3], f, f_top, P));

@@ -13,7 +13,7 @@ namespace iptq {
 // Returns false for longer rows: one wavefront per row serves those better (softmax_wide.h;
 // measured 70-75 % against 66-69 % of the HBM roofline at 650 to 829 columns, 57-67 % against
 // 69-75 % at 509 to 600).
-bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used)
+bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots)
 {
     const int nb_max = (cols % 4 == 0) ? cols / 4 : ((cols % 2 == 0) ? (cols + 2 + 3) / 4 : (cols + 3 + 3) / 4);
     int k = 1;
@@ -21,7 +21,6 @@ bool rowsdyn_geometry(int32_t cols, int *lanes, int *slots, int *n_used)
     const int n = (nb_max + k - 1) / k;
     if (n > 10) return false;
     *lanes = k;
-    *n_used = n;
     *slots = n;
     return true;
 }
@@ -32,8 +31,8 @@ hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_m
                                   hipStream_t stream)
 {
     *done = 0;
-    int k = 0, slots = 0, n_used = 0;
-    if (!rowsdyn_geometry(cols, &k, &slots, &n_used)) return hipSuccess;
+    int k = 0, slots = 0;
+    if (!rowsdyn_geometry(cols, &k, &slots)) return hipSuccess;
     const int rpw = 64 / k;
     const bool has_bias = c.bias != nullptr;
     const bool aligned = ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.out)) & 15) == 0;

@@ -152,9 +152,9 @@ softmax_wgrow_kernel(WideArgs A)
     uint32_t w[SLOTS];                                // four probabilities per block, one per byte
     const WorkgroupSum<WAVES> wg_sum{part_sum, wv, lane};
     if (P.variant == 0)
-        softmax_slab_math<64, SLOTS, MODE, 0, PM_NONE, false, WorkgroupSum<WAVES>>(x, w, mx, lower, low_row, lut, P, SLOTS, wg_sum);
+        softmax_slab_math<64, SLOTS, MODE, 0, PM_NONE, WorkgroupSum<WAVES>>(x, w, mx, lower, low_row, lut, P, wg_sum);
     else
-        softmax_slab_math<64, SLOTS, MODE, 1, PM_NONE, false, WorkgroupSum<WAVES>>(x, w, mx, lower, low_row, lut, P, SLOTS, wg_sum);
+        softmax_slab_math<64, SLOTS, MODE, 1, PM_NONE, WorkgroupSum<WAVES>>(x, w, mx, lower, low_row, lut, P, wg_sum);
 
     // ---- post step on the packed bytes (a probability is at most 128)
     if (post_mode == PM_CLAMP127) {
