@@ -98,6 +98,19 @@ bool softmax_rows_compiled(int32_t cols)
 
 hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols, hipStream_t stream)
 {
+    // A single call of a few thousand rows is one generation of wavefronts whatever the kernel:
+    // its duration is one wavefront's chain of load, arithmetic and store, and one wavefront per
+    // row has the shortest (kernel-trace durations, 591 / 2364 / 4728 rows of 197 scores: 3.6 /
+    // 4.1 / 4.9 us against 5.5 / 5.3 / 4.9 us with the slab kernel; 392 to 3136 rows of 49 with a
+    // table: 3.5-4.2 against 5.3-4.7 us; the slab kernels win from about 4000 rows on).
+    constexpr int64_t kTinyRows = 3072;
+    if (n_calls == 1 && calls[0].algo == IPTQ_ALGO_AUTO && calls[0].rows <= kTinyRows) {
+        int64_t served = 0;
+        const hipError_t e = softmax_wide_launch(calls[0], cols, post_mode_of(calls[0].P, calls[0].out_bits),
+                                                 &served, stream);
+        if (e != hipSuccess) return e;
+        if (served == calls[0].rows) return hipSuccess;      // every row or none
+    }
     int rpw = 0;                                      // rows per wavefront of the compiled row length
     hipError_t (*launch)(const SoftmaxBatch &, unsigned, bool, int, int, hipStream_t) = nullptr;
 #define IPTQ_PICK_ROWS_SHAPE(COLS, K)                                                             \
