@@ -597,3 +597,51 @@ def test_calls_can_be_captured_in_a_hip_graph():
         torch.cuda.synchronize()
         assert np.array_equal(d_p.cpu().numpy(), ref.softmax_i32(s_new, sp)), rep
         assert np.array_equal(d_y.cpu().numpy(), ref.gelu_i8(x_new, gp)), rep
+
+
+def test_concurrent_calls_from_several_host_threads_and_streams():
+    """The library keeps no state: host threads that call it at the same time, each on a stream
+    of its own, get the same results as one thread would."""
+    import threading
+    import torch
+    import paper_2511_15369_amd as ip
+    n_threads, rounds = 4, 25
+    rng = np.random.default_rng(31)
+    jobs = []
+    for t in range(n_threads):
+        cols = (197, 49, 64, 1025)[t]
+        rows = 300 if cols < 1000 else 40
+        x = np.rint(rng.standard_normal((rows, cols)) * 600).astype(np.int32)
+        sp = prepare.softmax_prepare(2.0 ** -(6.0 + t), cols, t % 2)
+        g = rng.integers(-128, 128, size=50000 + 13 * t, dtype=np.int8)
+        gp = prepare.gelu_prepare(2.0 ** -(4.0 + t), 2.0 ** -5.0, t, -t, t % 2)
+        jobs.append((x, sp, ref.softmax_i32(x, sp), g, gp, ref.gelu_i8(g, gp)))
+    errors = []
+
+    def worker(t):
+        try:
+            x, sp, want_s, g, gp, want_g = jobs[t]
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                d_x = torch.from_numpy(x).cuda()
+                d_g = torch.from_numpy(g).cuda()
+                lsp, lgp = lib_softmax(sp), lib_gelu(gp)
+                for _ in range(rounds):
+                    d_p = torch.zeros(x.shape, dtype=torch.uint8, device="cuda")
+                    d_y = torch.zeros_like(d_g)
+                    ip.softmax_i32(d_x, None, 0, d_p, x.shape[0], x.shape[1], lsp)
+                    ip.gelu_i8(d_g, d_y, d_g.numel(), lgp)
+                    stream.synchronize()
+                    if not (np.array_equal(d_p.cpu().numpy(), want_s) and np.array_equal(d_y.cpu().numpy(), want_g)):
+                        errors.append((t, "mismatch"))
+                        return
+        except Exception as exc:                      # surfaces in the main thread below
+            errors.append((t, repr(exc)))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(n_threads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=100)
+    assert not any(th.is_alive() for th in threads)
+    assert not errors, errors
