@@ -53,6 +53,9 @@ extern "C" {
 #define IPTQ_ALGO_WIDE 3    /* softmax only: one wavefront (rows up to 4096 scores) or one workgroup
                                (up to 40957) per row, row in registers, no LDS staging, also where
                                another kernel would serve */
+#define IPTQ_ALGO_SLAB 4    /* softmax only: the slab kernels (compiled row length if there is one,
+                               else run-time row length) also for a call of few rows, which
+                               IPTQ_ALGO_AUTO gives to one wavefront per row */
 
 /*
  * y = clamp(rshr_round(x * m, s) + zp, qmin, qmax)

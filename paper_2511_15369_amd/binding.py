@@ -20,6 +20,7 @@ ALGO_AUTO = 0
 ALGO_GENERIC = 1
 ALGO_DYNAMIC = 2
 ALGO_WIDE = 3
+ALGO_SLAB = 4
 
 
 class IptqError(RuntimeError):

@@ -71,7 +71,7 @@ int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int
     if (p->variant != IPTQ_SOFTMAX_SHIFT_LINEAR && p->variant != IPTQ_SOFTMAX_EFFICIENT_BITEXP)
         return IPTQ_ERR_PARAM;
     if (p->algo != IPTQ_ALGO_AUTO && p->algo != IPTQ_ALGO_GENERIC &&
-        p->algo != IPTQ_ALGO_DYNAMIC && p->algo != IPTQ_ALGO_WIDE)
+        p->algo != IPTQ_ALGO_DYNAMIC && p->algo != IPTQ_ALGO_WIDE && p->algo != IPTQ_ALGO_SLAB)
         return IPTQ_ERR_PARAM;
     if (p->i0 < 16 || p->i0 >= (1 << 24)) return IPTQ_ERR_PARAM;
     if (p->n_shift < 0 || p->n_shift > 20) return IPTQ_ERR_PARAM;

@@ -148,7 +148,8 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
                                                ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
                                        (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 31) &&
                                                c.P.bias_period_rows >= rpw);
-            if (rpw == 0 || c.algo != IPTQ_ALGO_AUTO || !aligned || !bias_ok) continue;
+            const bool slab_algo = c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_SLAB;
+            if (rpw == 0 || !slab_algo || !aligned || !bias_ok) continue;
             const int64_t n_slabs = (c.rows + rpw - 1) / rpw;    // a partial last slab is served too
             if (n_slabs == 0) continue;
             const int pm = post_mode_of(c.P, c.out_bits);
@@ -182,7 +183,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             const SoftmaxCall &c = calls[base + i];
             const bool has_pre = !(c.P.pre_m == 1 && c.P.pre_s == 0);
             // a call no compiled row length served goes to the run-time-row-length kernels
-            if (done[i] == 0 && (c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_DYNAMIC)) {
+            if (done[i] == 0 && (c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_DYNAMIC || c.algo == IPTQ_ALGO_SLAB)) {
                 err = softmax_rowsdyn_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
                 if (err != hipSuccess) break;
             }

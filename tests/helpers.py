@@ -35,11 +35,19 @@ def gpu_softmax(scores: np.ndarray, p: ref.SoftmaxParams, bias=None, period=0, a
     rows, cols = scores.shape
     d_in = torch.from_numpy(np.ascontiguousarray(scores)).cuda()
     d_bias = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias)).cuda()
-    d_out = torch.full((rows, cols), 0x5A, dtype=torch.int8 if p.out_is_signed else torch.uint8,
-                       device="cuda")
-    ip.softmax_i32(d_in, d_bias, period, d_out, rows, cols, lib_softmax(p, algo))
-    torch.cuda.synchronize()
-    return d_out.cpu().numpy()
+
+    def run(which):
+        d_out = torch.full((rows, cols), 0x5A, dtype=torch.int8 if p.out_is_signed else torch.uint8,
+                           device="cuda")
+        ip.softmax_i32(d_in, d_bias, period, d_out, rows, cols, lib_softmax(p, which))
+        torch.cuda.synchronize()
+        return d_out.cpu().numpy()
+
+    out = run(algo)
+    if algo == 0:
+        # a call of few rows goes to one wavefront per row; the slab kernels must agree on it too
+        assert np.array_equal(run(4), out), "IPTQ_ALGO_SLAB differs from IPTQ_ALGO_AUTO"
+    return out
 
 
 def gpu_gelu_i8(x: np.ndarray, p: ref.GeluParams, algo=0, inplace=False) -> np.ndarray:

@@ -130,13 +130,15 @@ def test_softmax_partial_last_slab(cols):
         for p, with_bias in cases:
             dt = torch.int8 if p.out_is_signed else torch.uint8
             d_out = torch.full((rows * cols + 64,), 0x5A, dtype=dt, device="cuda")
-            ip.softmax_i32(d_scores, d_bias if with_bias else None, 64 if with_bias else 0, d_out, rows,
-                           cols, lib_softmax(p))
-            torch.cuda.synchronize()
-            got = d_out.cpu().numpy()
             want = ref.softmax_i32(scores[:rows], p, bias if with_bias else None, 64 if with_bias else 0)
-            assert np.array_equal(got[:rows * cols].reshape(rows, cols), want), (rows, with_bias)
-            assert (got[rows * cols:] == 0x5A).all(), (rows, with_bias)
+            for algo in (4, 0):                           # the slab kernels, then the default choice
+                d_out.fill_(0x5A)
+                ip.softmax_i32(d_scores, d_bias if with_bias else None, 64 if with_bias else 0, d_out, rows,
+                               cols, lib_softmax(p, algo))
+                torch.cuda.synchronize()
+                got = d_out.cpu().numpy()
+                assert np.array_equal(got[:rows * cols].reshape(rows, cols), want), (rows, with_bias, algo)
+                assert (got[rows * cols:] == 0x5A).all(), (rows, with_bias, algo)
 
 
 @pytest.mark.parametrize("cols", [49, 197, 64, 600, 1025, 4097])
@@ -206,7 +208,7 @@ def test_softmax_views_off_the_16_byte_grid(cols):
         d_in[in_off:in_off + n] = torch.from_numpy(scores.reshape(-1)).cuda()
         d_out = torch.full((n + 32,), 0x5A, dtype=torch.uint8, device="cuda")
         want = ref.softmax_i32(scores, p, bias if with_bias else None, 4 if with_bias else 0)
-        for algo in (0, 3):
+        for algo in (0, 3, 4):
             d_out.fill_(0x5A)
             lp = lib_softmax(p)
             lp.algo = algo

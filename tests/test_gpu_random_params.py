@@ -64,7 +64,7 @@ def test_softmax_random_domain(seed):
             bias = np.rint(rng.standard_normal((period, cols)) * 2.0 * i0).astype(np.int32)
             bias[rng.random((period, cols)) < 0.02] = I32_MIN
         want = ref.softmax_i32(x, p, bias, period)
-        for algo in (0, 1, 2, 3):
+        for algo in (0, 1, 2, 3, 4):
             got = gpu_softmax(x, p, bias, period, algo=algo)
             assert np.array_equal(got, want), (algo, cols, rows, p)
 
@@ -112,7 +112,7 @@ def test_softmax_random_row_lengths_and_views(seed):
         d_in = torch.zeros(n + 16, dtype=torch.int32, device="cuda")
         d_in[off:off + n] = torch.from_numpy(x.reshape(-1)).cuda()
         d_bias = torch.from_numpy(bias).cuda() if bias is not None else None
-        for algo in (0, 2, 3):
+        for algo in (0, 2, 3, 4):
             d_out = torch.full((n + 32,), 0x5A, dtype=torch.uint8, device="cuda").view(torch.int8 if signed else torch.uint8)
             ip.softmax_i32(d_in[off:off + n], d_bias, period, d_out[off:off + n], rows, cols, lib_softmax(p, algo))
             torch.cuda.synchronize()
