@@ -368,7 +368,9 @@ def main():
         "algorithmic_gbps": main_res["algorithmic_gbps"],
         "pct_of_hbm_peak": 100.0 * main_res["algorithmic_gbps"] / HBM_PEAK_GBS,
         "roofline": {
-            "bound": "hbm", "kernel": "softmax_rows_kernel",
+            "bound": "hbm",
+            # single calls of at most 3072 rows (DeiT-T at batch 1) run one wavefront per row
+            "kernel": "softmax_rows_kernel" if sm["elements"] // sm["launches"] > 3072 * 197 else "softmax_wide_kernel",
             "achieved": sm["gbps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": sm["gbps"] / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC.get(args.workload),
