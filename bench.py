@@ -292,6 +292,7 @@ def main():
             "ms_per_step": ms, "wall_ms_per_step": wall_ms,
             "elements_per_step": sm_el + ge_el,
             "softmax": {"elements": sm_el, "launches": len(units), "avg_launch_us": sm_ms * 1e3,
+                        "rows_per_launch": [u.rows for u in units],
                         "gbps": SOFTMAX_BYTES_PER_EL * sm_el / len(units) / (sm_ms * 1e-3) / 1e9},
             "gelu": {"elements": ge_el, "launches": len(units), "avg_launch_us": ge_ms * 1e3,
                      "gbps": GELU_BYTES_PER_EL * ge_el / len(units) / (ge_ms * 1e-3) / 1e9},
@@ -370,7 +371,7 @@ def main():
         "roofline": {
             "bound": "hbm",
             # single calls of at most 3072 rows (DeiT-T at batch 1) run one wavefront per row
-            "kernel": "softmax_rows_kernel" if sm["elements"] // sm["launches"] > 3072 * 197 else "softmax_wide_kernel",
+            "kernel": "softmax_rows_kernel" if min(sm["rows_per_launch"]) > 3072 else "softmax_wide_kernel",
             "achieved": sm["gbps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": sm["gbps"] / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC.get(args.workload),
