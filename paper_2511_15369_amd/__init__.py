@@ -5,6 +5,11 @@ gfx950).  PyTorch is used only for device memory and streams.
 """
 
 from .binding import (  # noqa: F401
+    ALGO_AUTO,
+    ALGO_DYNAMIC,
+    ALGO_GENERIC,
+    ALGO_SLAB,
+    ALGO_WIDE,
     BATCH_MAX,
     Dyadic,
     GeluProblem,
