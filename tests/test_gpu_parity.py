@@ -97,7 +97,7 @@ def test_softmax_mask_and_extreme_rows(cols):
 @pytest.mark.parametrize("cols", [1, 2, 3, 4, 5, 6, 7, 16, 50, 63, 64, 65, 128, 144, 145, 196, 198, 199,
                                   257, 401, 415, 416, 417, 577, 785, 800, 1017, 1018, 1019, 1025, 1270,
                                   1274, 1275, 1280, 2045, 2046, 2048, 3325, 3326, 4096, 4097, 4099, 5117,
-                                  5118, 8192, 13309, 13310, 20477, 20478, 32765, 32766, 40957, 40958])
+                                  5118, 8192, 13309, 13310, 20477, 20478, 26618, 26619, 32765, 32766, 40957, 40958, 65536])
 def test_softmax_any_row_length(cols):
     rng = np.random.default_rng(cols)
     rows = 137 if cols < 300 else (37 if cols < 6000 else 9)
