@@ -139,7 +139,9 @@ const char *iptq_strerror(int code);
 /*
  * Requantization of an int32 tensor (the formula of iptq_dyadic_t).
  * d_in: n int32 (device, 4-byte aligned); d_out: n uint8_t (out_is_signed == 0) or int8_t
- * (== 1) (device); n >= 0 (0 is a successful no-op); p: host.
+ * (== 1) (device); n >= 0 (0 is a successful no-op); p: host.  No further alignment is asked
+ * of either pointer here or in the GELU entry points (fastest on the 16-byte grid, within 10 % of
+ * that anywhere else).
  */
 int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t out_is_signed,
                  const iptq_dyadic_t *p, void *stream);

@@ -70,8 +70,11 @@ IPTQ_DEV int32_t sbyte(uint32_t w, int i) { return (int32_t)(int8_t)(w >> (8 * i
 // the 256 input codes with the exact integer formula, then every element is one byte
 // gather from LDS.  One launch serves up to kGeluBatchMax independent problems (the layers
 // of a sweep): workgroups [first_wg, first_wg + n_wgs) stream item i.  The last (n & 15)
-// bytes of an item are done by its first workgroup.  in and out must be 16-byte aligned;
-// they may be the same buffer.
+// bytes of an item are done by its first workgroup.  `out` is 16-byte aligned: the host
+// peels the `head` bytes in front of that boundary off the tensor (the item's first
+// workgroup does them too).  `in` is then aligned as well if the two tensors sit at the same
+// offset (in place, or views cut at the same element); if not, its 16-byte loads are
+// unaligned ones.  in and out may be the same buffer.
 constexpr int kGeluBatchMax = 16;
 #ifndef IPTQ_GELU_TABLE_GRID_CAP
 #define IPTQ_GELU_TABLE_GRID_CAP (256 * 56)
@@ -82,6 +85,7 @@ struct GeluItem {
     int64_t n;
     uint32_t first_wg;
     uint32_t n_wgs;
+    uint32_t head;          // bytes in front of in / out that belong to the tensor: 0..15
     GeluDev P;
 };
 struct GeluBatch {
@@ -100,7 +104,6 @@ gelu_i8_table_kernel(GeluBatch B)
     __shared__ uint8_t table[256];
     const int64_t n = I.n;
     const int64_t n16 = n >> 4;
-    const u32x4 *in4 = reinterpret_cast<const u32x4 *>(I.in);
     u32x4 *out4 = reinterpret_cast<u32x4 *>(I.out);
     const uint32_t lb = blockIdx.x - I.first_wg;
     const int64_t stride = (int64_t)I.n_wgs * 256;
@@ -117,18 +120,26 @@ gelu_i8_table_kernel(GeluBatch B)
         }
         return r;
     };
+    // the same global_load_dwordx4 serves an input on the 16-byte grid and one off it
+    typedef u32x4 __attribute__((aligned(1))) u32x4_unaligned;
+    const u32x4_unaligned *in4u = reinterpret_cast<const u32x4_unaligned *>(I.in);
+    auto load16 = [&](int64_t k) -> u32x4 { return __builtin_nontemporal_load(in4u + k); };
     int64_t i = (int64_t)lb * 256 + threadIdx.x;
     // the first chunk's load is in flight while the table is built
     u32x4 first = {0u, 0u, 0u, 0u};
-    if (i < n16) first = stream_load(in4 + i);
+    if (i < n16) first = load16(i);
     table[threadIdx.x] = (uint8_t)gelu_eval_any((int32_t)(int8_t)threadIdx.x, I.P);
     __syncthreads();
     if (i < n16) stream_store(gather(first), out4 + i);
     i += stride;
-    for (; i < n16; i += stride) stream_store(gather(stream_load(in4 + i)), out4 + i);
+    for (; i < n16; i += stride) stream_store(gather(load16(i)), out4 + i);
     if (lb == 0) {
         const int64_t j = (n16 << 4) + threadIdx.x;
         if (threadIdx.x < 16 && j < n) I.out[j] = table[I.in[j]];
+        if (threadIdx.x >= 32 && threadIdx.x < 32 + I.head) {     // the peeled bytes in front
+            const int64_t h = (int64_t)(threadIdx.x - 32) - (int64_t)I.head;
+            I.out[h] = table[I.in[h]];
+        }
     }
 }
 
@@ -175,23 +186,31 @@ gelu_i8_bytes_kernel(const uint8_t *in, uint8_t *out, int64_t n, GeluDev P)
 // of a pass owns the 4 consecutive elements of 16-byte chunk i (a wavefront reads 1 KiB
 // contiguous per load and writes 256 B contiguous per store).  One chunk in flight per thread
 // and many resident wavefronts measured fastest on MI355X (deeper per-thread unrolling lost
-// 10 %).  ALIGNED needs a 16-byte aligned input and a 4-byte aligned output.
+// 10 %).  ALIGNED: `out` is 4-byte aligned (the host peels the `head` elements in front of
+// that boundary off the tensor; the first workgroup does them too) and `in` is an int32
+// pointer anywhere on the 4-byte grid: the same global_load_dwordx4 serves an input on the
+// 16-byte grid and one off it.
+typedef i32x4 __attribute__((aligned(4))) i32x4_a4;
 template <bool ALIGNED, typename F>
-IPTQ_DEV void stream_i32_to_bytes(const int32_t *in, uint8_t *out, int64_t n, F one)
+IPTQ_DEV void stream_i32_to_bytes(const int32_t *in, uint8_t *out, int64_t n, int32_t head, F one)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
     const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (ALIGNED) {
         const int64_t n4 = n >> 2;
-        const i32x4 *in4 = reinterpret_cast<const i32x4 *>(in);
+        const i32x4_a4 *in4 = reinterpret_cast<const i32x4_a4 *>(in);
         uint32_t *out32 = reinterpret_cast<uint32_t *>(out);
         for (int64_t i = tid; i < n4; i += stride) {
-            const i32x4 v = stream_load(in4 + i);
+            const i32x4 v = __builtin_nontemporal_load(in4 + i);
             stream_store(pack4(one(v.x), one(v.y), one(v.z), one(v.w)), out32 + i);
         }
         if (blockIdx.x == 0) {
             const int64_t i = (n4 << 2) + threadIdx.x;
             if (threadIdx.x < 4 && i < n) out[i] = (uint8_t)one(in[i]);
+            if (threadIdx.x >= 32 && (int32_t)threadIdx.x < 32 + head) {   // the peeled elements in front
+                const int64_t h = (int64_t)threadIdx.x - 32 - head;
+                out[h] = (uint8_t)one(in[h]);
+            }
         }
     } else {
         for (int64_t i = tid; i < n; i += stride) out[i] = (uint8_t)one(in[i]);
@@ -203,7 +222,7 @@ IPTQ_DEV void stream_i32_to_bytes(const int32_t *in, uint8_t *out, int64_t n, F 
 // (pre_s >= 15) pre-requantization.
 template <bool ALIGNED, int MODE>
 __global__ void __launch_bounds__(256)
-gelu_i32_kernel(const int32_t *in, uint8_t *out, int64_t n, GeluDev P)
+gelu_i32_kernel(const int32_t *in, uint8_t *out, int64_t n, int32_t head, GeluDev P)
 {
     GeluDev Q = P;
     Q.zp_in = 0;
@@ -223,7 +242,7 @@ gelu_i32_kernel(const int32_t *in, uint8_t *out, int64_t n, GeluDev P)
         const int32_t q = clamp_i32(__builtin_elementwise_sub_sat(x, P.zp_in), -P.max_abs_q, P.max_abs_q);
         return gelu_eval_fast<MODE == 2>(q, P);
     };
-    stream_i32_to_bytes<ALIGNED>(in, out, n, one);
+    stream_i32_to_bytes<ALIGNED>(in, out, n, head, one);
 }
 
 // int32 accumulators -> int8 GELU through a table.  After the requantization in front the
@@ -236,7 +255,7 @@ constexpr int kGelu32TableMaxQ = 511;
 #endif
 template <bool ALIGNED>
 __global__ void __launch_bounds__(256)
-gelu_i32_table_kernel(const int32_t *in, uint8_t *out, int64_t n, GeluDev P)
+gelu_i32_table_kernel(const int32_t *in, uint8_t *out, int64_t n, int32_t head, GeluDev P)
 {
     __shared__ uint8_t table[2 * kGelu32TableMaxQ + 2];
     GeluDev Q = P;
@@ -255,41 +274,45 @@ gelu_i32_table_kernel(const int32_t *in, uint8_t *out, int64_t n, GeluDev P)
         // the first chunk's load is in flight while the table is built
         const int64_t stride = (int64_t)gridDim.x * 256;
         const int64_t n4 = n >> 2;
-        const i32x4 *in4 = reinterpret_cast<const i32x4 *>(in);
+        const i32x4_a4 *in4 = reinterpret_cast<const i32x4_a4 *>(in);
         uint32_t *out32 = reinterpret_cast<uint32_t *>(out);
         int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
         i32x4 v = {0, 0, 0, 0};
-        if (i < n4) v = stream_load(in4 + i);
+        if (i < n4) v = __builtin_nontemporal_load(in4 + i);
         for (int32_t e = threadIdx.x; e <= 2 * lim; e += 256)
             table[e] = (uint8_t)gelu_eval_any(e - lim, Q);
         __syncthreads();
         if (i < n4) stream_store(pack4(one(v.x), one(v.y), one(v.z), one(v.w)), out32 + i);
         for (i += stride; i < n4; i += stride) {
-            v = stream_load(in4 + i);
+            v = __builtin_nontemporal_load(in4 + i);
             stream_store(pack4(one(v.x), one(v.y), one(v.z), one(v.w)), out32 + i);
         }
         if (blockIdx.x == 0) {
             const int64_t j = (n4 << 2) + threadIdx.x;
             if (threadIdx.x < 4 && j < n) out[j] = (uint8_t)one(in[j]);
+            if (threadIdx.x >= 32 && (int32_t)threadIdx.x < 32 + head) {   // the peeled elements in front
+                const int64_t h = (int64_t)threadIdx.x - 32 - head;
+                out[h] = (uint8_t)one(in[h]);
+            }
         }
         return;
     }
     for (int32_t e = threadIdx.x; e <= 2 * lim; e += 256)
         table[e] = (uint8_t)gelu_eval_any(e - lim, Q);
     __syncthreads();
-    stream_i32_to_bytes<ALIGNED>(in, out, n, one);
+    stream_i32_to_bytes<ALIGNED>(in, out, n, head, one);
 }
 
 // int32 -> int8 / uint8 requantization.
 template <bool ALIGNED>
 __global__ void __launch_bounds__(256)
-requant_kernel(const int32_t *in, uint8_t *out, int64_t n, DyadicDev P)
+requant_kernel(const int32_t *in, uint8_t *out, int64_t n, int32_t head, DyadicDev P)
 {
     auto one = [&](int32_t x) -> int32_t {
         return P.s >= 16 ? requant_dev<true>(x, P.m, P.s, P.zp, P.qmin, P.qmax)
                          : requant_dev<false>(x, P.m, P.s, P.zp, P.qmin, P.qmax);
     };
-    stream_i32_to_bytes<ALIGNED>(in, out, n, one);
+    stream_i32_to_bytes<ALIGNED>(in, out, n, head, one);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -321,7 +344,9 @@ hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stre
         const uint8_t *uin = reinterpret_cast<const uint8_t *>(g.in);
         uint8_t *uout = reinterpret_cast<uint8_t *>(g.out);
         const bool aligned = ((reinterpret_cast<uintptr_t>(g.in) | reinterpret_cast<uintptr_t>(g.out)) & 15) == 0;
-        if (!aligned) {
+        // bytes in front of the output's first 16-byte boundary
+        const uint32_t head = (uint32_t)((0 - reinterpret_cast<uintptr_t>(g.out)) & 15);
+        if (!aligned && (g.force_direct || g.n < 64)) {
             hipLaunchKernelGGL(gelu_i8_bytes_kernel, dim3(grid_for(g.n, 256)), dim3(256), 0, stream,
                                uin, uout, g.n, g.P);
         } else if (g.force_direct) {
@@ -335,9 +360,10 @@ hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stre
         } else {
             if (B.n_items == kGeluBatchMax) flush();
             GeluItem &it = B.item[B.n_items++];
-            it.in = uin; it.out = uout; it.n = g.n; it.P = g.P;
+            it.in = uin + head; it.out = uout + head; it.n = g.n - head; it.P = g.P;
+            it.head = head;
             it.first_wg = total_wgs;
-            it.n_wgs = grid_for(g.n >> 4, 256, IPTQ_GELU_TABLE_GRID_CAP);
+            it.n_wgs = grid_for(it.n >> 4, 256, IPTQ_GELU_TABLE_GRID_CAP);
             total_wgs += it.n_wgs;
         }
     }
@@ -345,27 +371,39 @@ hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stre
     return hipGetLastError();
 }
 
+// The vector path of the int32-input kernels wants a 4-byte aligned output: the elements in
+// front of that boundary are peeled off (the kernel's first workgroup does them), the input
+// follows wherever that leaves it on its 4-byte grid.  Calls too short for that stream bytes.
+static bool peel_to_dword_out(const int32_t *&in, uint8_t *&out, int64_t &n, int32_t *head)
+{
+    *head = (int32_t)((0 - reinterpret_cast<uintptr_t>(out)) & 3);
+    if ((reinterpret_cast<uintptr_t>(in) & 3) != 0 || n < 64) return false;
+    in += *head; out += *head; n -= *head;
+    return true;
+}
+
 hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,
                              bool force_direct, hipStream_t stream)
 {
     uint8_t *uout = reinterpret_cast<uint8_t *>(out);
-    const bool aligned = (reinterpret_cast<uintptr_t>(in) & 15) == 0 && (reinterpret_cast<uintptr_t>(out) & 3) == 0;
+    int32_t head = 0;
+    const bool aligned = peel_to_dword_out(in, uout, n, &head);
     const int mode = (P.fast && P.pre_mode != 2) ? (P.quartic ? 2 : 1) : 0;
     const bool table = !force_direct && P.max_abs_q <= kGelu32TableMaxQ;
     if (aligned) {
         const dim3 grid(grid_for(n >> 2, 256, 256 * 64)), block(256);
         if (table)
             hipLaunchKernelGGL(gelu_i32_table_kernel<true>, dim3(grid_for(n >> 2, 256, IPTQ_GELU32_TABLE_GRID_CAP)),
-                               block, 0, stream, in, uout, n, P);
-        else if (mode == 0) hipLaunchKernelGGL((gelu_i32_kernel<true, 0>), grid, block, 0, stream, in, uout, n, P);
-        else if (mode == 1) hipLaunchKernelGGL((gelu_i32_kernel<true, 1>), grid, block, 0, stream, in, uout, n, P);
-        else hipLaunchKernelGGL((gelu_i32_kernel<true, 2>), grid, block, 0, stream, in, uout, n, P);
+                               block, 0, stream, in, uout, n, head, P);
+        else if (mode == 0) hipLaunchKernelGGL((gelu_i32_kernel<true, 0>), grid, block, 0, stream, in, uout, n, head, P);
+        else if (mode == 1) hipLaunchKernelGGL((gelu_i32_kernel<true, 1>), grid, block, 0, stream, in, uout, n, head, P);
+        else hipLaunchKernelGGL((gelu_i32_kernel<true, 2>), grid, block, 0, stream, in, uout, n, head, P);
     } else {
         const dim3 grid(grid_for(n, 256)), block(256);
-        if (table) hipLaunchKernelGGL(gelu_i32_table_kernel<false>, grid, block, 0, stream, in, uout, n, P);
-        else if (mode == 0) hipLaunchKernelGGL((gelu_i32_kernel<false, 0>), grid, block, 0, stream, in, uout, n, P);
-        else if (mode == 1) hipLaunchKernelGGL((gelu_i32_kernel<false, 1>), grid, block, 0, stream, in, uout, n, P);
-        else hipLaunchKernelGGL((gelu_i32_kernel<false, 2>), grid, block, 0, stream, in, uout, n, P);
+        if (table) hipLaunchKernelGGL(gelu_i32_table_kernel<false>, grid, block, 0, stream, in, uout, n, 0, P);
+        else if (mode == 0) hipLaunchKernelGGL((gelu_i32_kernel<false, 0>), grid, block, 0, stream, in, uout, n, 0, P);
+        else if (mode == 1) hipLaunchKernelGGL((gelu_i32_kernel<false, 1>), grid, block, 0, stream, in, uout, n, 0, P);
+        else hipLaunchKernelGGL((gelu_i32_kernel<false, 2>), grid, block, 0, stream, in, uout, n, 0, P);
     }
     return hipGetLastError();
 }
@@ -374,13 +412,13 @@ hipError_t requant_dispatch(const int32_t *in, void *out, int64_t n, const Dyadi
                             hipStream_t stream)
 {
     uint8_t *uout = reinterpret_cast<uint8_t *>(out);
-    const bool aligned = (reinterpret_cast<uintptr_t>(in) & 15) == 0 && (reinterpret_cast<uintptr_t>(out) & 3) == 0;
-    if (aligned)
+    int32_t head = 0;
+    if (peel_to_dword_out(in, uout, n, &head))
         hipLaunchKernelGGL(requant_kernel<true>, dim3(grid_for(n >> 2, 256, 256 * 64)), dim3(256), 0, stream, in,
-                           uout, n, P);
+                           uout, n, head, P);
     else
         hipLaunchKernelGGL(requant_kernel<false>, dim3(grid_for(n, 256)), dim3(256), 0, stream, in, uout,
-                           n, P);
+                           n, 0, P);
     return hipGetLastError();
 }
 

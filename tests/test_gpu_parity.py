@@ -9,7 +9,7 @@ import pytest
 
 import workloads
 from oracle import prepare, ref
-from tests.helpers import (gpu_gelu_i8, gpu_gelu_i32, gpu_requant, gpu_softmax, lib_gelu,
+from tests.helpers import (gpu_gelu_i8, gpu_gelu_i32, gpu_requant, gpu_softmax, lib_dyadic, lib_gelu,
                            lib_softmax)
 
 pytestmark = pytest.mark.gpu
@@ -647,3 +647,54 @@ def test_concurrent_calls_from_several_host_threads_and_streams():
         th.join(timeout=100)
     assert not any(th.is_alive() for th in threads)
     assert not errors, errors
+
+
+def test_elementwise_views_at_every_offset():
+    """Requantization, GELU on int32 accumulators and GELU on int8 codes on views that start at
+    every offset of the input's and the output's 16-byte grids (the kernels peel the output's
+    head up to its vector boundary and load the input wherever that leaves it): exact results,
+    no byte outside the view written, sizes around the peel / vector / tail boundaries."""
+    import torch
+    import paper_2511_15369_amd as ip
+    rng = np.random.default_rng(909)
+    dy = ref.Dyadic(-23170, 21, 5, -128, 127)
+    gp32 = prepare.gelu_prepare(2.0 ** -4.7, 2.0 ** -5.2, 2, -3, 1, max_abs_q=127)
+    gp32.pre_m, gp32.pre_s = 20000, 26
+    gp8 = prepare.gelu_prepare(2.0 ** -4.7, 2.0 ** -5.2, 2, -3, 1)
+    for n in (63, 64, 65, 67, 100, 4099, 70001):
+        x32 = rng.integers(-(2 ** 31), 2 ** 31, size=n).astype(np.int32)
+        x8 = rng.integers(-128, 128, size=n, dtype=np.int8)
+        want_rq = ref.requant(x32, dy, 1)
+        want_g32 = ref.gelu_i32(x32, gp32)
+        want_g8 = ref.gelu_i8(x8, gp8)
+        for in_off in (0, 1, 2, 3, 5):
+            d_x32 = torch.zeros(n + 8, dtype=torch.int32, device="cuda")
+            d_x32[in_off:in_off + n] = torch.from_numpy(x32).cuda()
+            for out_off in (0, 1, 2, 3, 4, 7, 15):
+                for what, want in (("requant", want_rq), ("gelu_i32", want_g32), ("gelu_i32 direct", want_g32)):
+                    d_y = torch.full((n + 32,), 0x5A, dtype=torch.int8, device="cuda")
+                    if what == "requant":
+                        ip.requant(d_x32[in_off:in_off + n], d_y[out_off:out_off + n], n, 1, lib_dyadic(dy))
+                    else:
+                        ip.gelu_i32(d_x32[in_off:in_off + n], d_y[out_off:out_off + n], n,
+                                    lib_gelu(gp32, algo=int(what.endswith("direct"))))
+                    torch.cuda.synchronize()
+                    got = d_y.cpu().numpy()
+                    assert np.array_equal(got[out_off:out_off + n], want), (what, n, in_off, out_off)
+                    assert (got[:out_off] == 0x5A).all() and (got[out_off + n:] == 0x5A).all(), (what, n, in_off, out_off)
+        for in_off in (0, 1, 3, 4, 9, 15, 16, 17):
+            d_x8 = torch.zeros(n + 32, dtype=torch.int8, device="cuda")
+            d_x8[in_off:in_off + n] = torch.from_numpy(x8).cuda()
+            for out_off in (0, 1, 3, 4, 9, 15, 16, 17):
+                d_y = torch.full((n + 48,), 0x5A, dtype=torch.int8, device="cuda")
+                ip.gelu_i8(d_x8[in_off:in_off + n], d_y[out_off:out_off + n], n, lib_gelu(gp8))
+                torch.cuda.synchronize()
+                got = d_y.cpu().numpy()
+                assert np.array_equal(got[out_off:out_off + n], want_g8), ("gelu_i8", n, in_off, out_off)
+                assert (got[:out_off] == 0x5A).all() and (got[out_off + n:] == 0x5A).all(), ("gelu_i8", n, in_off, out_off)
+        # in place on an unaligned view
+        d_io = torch.zeros(n + 32, dtype=torch.int8, device="cuda")
+        d_io[5:5 + n] = torch.from_numpy(x8).cuda()
+        ip.gelu_i8(d_io[5:5 + n], d_io[5:5 + n], n, lib_gelu(gp8))
+        torch.cuda.synchronize()
+        assert np.array_equal(d_io.cpu().numpy()[5:5 + n], want_g8), ("in place", n)
