@@ -158,13 +158,11 @@ int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t out_is_sig
  * The post step runs at full speed when it is the identity, the int8 clip at 127, or the shift to
  * signed codes p - 128 (post = {1, 0, -128, -128, qmax >= 0}: the operand form of a signed 8-bit
  * matrix instruction for the product with V); any other post step goes through a small table.
- * Every shape gives the same bytes; speed depends on it.  Fastest: 16-byte aligned d_scores and
- * d_out (and d_bias, with bias_period_rows * cols a multiple of 4) and a row length of 197, 49,
- * 198, 144, 257 or 577; any other row length up to 40957 runs in the register-resident kernels
- * with a run-time row length.  Views cut at the same element of larger 16-byte aligned tensors
- * (d_scores off the 16-byte grid by k elements, d_out by k bytes, no d_bias) run one wavefront
- * or workgroup per row: full speed for rows of a thousand scores and more, a third of it at
- * 197.  Longer rows and other alignments take a slower multi-pass kernel.
+ * Every shape gives the same bytes; speed depends on it.  Fastest: a row length of 197, 49, 198,
+ * 144, 257 or 577; any other row length up to 40957 runs in the register-resident kernels with
+ * a run-time row length, longer rows in a slower multi-pass kernel.  The tensors need their
+ * natural alignment only (views into larger tensors run at the same speed as tensors on the
+ * 16-byte grid); an additive table is fused when bias_period_rows * cols is a multiple of 4.
  */
 int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias, int64_t bias_period_rows,
                      void *d_out, int64_t rows, int32_t cols, const iptq_softmax_params_t *p,

@@ -40,6 +40,42 @@ __device__ __forceinline__ void stream_store(T v, T *p)
 #endif
 }
 
+// 16-byte and 4-byte accesses at addresses that are only as aligned as their elements: a
+// tensor that is a view into a larger one can start anywhere on its element grid, and
+// global_load_dwordx4 / global_store_dwordx4 take any address on this part.  The pointer
+// types say so; the instructions are the ones an aligned access compiles to.
+typedef i32x4 __attribute__((aligned(4))) i32x4_a4;
+typedef u32x4 __attribute__((aligned(1))) u32x4_a1;
+typedef uint32_t __attribute__((aligned(1))) u32_a1;
+__device__ __forceinline__ i32x4 stream_load_i32x4(const int32_t *p)
+{
+#if IPTQ_NONTEMPORAL
+    return __builtin_nontemporal_load(reinterpret_cast<const i32x4_a4 *>(p));
+#else
+    return *reinterpret_cast<const i32x4_a4 *>(p);
+#endif
+}
+__device__ __forceinline__ i32x4 load_i32x4(const int32_t *p)
+{
+    return *reinterpret_cast<const i32x4_a4 *>(p);
+}
+__device__ __forceinline__ void stream_store_bytes16(u32x4 v, uint8_t *p)
+{
+#if IPTQ_NONTEMPORAL
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_a1 *>(p));
+#else
+    *reinterpret_cast<u32x4_a1 *>(p) = v;
+#endif
+}
+__device__ __forceinline__ void stream_store_bytes4(uint32_t v, uint8_t *p)
+{
+#if IPTQ_NONTEMPORAL
+    __builtin_nontemporal_store(v, reinterpret_cast<u32_a1 *>(p));
+#else
+    *reinterpret_cast<u32_a1 *>(p) = v;
+#endif
+}
+
 IPTQ_HD uint32_t mulhi_u32(uint32_t a, uint32_t b)
 {
 #if defined(__HIP_DEVICE_COMPILE__)

@@ -141,11 +141,13 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             const SoftmaxCall &c = calls[base + i];
             done[i] = 0;
             const bool has_bias = c.bias != nullptr;
+            // the slab kernels load and store 16 bytes at any element address: views that start
+            // off the 16-byte grid need nothing but their natural alignment
             const bool aligned =
-                ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.out)) & 15) == 0;
-            // the fused bias needs 16-byte aligned bias blocks and at most one wrap per slab
-            const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
-                                               ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
+                ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.bias)) & 3) == 0;
+            // the fused bias is read in blocks of four scores that must not straddle the table's
+            // end, with at most one wrap per slab
+            const bool bias_ok = !has_bias || (((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
                                        (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 31) &&
                                                c.P.bias_period_rows >= rpw);
             const bool slab_algo = c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_SLAB;

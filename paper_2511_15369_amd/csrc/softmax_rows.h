@@ -1,10 +1,11 @@
 // Fixed-row-length integer softmax kernel for gfx950 (Section 4.4, Eq. 6-15).
 //
 // A wavefront owns 64/K whole rows (a "slab"), K lanes per row.  The slab is contiguous
-// and 16-byte aligned in both the int32 input and the byte output, so all global traffic
-// is full dwordx4: the slab is copied flat into LDS (with the additive bias fused into the
-// copy), lanes then read their rows from LDS on the 16-byte grid of the flat tensor
-// ("blocks" of 4 elements; a row that does not start on that grid ignores the
+// and a whole number of 16-byte chunks in both the int32 input and the byte output, so all
+// global traffic is full dwordx4 (at the tensor's own alignment: a view into a larger tensor
+// need not sit on the 16-byte grid): the slab is copied flat into LDS (with the additive
+// bias fused into the copy), lanes then read their rows from LDS on the 16-byte grid of the
+// slab ("blocks" of 4 elements; a row that does not start on that grid ignores the
 // neighbours' elements in its first and last block), results are assembled as bytes in
 // LDS and stored flat.  Only wavefront-level ordering is needed: no workgroup barrier.
 //
@@ -299,7 +300,7 @@ softmax_rows_kernel(SoftmaxBatch B)
         const int p_max = 1 << (P.m_bits - P.p_shift);    // 2^(b-1) <= 128
         for (int p = lane; p <= p_max; p += 64) lut[p] = (uint8_t)post_dev<PM_GENERAL>((uint32_t)p, P);
     }
-    const i32x4 *src = reinterpret_cast<const i32x4 *>(scores + slab * SLAB);
+    const int32_t *src = scores + slab * SLAB;       // anywhere on the 4-byte grid
     const int lr = lane / K;                          // row inside the slab
     const int j = lane % K;                           // lane inside the row
     const int e_r = lr * COLS;                        // first element of the row in the slab
@@ -329,9 +330,9 @@ softmax_rows_kernel(SoftmaxBatch B)
             const int li = (PARTIAL || full_pass) ? idx : min(idx, IN_CHUNKS - 1);
             i32x4 v;
             if (!PARTIAL || 4 * idx + 3 < valid_el) {
-                v = stream_load(src + li);
+                v = stream_load_i32x4(src + 4 * li);
             } else {
-                const int32_t *s = scores + slab * SLAB + 4 * idx;
+                const int32_t *s = src + 4 * idx;
                 v = (i32x4){0, 0, 0, 0};
                 if (4 * idx < valid_el) v.x = s[0];
                 if (4 * idx + 1 < valid_el) v.y = s[1];
@@ -340,7 +341,7 @@ softmax_rows_kernel(SoftmaxBatch B)
             if (BIAS) {
                 uint32_t o = boff + 4u * (uint32_t)li;
                 if (o >= pe) o -= pe;
-                const i32x4 bv = *reinterpret_cast<const i32x4 *>(bias + o);
+                const i32x4 bv = load_i32x4(bias + o);
                 v.x = v.x == kI32Min ? v.x : sat_add_i32(v.x, bv.x);
                 v.y = v.y == kI32Min ? v.y : sat_add_i32(v.y, bv.y);
                 v.z = v.z == kI32Min ? v.z : sat_add_i32(v.z, bv.z);
@@ -455,9 +456,9 @@ softmax_rows_kernel(SoftmaxBatch B)
             if ((i + 1) * 64 <= OUT_CHUNKS || idx < OUT_CHUNKS) {
                 if (!PARTIAL || CB * idx + CB - 1 < valid_el) {
                     if (OUT16)
-                        stream_store(reinterpret_cast<const u32x4 *>(lds)[idx], reinterpret_cast<u32x4 *>(dst8) + idx);
+                        stream_store_bytes16(reinterpret_cast<const u32x4 *>(lds)[idx], dst8 + 16 * idx);
                     else
-                        stream_store(lds32[idx], reinterpret_cast<uint32_t *>(dst8) + idx);
+                        stream_store_bytes4(lds32[idx], dst8 + 4 * idx);
                 } else {
 #pragma unroll 1
                     for (int b = CB * idx; b < valid_el && b < CB * idx + CB; ++b) dst8[b] = lds[b];

@@ -69,7 +69,6 @@ softmax_rowsdyn_kernel(DynArgs A)
         for (int p = lane; p <= p_max; p += 64) lut[p] = (uint8_t)post_dev<PM_GENERAL>((uint32_t)p, P);
     }
     const int32_t *src1 = A.scores + slab * slab_el;
-    const i32x4 *src = reinterpret_cast<const i32x4 *>(src1);
     const int32_t *__restrict__ bias = A.bias;
     const bool partial = A.tail_rows != 0 && slab == A.n_slabs - 1;
     const int valid_el = (partial ? A.tail_rows : RPW) * cols;
@@ -101,11 +100,11 @@ softmax_rowsdyn_kernel(DynArgs A)
         auto bias_chunk = [&](int i) {
             uint32_t o = boff + 4u * (uint32_t)chunk_of(i);
             if (o >= pe) o -= pe;
-            return *reinterpret_cast<const i32x4 *>(bias + o);
+            return load_i32x4(bias + o);
         };
         i32x4 v[SLOTS], bv[BIAS ? kAhead : 1];
 #pragma unroll
-        for (int i = 0; i < SLOTS; ++i) v[i] = stream_load(src + chunk_of(i));
+        for (int i = 0; i < SLOTS; ++i) v[i] = stream_load_i32x4(src1 + 4 * chunk_of(i));
         if (BIAS) {
 #pragma unroll
             for (int i = 0; i < kAhead && i < SLOTS; ++i) bv[i] = bias_chunk(i);
@@ -127,7 +126,7 @@ softmax_rowsdyn_kernel(DynArgs A)
         for (int idx = lane; idx < in_chunks; idx += 64) {
             i32x4 v;
             if (4 * idx + 3 < valid_el) {
-                v = stream_load(src + idx);
+                v = stream_load_i32x4(src1 + 4 * idx);
             } else {
                 v = (i32x4){0, 0, 0, 0};
                 if (4 * idx < valid_el) v.x = src1[4 * idx];
@@ -137,7 +136,7 @@ softmax_rowsdyn_kernel(DynArgs A)
             if (bias != nullptr) {
                 uint32_t o = boff + 4u * (uint32_t)idx;
                 if (o >= pe) o -= pe;
-                v = add_bias(v, *reinterpret_cast<const i32x4 *>(bias + o));
+                v = add_bias(v, load_i32x4(bias + o));
             }
             lds4[idx] = v;
         }
@@ -254,7 +253,7 @@ softmax_rowsdyn_kernel(DynArgs A)
             const int idx = i * 64 + lane;
             if (idx < n16) {
                 if (16 * idx + 15 < valid_el) {
-                    stream_store(reinterpret_cast<const u32x4 *>(lds)[idx], reinterpret_cast<u32x4 *>(dst8) + idx);
+                    stream_store_bytes16(reinterpret_cast<const u32x4 *>(lds)[idx], dst8 + 16 * idx);
                 } else {
 #pragma unroll 1
                     for (int b = 16 * idx; b < valid_el && b < 16 * idx + 16; ++b) dst8[b] = lds[b];
@@ -267,7 +266,7 @@ softmax_rowsdyn_kernel(DynArgs A)
             const int idx = i * 64 + lane;
             if (idx < in_chunks) {
                 if (4 * idx + 3 < valid_el) {
-                    stream_store(lds32[idx], reinterpret_cast<uint32_t *>(dst8) + idx);
+                    stream_store_bytes4(lds32[idx], dst8 + 4 * idx);
                 } else {
 #pragma unroll 1
                     for (int b = 4 * idx; b < valid_el && b < 4 * idx + 4; ++b) dst8[b] = lds[b];

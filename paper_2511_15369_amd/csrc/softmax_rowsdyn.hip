@@ -35,9 +35,8 @@ hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_m
     if (!rowsdyn_geometry(cols, &k, &slots)) return hipSuccess;
     const int rpw = 64 / k;
     const bool has_bias = c.bias != nullptr;
-    const bool aligned = ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.out)) & 15) == 0;
-    const bool bias_ok = !has_bias || ((reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&
-                                       ((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
+    const bool aligned = ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.bias)) & 3) == 0;
+    const bool bias_ok = !has_bias || (((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
                                        (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 31) &&
                                        c.P.bias_period_rows >= rpw);
     const int64_t n_slabs = (c.rows + rpw - 1) / rpw;

@@ -175,10 +175,10 @@ softmax_wgrow_kernel(WideArgs A)
         const int b = s * T + tid;
         const int c0 = 4 * b - phi;
         if (!edge_slot(s)) {                          // every thread's block lies inside the row
-            stream_store(w[s], reinterpret_cast<uint32_t *>(dst8) + b);
+            stream_store_bytes4(w[s], dst8 + 4 * b);
         } else if (b < nb) {
             if (c0 >= 0 && c0 + 3 < cols) {
-                stream_store(w[s], reinterpret_cast<uint32_t *>(dst8) + b);
+                stream_store_bytes4(w[s], dst8 + 4 * b);
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)

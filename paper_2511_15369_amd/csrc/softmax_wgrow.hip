@@ -31,12 +31,12 @@ hipError_t softmax_wgrow_launch(const SoftmaxCall &c, int32_t cols, int post_mod
 {
     *done = 0;
     int waves = 0, slots = 0;
-    // The tensor may start anywhere on the 4-byte grid if the output starts at the same offset
-    // from its own 4-byte grid (views cut at the same element of both tensors do); the additive
-    // table is indexed block by block and needs both on the 16-byte grid.
-    const uintptr_t sa = reinterpret_cast<uintptr_t>(c.scores), oa = reinterpret_cast<uintptr_t>(c.out);
+    // The tensor may start anywhere on the 4-byte grid (rows are addressed on the 16-byte grid
+    // below it) and the output anywhere; the additive table is indexed block by block and needs
+    // both tensors on the 16-byte grid.
+    const uintptr_t sa = reinterpret_cast<uintptr_t>(c.scores);
     const int base_off = (int)((sa & 15) >> 2);
-    if ((sa & 3) != 0 || ((oa - (uintptr_t)base_off) & 3) != 0) return hipSuccess;
+    if ((sa & 3) != 0) return hipSuccess;
     if (!wgrow_geometry(cols, &waves, &slots, base_off != 0)) return hipSuccess;
     const bool has_bias = c.bias != nullptr;
     const bool bias_ok = !has_bias || (base_off == 0 && (reinterpret_cast<uintptr_t>(c.bias) & 15) == 0 &&

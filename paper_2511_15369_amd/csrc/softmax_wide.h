@@ -3,8 +3,9 @@
 // 16-byte block s * 64 + l of the aligned block range that covers the row, so a pass is one
 // fully coalesced 1 KiB load.  A row that does not start on a 16-byte boundary shares its first
 // and last block with its neighbours: their elements are masked on the way in and those
-// blocks are written back with byte stores, every other block with one dword store (so the
-// tensor itself may start anywhere on the 4-byte grid, the output at the same offset).  The
+// blocks are written back with byte stores, every other block with one dword store at whatever
+// byte address it has (so the tensor may start anywhere on the 4-byte grid and the output
+// anywhere at all).  The
 // arithmetic is the slab kernels' (softmax_slab_math with 64 lanes per row).
 // SLOTS is exactly the number of passes a row of this length needs at its worst alignment,
 // ceil(B / 64) with B the most blocks it can touch: a row touches B or B - 1 blocks, so the
@@ -26,7 +27,7 @@ namespace iptq {
 struct WideArgs {
     const int32_t *scores;   // the tensor's address rounded down to 16 bytes
     const int32_t *bias;     // NULL or 16-byte aligned, period * cols a multiple of 4 (base_off == 0 then)
-    uint8_t *out;            // the output's address minus base_off, 4-byte aligned
+    uint8_t *out;            // the output's address minus base_off (any byte address)
     int64_t rows;
     int32_t base_off;        // scores between the rounded-down address and the tensor: 0..3
     int32_t cols;            // >= 8 when cut_el != 0 (host)
@@ -163,16 +164,16 @@ softmax_wide_kernel(WideArgs A)
     }
 
     // ---- write back: whole blocks as dwords, the two shared edge blocks byte by byte
-    uint8_t *dst8 = A.out + (e0 - phi);               // the byte of the row's first block, 4-byte aligned
+    uint8_t *dst8 = A.out + (e0 - phi);               // the byte of the row's first block
 #pragma unroll
     for (int s = 0; s < SLOTS; ++s) {
         const int b = s * 64 + lane;
         const int c0 = 4 * b - phi;
         if (!edge_slot(s)) {                          // every lane's block lies inside the row
-            stream_store(w[s], reinterpret_cast<uint32_t *>(dst8) + b);
+            stream_store_bytes4(w[s], dst8 + 4 * b);
         } else if (b < nb) {
             if (c0 >= 0 && c0 + 3 < cols) {
-                stream_store(w[s], reinterpret_cast<uint32_t *>(dst8) + b);
+                stream_store_bytes4(w[s], dst8 + 4 * b);
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)

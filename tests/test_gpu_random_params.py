@@ -107,6 +107,7 @@ def test_softmax_random_row_lengths_and_views(seed):
             bias[rng.random((period, cols)) < 0.02] = I32_MIN
         elif rng.integers(0, 2):
             off = int(rng.integers(1, 8))
+        ooff = off if rng.integers(0, 2) else int(rng.integers(0, 17))      # output view: same or another offset
         want = ref.softmax_i32(x, p, bias, period).view(np.uint8).reshape(-1)
         n = rows * cols
         d_in = torch.zeros(n + 16, dtype=torch.int32, device="cuda")
@@ -114,11 +115,11 @@ def test_softmax_random_row_lengths_and_views(seed):
         d_bias = torch.from_numpy(bias).cuda() if bias is not None else None
         for algo in (0, 2, 3, 4):
             d_out = torch.full((n + 32,), 0x5A, dtype=torch.uint8, device="cuda").view(torch.int8 if signed else torch.uint8)
-            ip.softmax_i32(d_in[off:off + n], d_bias, period, d_out[off:off + n], rows, cols, lib_softmax(p, algo))
+            ip.softmax_i32(d_in[off:off + n], d_bias, period, d_out[ooff:ooff + n], rows, cols, lib_softmax(p, algo))
             torch.cuda.synchronize()
             got = d_out.view(torch.uint8).cpu().numpy()
-            assert np.array_equal(got[off:off + n], want), (it, cols, rows, algo, off, period, p)
-            assert (got[:off] == 0x5A).all() and (got[off + n:] == 0x5A).all(), (it, cols, rows, algo, off)
+            assert np.array_equal(got[ooff:ooff + n], want), (it, cols, rows, algo, off, ooff, period, p)
+            assert (got[:ooff] == 0x5A).all() and (got[ooff + n:] == 0x5A).all(), (it, cols, rows, algo, off, ooff)
 
 
 @pytest.mark.parametrize("seed", range(3))
