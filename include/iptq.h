@@ -162,7 +162,8 @@ int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t out_is_sig
  * 144, 257 or 577; any other row length up to 40957 runs in the register-resident kernels with
  * a run-time row length, longer rows in a slower multi-pass kernel.  The tensors need their
  * natural alignment only (views into larger tensors run at the same speed as tensors on the
- * 16-byte grid); an additive table is fused when bias_period_rows * cols is a multiple of 4.
+ * 16-byte grid); an additive table of any size is fused (a little faster when
+ * bias_period_rows * cols is a multiple of 4, as with 4, 8, 16 or 32 Swin heads).
  */
 int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias, int64_t bias_period_rows,
                      void *d_out, int64_t rows, int32_t cols, const iptq_softmax_params_t *p,

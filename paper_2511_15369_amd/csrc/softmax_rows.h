@@ -113,6 +113,24 @@ IPTQ_DEV uint32_t row_mod_period(uint32_t row, const SoftmaxDev &P)
     return row - q * (uint32_t)P.bias_period_rows;
 }
 
+// Four consecutive entries of the additive table from entry o (0 <= o < pe entries in all),
+// continuing at entry 0 past the table's end.  The table's size need not be a multiple of
+// four (Swin with 3 or 6 heads: 147 * 49 entries): the load is placed so that it ends inside
+// the table (`a`), and a chunk that straddles the end takes its last entries from `first4`
+// (entries 0..3, loaded once per wavefront).  Branch-free; `sh` is 0 for every other chunk.
+IPTQ_DEV i32x4 bias_chunk_wrapping(const int32_t *bias, uint32_t o, uint32_t pe, const i32x4 first4)
+{
+    const uint32_t a = min(o, pe - 4u);
+    const uint32_t sh = o - a;
+    const i32x4 A = load_i32x4(bias + a);
+    i32x4 r;
+    r.x = sh == 0 ? A.x : (sh == 1 ? A.y : (sh == 2 ? A.z : A.w));
+    r.y = sh == 0 ? A.y : (sh == 1 ? A.z : (sh == 2 ? A.w : first4.x));
+    r.z = sh == 0 ? A.z : (sh == 1 ? A.w : (sh == 2 ? first4.x : first4.y));
+    r.w = sh == 0 ? A.w : (sh == 1 ? first4.x : (sh == 2 ? first4.y : first4.z));
+    return r;
+}
+
 // bytes 3 of (a, b, c, d) -> one dword (a in byte 0)
 IPTQ_DEV uint32_t pack_top_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
 {
@@ -312,12 +330,18 @@ softmax_rows_kernel(SoftmaxBatch B)
     // element and zero-fills the rest; its surplus rows are computed and never stored.
     const bool partial = I.tail_rows != 0 && slab == I.n_slabs - 1;
     const int valid_el = (partial ? I.tail_rows : RPW) * COLS;
-    auto copy_in = [&](auto tag) {
+    // STRADDLE: the additive table's size is not a multiple of four scores and its end falls
+    // inside this slab, so one of the slab's chunks takes entries from both ends of the table.
+    uint32_t boff = 0;
+    if (BIAS) boff = row_mod_period((uint32_t)(slab * RPW), P) * (uint32_t)COLS;
+    const uint32_t pe = (uint32_t)P.bias_period_rows * (uint32_t)COLS;
+    const bool straddle = BIAS && (pe & 3u) != 0 && boff + (uint32_t)SLAB > pe;    // wavefront-uniform
+    auto copy_in = [&](auto tag, auto straddle_tag) {
         constexpr bool PARTIAL = decltype(tag)::value;
+        constexpr bool STRADDLE = decltype(straddle_tag)::value;
         i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
-        uint32_t boff = 0;
-        if (BIAS) boff = row_mod_period((uint32_t)(slab * RPW), P) * (uint32_t)COLS;
-        const uint32_t pe = (uint32_t)P.bias_period_rows * (uint32_t)COLS;
+        i32x4 first4 = {0, 0, 0, 0};
+        if (BIAS && STRADDLE) first4 = load_i32x4(bias);
 #pragma unroll
         for (int i = 0; i < (IN_CHUNKS + 63) / 64; ++i) {
             const int idx = i * 64 + lane;
@@ -341,7 +365,7 @@ softmax_rows_kernel(SoftmaxBatch B)
             if (BIAS) {
                 uint32_t o = boff + 4u * (uint32_t)li;
                 if (o >= pe) o -= pe;
-                const i32x4 bv = load_i32x4(bias + o);
+                const i32x4 bv = STRADDLE ? bias_chunk_wrapping(bias, o, pe, first4) : load_i32x4(bias + o);
                 v.x = v.x == kI32Min ? v.x : sat_add_i32(v.x, bv.x);
                 v.y = v.y == kI32Min ? v.y : sat_add_i32(v.y, bv.y);
                 v.z = v.z == kI32Min ? v.z : sat_add_i32(v.z, bv.z);
@@ -351,8 +375,9 @@ softmax_rows_kernel(SoftmaxBatch B)
         }
         wave_lds_fence();
     };
-    if (partial) copy_in(std::true_type{});
-    else copy_in(std::false_type{});
+    if (partial) copy_in(std::true_type{}, std::integral_constant<bool, BIAS>{});
+    else if (straddle) copy_in(std::false_type{}, std::true_type{});
+    else copy_in(std::false_type{}, std::false_type{});
 
     // ---- this lane's blocks; elements outside the row become "minus infinity"
     int32_t x[SLOTS][4];

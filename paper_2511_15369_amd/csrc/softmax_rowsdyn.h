@@ -83,8 +83,11 @@ softmax_rowsdyn_kernel(DynArgs A)
         v.w = v.w == kI32Min ? v.w : sat_add_i32(v.w, bv.w);
         return v;
     };
-    auto copy_in = [&](auto bias_tag) {
+    auto copy_in = [&](auto bias_tag, auto straddle_tag) {
         constexpr bool BIAS = decltype(bias_tag)::value;
+        // the additive table's size is not a multiple of four scores and its end falls inside
+        // this slab: one chunk takes entries from both ends of the table
+        constexpr bool STRADDLE = decltype(straddle_tag)::value;
         i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
         const int last = in_chunks - 1;
         auto chunk_of = [&](int i) {
@@ -97,10 +100,12 @@ softmax_rowsdyn_kernel(DynArgs A)
         // bias chunks come from L2: a ring of kAhead loads in flight behind the score loads
         // keeps the staging registers at 4 * (SLOTS + kAhead)
         constexpr int kAhead = 4;
+        i32x4 first4 = {0, 0, 0, 0};
+        if (STRADDLE) first4 = load_i32x4(bias);
         auto bias_chunk = [&](int i) {
             uint32_t o = boff + 4u * (uint32_t)chunk_of(i);
             if (o >= pe) o -= pe;
-            return load_i32x4(bias + o);
+            return STRADDLE ? bias_chunk_wrapping(bias, o, pe, first4) : load_i32x4(bias + o);
         };
         i32x4 v[SLOTS], bv[BIAS ? kAhead : 1];
 #pragma unroll
@@ -136,15 +141,20 @@ softmax_rowsdyn_kernel(DynArgs A)
             if (bias != nullptr) {
                 uint32_t o = boff + 4u * (uint32_t)idx;
                 if (o >= pe) o -= pe;
-                v = add_bias(v, load_i32x4(bias + o));
+                v = add_bias(v, bias_chunk_wrapping(bias, o, pe, load_i32x4(bias)));
             }
             lds4[idx] = v;
         }
         wave_lds_fence();
     };
     if (partial) copy_in_partial();
-    else if (bias != nullptr) copy_in(std::true_type{});
-    else copy_in(std::false_type{});
+    else if (bias == nullptr) copy_in(std::false_type{}, std::false_type{});
+    else {
+        const uint32_t pe = (uint32_t)P.bias_period_rows * (uint32_t)cols;
+        const uint32_t boff = row_mod_period((uint32_t)(slab * RPW), P) * (uint32_t)cols;
+        if ((pe & 3u) != 0 && boff + (uint32_t)slab_el > pe) copy_in(std::true_type{}, std::true_type{});
+        else copy_in(std::true_type{}, std::false_type{});
+    }
 
     // ---- this lane's blocks; elements outside the row become "minus infinity"
     const int lr = lane / K;                          // row inside the slab

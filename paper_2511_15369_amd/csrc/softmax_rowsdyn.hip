@@ -36,7 +36,7 @@ hipError_t softmax_rowsdyn_launch(const SoftmaxCall &c, int32_t cols, int post_m
     const int rpw = 64 / k;
     const bool has_bias = c.bias != nullptr;
     const bool aligned = ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.bias)) & 3) == 0;
-    const bool bias_ok = !has_bias || (((int64_t)c.P.bias_period_rows * cols) % 4 == 0 &&
+    const bool bias_ok = !has_bias || ((int64_t)c.P.bias_period_rows * cols >= 4 &&
                                        (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 31) &&
                                        c.P.bias_period_rows >= rpw);
     const int64_t n_slabs = (c.rows + rpw - 1) / rpw;

@@ -166,13 +166,15 @@ def test_softmax_signed_output_around_zero_point_minus_128(cols):
                     assert np.array_equal(gpu_softmax(scores, p, b, period, algo=algo), want), (variant, qmax, algo)
 
 
-@pytest.mark.parametrize("cols,period", [(49, 196), (49, 392), (49, 12544), (197, 197), (197, 2364), (64, 256),
+@pytest.mark.parametrize("cols,period", [(49, 196), (49, 392), (49, 12544), (49, 147), (49, 294), (49, 33), (197, 197), (197, 2364), (64, 256), (5, 65), (9, 100), (333, 17),
                                          (64, 200), (100, 96), (100, 45), (256, 1024), (576, 2304), (33, 7)])
 def test_softmax_additive_table_with_workgroups_that_share_its_rows(cols, period):
     """With an additive table the wavefronts of a workgroup take slabs that start at congruent
     rows modulo the table's period (so that they read the same table rows): every slab must
     still be served exactly once, for periods that divide the slab, share a factor with it or
-    are coprime to it, with a row count that leaves the last group of slabs incomplete."""
+    are coprime to it, with a row count that leaves the last group of slabs incomplete.  Tables
+    whose size is not a multiple of four scores (Swin with 3 or 6 heads: 147 x 49, 294 x 49)
+    are read in chunks of four that can straddle the table's end."""
     rng = np.random.default_rng(cols * 100003 + period)
     for rows in (period * 9 + 5, 4111, 257):
         scores = np.rint(rng.standard_normal((rows, cols)) * 400).astype(np.int32)
