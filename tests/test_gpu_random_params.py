@@ -102,7 +102,7 @@ def test_softmax_random_row_lengths_and_views(seed):
             x[rng.integers(0, rows)] = I32_MIN
         bias, period, off = None, 0, 0
         if rng.integers(0, 3) == 0:
-            period = int(rng.choice([1, 2, 3, 4, 8, 64]))
+            period = int(rng.choice([1, 2, 3, 4, 8, 64, 65, 147]))
             bias = np.rint(rng.standard_normal((period, cols)) * 2.0 * p.i0).astype(np.int32)
             bias[rng.random((period, cols)) < 0.02] = I32_MIN
         elif rng.integers(0, 2):
