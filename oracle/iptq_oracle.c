@@ -14,7 +14,9 @@
  *   rshr_round(v, s) = floor((v + 2^(s-1)) / 2^s) for s >= 1 and v for s == 0
  *     (round to nearest, ties toward +infinity);
  *   the value INT32_MIN in a score row is "minus infinity": it never wins the row
- *     maximum, is never added to, and its exponential is 0;
+ *     maximum, is never added to, and its exponential is 0; an entry INT32_MIN of an
+ *     additive table (relative-position bias, shifted-window mask) makes the position
+ *     minus infinity whatever the score is (any other entry is added with saturation);
  *   a row whose entries are all minus infinity yields the requantized value of 0.
  *
  * Parity pins: tests/test_oracle_*.py (closed forms, exact rational brackets,
@@ -39,7 +41,8 @@ typedef struct {
 } orc_dyadic;
 
 typedef struct {
-    int32_t variant;  /* 0: 1 + x/2 fractional part (Eq. 10); 1: 1 + (0.1011)b x (Eq. 13-14) */
+    int32_t variant;  /* 0: 1 + x/2 fractional part (Eq. 10); 1: 1 + (0.1011)b x (Eq. 13-14);
+                         2: second-degree term of the Taylor series of Eq. 11 added to variant 1 */
     int32_t i0;       /* floor(1 / S_delta) (Eq. 14) */
     int32_t n_shift;  /* guard bits N: exponentials carry the scale S_delta / 2^N */
     int32_t m_bits;   /* M of Eq. 15 */
@@ -149,6 +152,10 @@ static int64_t bit_exp(int64_t delta, const orc_softmax_params *p)
         frac = shr_floor(-r, 1); /* Eq. 10: x / 2 */
     else
         frac = shr_floor(-r, 1) + shr_floor(-r, 3) + shr_floor(-r, 4); /* Eq. 13: Phi(x) */
+    /* Eq. 11 with D = 2 (the "D2" form of the degree ablation; its integer form is not printed:
+       declared reading): y = Phi(-r) is ln2 X on the scale 1/S ~ i0, so (ln2 X)^2 / 2 on that
+       scale is y^2 / (2 i0), floored */
+    if (p->variant == 2) frac += floor_div(frac * frac, 2 * i0);
     int64_t base = frac + i0; /* Eq. 14: Phi(-r) + floor(1 / S) */
     /* Eq. 9: the integer part is a right shift; a shift of 32 or more leaves nothing */
     if (q >= 32) return 0;
@@ -157,8 +164,9 @@ static int64_t bit_exp(int64_t delta, const orc_softmax_params *p)
 
 static int softmax_params_ok(const orc_softmax_params *p, int32_t cols)
 {
-    if (p->variant != 0 && p->variant != 1) return 0;
+    if (p->variant != 0 && p->variant != 1 && p->variant != 2) return 0;
     if (p->i0 < 16 || p->i0 >= (1 << 24)) return 0;
+    if (p->variant == 2 && p->i0 >= (1 << 16)) return 0; /* y^2 stays below 2^31 */
     if (p->n_shift < 0 || p->n_shift > 20) return 0;
     if (((int64_t)p->i0 << p->n_shift) >= (1 << 24)) return 0;
     if (p->out_bits < 2 || p->out_bits > 8) return 0;
@@ -169,12 +177,28 @@ static int softmax_params_ok(const orc_softmax_params *p, int32_t cols)
     return dyadic_ok(&p->post, p->out_is_signed);
 }
 
-int iptq_ref_softmax_i32(const int32_t *scores, const int32_t *bias, int64_t bias_period_rows,
-                         void *out, int64_t rows, int32_t cols, const orc_softmax_params *p)
+/* x + t for one entry t of an additive table: minus infinity if either is */
+static int64_t add_table_entry(int64_t x, int64_t t)
+{
+    if (x == INT32_MIN || t == INT32_MIN) return INT32_MIN;
+    return sat_i32(x + t);
+}
+
+/*
+ * Rows are ordered [image, window, head, query].  bias: [bias_period_rows, cols], row r takes
+ * table row r mod bias_period_rows (the relative-position bias, period heads * cols).
+ * mask: [n_windows, cols, cols], the shifted-window mask: row r lies in window
+ * (r div (heads * cols)) mod n_windows and is query r mod cols of it.  Either may be NULL.
+ */
+int iptq_ref_softmax_i32_windowed(const int32_t *scores, const int32_t *bias,
+                                  int64_t bias_period_rows, const int32_t *mask,
+                                  int64_t n_windows, int64_t heads, void *out, int64_t rows,
+                                  int32_t cols, const orc_softmax_params *p)
 {
     if (rows < 0 || cols < 1 || !p) return ORC_ERR_ARG;
     if (rows > 0 && (!scores || !out)) return ORC_ERR_ARG;
     if (bias && bias_period_rows < 1) return ORC_ERR_ARG;
+    if (mask && (n_windows < 1 || heads < 1)) return ORC_ERR_ARG;
     if (!softmax_params_ok(p, cols)) return ORC_ERR_ARG;
 
     int64_t *x = (int64_t *)malloc(sizeof(int64_t) * (size_t)cols);
@@ -185,11 +209,18 @@ int iptq_ref_softmax_i32(const int32_t *scores, const int32_t *bias, int64_t bia
     for (int64_t row = 0; row < rows; ++row) {
         const int32_t *srow = scores + row * cols;
         const int32_t *brow = bias ? bias + (row % bias_period_rows) * cols : 0;
+        const int32_t *mrow = 0;
+        if (mask) {
+            const int64_t window = (row / (heads * cols)) % n_windows;
+            const int64_t query = row % cols;
+            mrow = mask + (window * cols + query) * cols;
+        }
 
-        /* additive bias and optional requantization; minus infinity stays as it is */
+        /* additive bias, additive mask and optional requantization; minus infinity stays as it is */
         for (int32_t j = 0; j < cols; ++j) {
             int64_t v = srow[j];
-            if (v != INT32_MIN && brow) v = sat_i32(v + (int64_t)brow[j]);
+            if (brow) v = add_table_entry(v, brow[j]);
+            if (mrow) v = add_table_entry(v, mrow[j]);
             if (v != INT32_MIN && has_pre) v = sat_i32(rshr_round(v * (int64_t)p->pre_m, p->pre_s));
             x[j] = v;
         }
@@ -219,6 +250,12 @@ int iptq_ref_softmax_i32(const int32_t *scores, const int32_t *bias, int64_t bia
     free(x);
     free(qexp);
     return ORC_OK;
+}
+
+int iptq_ref_softmax_i32(const int32_t *scores, const int32_t *bias, int64_t bias_period_rows,
+                         void *out, int64_t rows, int32_t cols, const orc_softmax_params *p)
+{
+    return iptq_ref_softmax_i32_windowed(scores, bias, bias_period_rows, 0, 0, 0, out, rows, cols, p);
 }
 
 /* ------------------------------------------------------------------ GELU */

@@ -107,6 +107,10 @@ def _load():
                                          ctypes.POINTER(_Dyadic)]
         lib.iptq_ref_softmax_i32.argtypes = [vp, vp, ctypes.c_int64, vp, ctypes.c_int64,
                                              ctypes.c_int32, ctypes.POINTER(_SoftmaxParams)]
+        lib.iptq_ref_softmax_i32_windowed.argtypes = [vp, vp, ctypes.c_int64, vp, ctypes.c_int64,
+                                                      ctypes.c_int64, vp, ctypes.c_int64,
+                                                      ctypes.c_int32, ctypes.POINTER(_SoftmaxParams)]
+        lib.iptq_ref_softmax_i32_windowed.restype = ctypes.c_int
         lib.iptq_ref_gelu_i8.argtypes = [vp, vp, ctypes.c_int64, ctypes.POINTER(_GeluParams)]
         lib.iptq_ref_gelu_i32.argtypes = [vp, vp, ctypes.c_int64, ctypes.POINTER(_GeluParams)]
         lib.iptq_ref_bit_exp.argtypes = [ctypes.c_int64, ctypes.POINTER(_SoftmaxParams)]
@@ -155,6 +159,28 @@ def softmax_i32(scores: np.ndarray, p: SoftmaxParams, bias: Optional[np.ndarray]
     pc = p.c()
     _check(_load().iptq_ref_softmax_i32(_ptr(scores), _ptr(bias), bias_period_rows, _ptr(out),
                                         rows, cols, ctypes.byref(pc)), "softmax_i32")
+    return out
+
+
+def softmax_i32_windowed(scores: np.ndarray, p: SoftmaxParams, bias: Optional[np.ndarray],
+                         bias_period_rows: int, mask: Optional[np.ndarray], heads: int) -> np.ndarray:
+    """Rows ordered [image, window, head, query]; mask [n_windows, cols, cols] (0 / INT32_MIN
+    or any additive int32), added beside the bias of period heads * cols."""
+    scores = np.ascontiguousarray(scores, dtype=np.int32)
+    rows, cols = scores.shape
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.int32)
+        assert bias.shape == (bias_period_rows, cols)
+    n_windows = 0
+    if mask is not None:
+        mask = np.ascontiguousarray(mask, dtype=np.int32)
+        assert mask.ndim == 3 and mask.shape[1:] == (cols, cols)
+        n_windows = mask.shape[0]
+    out = np.empty((rows, cols), dtype=np.int8 if p.out_is_signed else np.uint8)
+    pc = p.c()
+    _check(_load().iptq_ref_softmax_i32_windowed(_ptr(scores), _ptr(bias), bias_period_rows,
+                                                 _ptr(mask), n_windows, heads, _ptr(out), rows,
+                                                 cols, ctypes.byref(pc)), "softmax_i32_windowed")
     return out
 
 

@@ -246,7 +246,7 @@ def test_out_bits():
 
 def test_rejects_bad_params():
     row = np.zeros((1, 4), np.int32)
-    bad = [params(2, 16, 0), params(0, 15, 0), params(0, 2 ** 24, 0), params(0, 2 ** 20, 4),
+    bad = [params(3, 16, 0), params(0, 15, 0), params(0, 2 ** 24, 0), params(0, 2 ** 20, 4),
            params(0, 16, 0, out_bits=9), params(0, 16, 0, m_bits=32),
            params(0, 2 ** 15, 8, m_bits=24), params(0, 16, 0, pre_m=0),
            params(0, 16, 0, post=ref.Dyadic(1, 0, 0, -1, 255))]
@@ -285,3 +285,101 @@ def test_all_short_rows_over_a_small_value_range():
             got = ref.softmax_i32(rows, p)
             for r, g in zip(rows.tolist(), got.tolist()):
                 assert g == brute_softmax_row(r, variant, i0, n)
+
+
+# ----------------------------------------------------------------- second-degree form (variant 2)
+def real_bit_exp_d2(delta, i0):
+    """Eq. 11 with D = 2 over the reals, on top of the base change and the split of Eq. 7-9:
+    2^-x ~ 1 - c x + (c x)^2 / 2 with c = (0.1011)b."""
+    y = 1.4375 * (-delta) / i0
+    q = math.floor(y)
+    x = y - q
+    return 2.0 ** (-q) * (1.0 - 0.6875 * x + (0.6875 * x) ** 2 / 2.0)
+
+
+@pytest.mark.parametrize("i0,n", PARAM_SETS)
+def test_second_degree_tracks_real_valued_series(i0, n):
+    p = params(2, i0, n)
+    one = i0 << n
+    assert ref.bit_exp(0, p) == one
+    # floors: Qp < 1, Phi three floors < 2.4, the squared term moves by < 0.6875 * 2.4 / ... < 2, its
+    # own floor < 1, the final shift < 1
+    tol = (1.4375 + 2.4 + 2.0 + 1.0) / i0 + 1.0 / one
+    for delta in range(0, -40 * i0, -max(1, i0 // 37)):
+        got = ref.bit_exp(delta, p) / one
+        cands = [real_bit_exp_d2(delta + e, i0) for e in (-1.0, 0.0, 1.0)]
+        assert min(abs(got - c) for c in cands) <= tol, (delta, got, cands)
+
+
+def test_second_degree_error_against_exp_is_its_analytic_worst_case():
+    # on x in [0, 1): 1 - c x + (c x)^2 / 2 - 2^-x with c = 0.6875 peaks at x -> 1:
+    # 1 - 0.6875 + 0.236328 - 0.5 = 0.048828 (the exact-ln2 series gives 0.0471 there);
+    # the first-degree form has 0.1875 at the same point
+    worst_real = max(abs(1 - 0.6875 * x + (0.6875 * x) ** 2 / 2 - 2.0 ** (-x))
+                     for x in np.linspace(0.0, 1.0, 20001)[:-1])
+    assert abs(worst_real - 0.048828) < 2e-4
+    i0, n = 4096, 3
+    p2, p1 = params(2, i0, n), params(1, i0, n)
+    worst2 = worst1 = 0.0
+    for delta in range(0, -12 * i0, -7):
+        t = math.exp(delta / i0)
+        worst2 = max(worst2, abs(ref.bit_exp(delta, p2) / (i0 << n) - t))
+        worst1 = max(worst1, abs(ref.bit_exp(delta, p1) / (i0 << n) - t))
+    assert worst2 <= 0.048828 + 0.0014 + 6.0 / i0
+    assert worst2 >= 0.048828 * 0.8
+    assert worst2 < worst1 / 3
+
+
+def test_second_degree_term_is_the_floored_square():
+    # the only difference from variant 1 is + floor(Phi^2 / (2 i0)) before the shifts
+    for i0, n in PARAM_SETS:
+        p1, p2 = params(1, i0, 0), params(2, i0, 0)
+        for r in range(0, i0, max(1, i0 // 50)):
+            # find a delta whose split has q = 0 and this r: n = r means Qp = -r; scan near
+            delta = -math.ceil(r / 1.4375)
+            for d in (delta - 1, delta, delta + 1):
+                if d > 0:
+                    continue
+                nn = -(d + (d >> 1) - (d >> 4))
+                if nn >= i0:
+                    continue
+                phi = ((-nn) >> 1) + ((-nn) >> 3) + ((-nn) >> 4)
+                assert ref.bit_exp(d, p1) == i0 + phi
+                assert ref.bit_exp(d, p2) == i0 + phi + (phi * phi) // (2 * i0)
+
+
+def test_second_degree_domain():
+    with pytest.raises(ref.OracleError):
+        ref.softmax_i32(np.zeros((1, 4), np.int32), params(2, 1 << 16, 0))
+    ref.softmax_i32(np.zeros((1, 4), np.int32), params(2, (1 << 16) - 1, 0))
+
+
+# ----------------------------------------------------------------- additive tables and minus infinity
+def test_table_entry_int32_min_masks_whatever_the_score():
+    p = params(1, 16, 0)
+    # hand-worked: keys 0 and 2 live with equal scores -> 64 each (row C of the golden file);
+    # key 1 is masked by the table although its score is positive and the largest
+    scores = np.array([[5, 1000, 5]], np.int32)
+    bias = np.array([[0, INT32_MIN, 0]], np.int32)
+    assert ref.softmax_i32(scores, p, bias, 1)[0].tolist() == [64, 0, 64]
+    # every key masked by the table, scores positive: the all-masked row, i.e. the zero-point
+    bias = np.full((1, 3), INT32_MIN, np.int32)
+    pz = params(1, 16, 0, post=ref.Dyadic(1, 0, 3, 0, 255))
+    assert ref.softmax_i32(np.array([[7, 1, 9]], np.int32), pz, bias, 1)[0].tolist() == [3, 3, 3]
+    # any other table value is an ordinary saturating addend: INT32_MIN + 1 leaves the key live
+    bias = np.array([[INT32_MIN + 1, INT32_MIN + 1, INT32_MIN + 1]], np.int32)
+    assert ref.softmax_i32(np.array([[7, 7, 7]], np.int32), p, bias, 1)[0].tolist() == [42, 42, 42]
+
+
+def test_saturated_pre_requantized_scores():
+    # hand-worked: 4 * (2^31 - 1) and 4 * 2^30 both exceed int32 and saturate at 2^31 - 1, so the
+    # two keys tie: 64, 64 (row C).  Without the saturation the second would be 2^32 below the
+    # first and get 0.
+    p = params(1, 16, 0, pre_m=4, pre_s=0)
+    row = np.array([[2 ** 31 - 1, 2 ** 30]], np.int32)
+    assert ref.softmax_i32(row, p)[0].tolist() == [64, 64]
+    # one step below the saturation point the order is kept: 4 * (2^29 - 8) = 2^31 - 32, delta -31:
+    # Qp = -31 - 16 + 2 = -45, q = 2, r = 13, Phi(-13) = -7 - 2 - 1 = -10, base 6, Qexp = 6 >> 2 = 1
+    # sum 17, f = floor(2^30 / 17) = 63161283, p = (16 f) >> 23 = 120, (1 f) >> 23 = 7
+    row = np.array([[2 ** 30, 2 ** 29 - 8]], np.int32)
+    assert ref.softmax_i32(row, p)[0].tolist() == [120, 7]

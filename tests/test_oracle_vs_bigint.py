@@ -26,8 +26,9 @@ def softmax_row(row, bias_row, p):
     x = []
     for j, v in enumerate(row):
         v = int(v)
-        if v != I32_MIN and bias_row is not None:
-            v = sat32(v + int(bias_row[j]))
+        if bias_row is not None:
+            b = int(bias_row[j])
+            v = I32_MIN if (v == I32_MIN or b == I32_MIN) else sat32(v + b)
         if v != I32_MIN and not (p.pre_m == 1 and p.pre_s == 0):
             v = sat32(rshr_round(v * p.pre_m, p.pre_s))
         x.append(v)
@@ -41,6 +42,8 @@ def softmax_row(row, bias_row, p):
         qp = d + (d >> 1) - (d >> 4)
         q, r = divmod(-qp, p.i0)
         fr = ((-r) >> 1) if p.variant == 0 else ((-r) >> 1) + ((-r) >> 3) + ((-r) >> 4)
+        if p.variant == 2:
+            fr += (fr * fr) // (2 * p.i0)
         qexp.append(0 if q >= 32 else ((fr + p.i0) << p.n_shift) >> q)
     total = sum(qexp)
     f = (1 << p.m_bits) // total if total > 0 else 0
@@ -65,7 +68,7 @@ def test_softmax_random_parameters(seed):
     for _ in range(60):
         cols = int(rng.integers(1, 40))
         rows = 5
-        i0 = int(rng.choice([16, 17, 100, 181, 4095, 65536, 2 ** 20 + 3, 2 ** 24 - 1]))
+        i0 = int(rng.choice([16, 17, 100, 181, 4095, 65535, 65536, 2 ** 20 + 3, 2 ** 24 - 1]))
         n_max = 0
         while ((i0 << (n_max + 1)) < 2 ** 24) and n_max < 20:
             n_max += 1
@@ -81,7 +84,7 @@ def test_softmax_random_parameters(seed):
         if rng.integers(0, 3) == 0:
             post = ref.Dyadic(1, 0, 0, 0 if not signed else -128, hi)
         pre = (1, 0) if rng.integers(0, 2) else (int(rng.integers(1, 32768)), int(rng.integers(0, 63)))
-        p = ref.SoftmaxParams(variant=int(rng.integers(0, 2)), i0=i0, n_shift=n_shift, m_bits=m_bits,
+        p = ref.SoftmaxParams(variant=int(rng.integers(0, 3 if i0 < 2 ** 16 else 2)), i0=i0, n_shift=n_shift, m_bits=m_bits,
                               out_bits=out_bits, pre_m=pre[0], pre_s=pre[1], post=post,
                               out_is_signed=signed)
         kind = rng.integers(0, 3)
@@ -99,6 +102,7 @@ def test_softmax_random_parameters(seed):
             bias = rng.integers(I32_MIN, I32_MAX + 1, size=(period, cols)).astype(np.int32)
             if rng.integers(0, 2):
                 bias = (bias // 2 ** 20).astype(np.int32)
+            bias[rng.random(bias.shape) < 0.15] = I32_MIN
         got = ref.softmax_i32(x, p, bias, period).astype(np.int64)
         for r in range(rows):
             want = softmax_row(x[r], None if bias is None else bias[r % period], p)
