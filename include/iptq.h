@@ -40,6 +40,8 @@ extern "C" {
 /* Softmax fractional-part approximation of 2^(S(-r)) (the per-layer choice of Section 4.2) */
 #define IPTQ_SOFTMAX_SHIFT_LINEAR 0     /* 1 + x/2            (Eq. 10) */
 #define IPTQ_SOFTMAX_EFFICIENT_BITEXP 1 /* 1 + (0.1011)b x    (Eq. 12-14) */
+#define IPTQ_SOFTMAX_BITEXP_DEGREE2 2   /* 1 + y + y^2/2, y = (0.1011)b x: Eq. 11 with D = 2, the
+                                           second-degree form of the degree ablation (Section 4.4) */
 /* GELU erf polynomial */
 #define IPTQ_GELU_POLY2 0            /* second order a(x+b)^2 + c form (Eq. 2) */
 #define IPTQ_GELU_POLY4_DATA_AWARE 1 /* quartic, a = -0.019913, b = -2.698088 (Eq. 3) */
@@ -71,19 +73,22 @@ typedef struct {
 
 /*
  * Integer softmax of one row x[0..cols) of int32 scores (Section 4.4):
- *   0. x_j == INT32_MIN means "minus infinity" (masked) at every stage below;
- *      otherwise x_j = sat32(x_j + bias_j) when a bias is given, then
+ *   0. x_j == INT32_MIN means "minus infinity" (masked) at every stage below; an entry
+ *      INT32_MIN of an additive table (bias, window mask) makes x_j minus infinity whatever
+ *      the score; otherwise x_j = sat32(x_j + entry) for each table given, then
  *      x_j = sat32(rshr_round(x_j * pre_m, pre_s)) unless (pre_m, pre_s) == (1, 0)
  *   1. d_j = max(x_j - max_j x_j, -2^30)                                  (Eq. 6)
  *   2. Qp = d + (d >> 1) - (d >> 4)                                       (Eq. 7)
  *   3. n = -Qp, q = n div i0, r = n mod i0                                (Eq. 8)
  *   4. base = i0 + ((-r) >> 1)                       variant 0            (Eq. 10)
  *      base = i0 + ((-r) >> 1) + ((-r) >> 3) + ((-r) >> 4)  variant 1     (Eq. 13-14)
+ *      base = i0 + y + floor(y^2 / (2 i0)), y the variant-1 sum   variant 2 (Eq. 11, D = 2; the
+ *      paper prints no integer form of it: this one is the library's reading; i0 < 2^16)
  *   5. Qexp_j = 0 if masked or q >= 32, else (base << n_shift) >> q       (Eq. 9)
  *   6. f = floor(2^m_bits / sum_j Qexp_j)  (0 for an all-masked row)
  *      p_j = (f * Qexp_j) >> (m_bits - (out_bits - 1))                    (Eq. 15)
  *   7. out_j = clamp(rshr_round(p_j * post.m, post.s) + post.zp, post.qmin, post.qmax)
- * Domain: variant in {0,1}; 16 <= i0 < 2^24; n_shift >= 0 with (i0 << n_shift) < 2^24;
+ * Domain: variant in {0,1,2}; 16 <= i0 < 2^24 (< 2^16 for variant 2); n_shift >= 0 with (i0 << n_shift) < 2^24;
  * 2 <= out_bits <= 8; out_bits - 1 <= m_bits <= 31; cols * (i0 << n_shift) <= 2^m_bits
  * (else IPTQ_ERR_RANGE); 1 <= pre_m < 2^15; 0 <= pre_s <= 62.
  */
@@ -130,6 +135,18 @@ typedef struct {
                            IPTQ_ALGO_GENERIC: polynomial per element */
 } iptq_gelu_params_t;
 
+/*
+ * Which kernel family serves softmax rows of `cols` scores (16-byte aligned tensors, a call of
+ * more than a few thousand rows).  *lanes: lanes that share a row; *blocks: 16-byte blocks (or
+ * passes) per lane; both 0 where they do not apply.  Results never depend on the family.
+ */
+#define IPTQ_FAMILY_COMPILED 0          /* row length compiled in (197, 49, 198, 144, 257, 577) */
+#define IPTQ_FAMILY_SLAB 1              /* slab kernel with a run-time row length */
+#define IPTQ_FAMILY_WAVEFRONT_PER_ROW 2
+#define IPTQ_FAMILY_WORKGROUP_PER_ROW 3
+#define IPTQ_FAMILY_THREE_PASS 4        /* re-reads the row: any row length, slow */
+int iptq_softmax_kernel_family(int32_t cols, int32_t *family, int32_t *lanes, int32_t *blocks);
+
 /* Library version (major * 10000 + minor * 100 + patch). */
 int iptq_version(void);
 
@@ -163,11 +180,34 @@ int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t out_is_sig
  * a run-time row length, longer rows in a slower multi-pass kernel.  The tensors need their
  * natural alignment only (views into larger tensors run at the same speed as tensors on the
  * 16-byte grid); an additive table of any size is fused (a little faster when
- * bias_period_rows * cols is a multiple of 4, as with 4, 8, 16 or 32 Swin heads).
+ * bias_period_rows * cols is a multiple of 4, as with 4, 8, 16 or 32 Swin heads), except a
+ * table with fewer rows than one wavefront's slab (64 rows divided by the lanes per row: 32 at
+ * 49 columns, 8 or 16 at 197), or of 2^31 entries and more, which takes the three-pass kernel
+ * (about a sixth of the speed).
  */
 int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias, int64_t bias_period_rows,
                      void *d_out, int64_t rows, int32_t cols, const iptq_softmax_params_t *p,
                      void *stream);
+
+/*
+ * The same for windowed attention whose windows carry their own additive mask (the shifted-window
+ * blocks of a Swin backbone; Section 4.1 keeps every operation of the block in integer
+ * arithmetic): the rows of d_scores are ordered [image, window, head, query], each window has
+ * `cols` queries and `cols` keys, and d_mask is a row-major [n_windows, cols, cols] int32 (device)
+ * whose entry [w, q, k] is added to the score of key k in every row of window w, query q (0 or
+ * INT32_MIN in a Swin model; any other value is an ordinary saturating addend).  Row r lies in
+ * window (r div (heads * cols)) mod n_windows and is query r mod cols.  d_bias as above (normally
+ * [heads * cols, cols] with bias_period_rows = heads * cols); either table may be NULL.  Nothing
+ * is materialised: both tables are read beside the scores.  n_windows >= 1, heads >= 1,
+ * n_windows * heads * cols < 2^31 (else IPTQ_ERR_SHAPE).
+ * Speed: windows of 49 or 144 tokens with a bias run in the slab kernels (the extra table costs
+ * about a tenth of the time); any other shape, or a mask without a bias, takes the slow
+ * three-pass kernel.
+ */
+int iptq_softmax_i32_windowed(const int32_t *d_scores, const int32_t *d_bias,
+                              int64_t bias_period_rows, const int32_t *d_mask, int32_t n_windows,
+                              int32_t heads, void *d_out, int64_t rows, int32_t cols,
+                              const iptq_softmax_params_t *p, void *stream);
 
 /*
  * Integer GELU (Section 4.3, Eq. 3 and 5; steps listed at iptq_gelu_params_t) of n int8
@@ -196,6 +236,9 @@ typedef struct {
     void *d_out;              /* rows * cols bytes (device) */
     int64_t rows;
     iptq_softmax_params_t params;
+    const int32_t *d_mask;    /* NULL or the per-window mask of iptq_softmax_i32_windowed */
+    int32_t n_windows;
+    int32_t heads;
 } iptq_softmax_problem_t;
 
 typedef struct {
@@ -222,8 +265,9 @@ int iptq_gelu_i8_layers(const int8_t *d_in, int64_t in_stride, int8_t *d_out, in
                         int64_t n, int32_t n_layers, const iptq_gelu_params_t *p, void *stream);
 
 /*
- * Host-only helpers: real scales -> integer constants, once, before inference
- * ("pre-quantized as a constant", Section 4.3; floor(1/S), Eq. 14).  IEEE double.
+ * Host-only helpers: real scales -> integer constants, once, before inference (the
+ * polynomial coefficients of Section 4.3 become integer constants; floor(1/S), Eq. 14).
+ * IEEE double.
  */
 
 /* ratio ~ m / 2^s with |m| in [2^14, 2^15) and the largest s <= 62 (see the .cpp for ties). */
@@ -240,6 +284,40 @@ int iptq_softmax_prepare(double s_delta, int32_t cols, int32_t variant, int32_t 
  * post = dyadic(s_in * a * S_e^p * 2^k / 2 / s_out), zero-point zp_out, int8 clip. */
 int iptq_gelu_prepare(double s_in, double s_out, int32_t zp_in, int32_t zp_out, int32_t variant,
                       int32_t max_abs_q, iptq_gelu_params_t *out);
+
+/*
+ * Host-only: the Unified Metric that picks the approximation function of each activation layer
+ * (Section 4.5, Eq. 16-20), i.e. the `variant` field of the parameter structs.  For one layer
+ * and one candidate, from the layer's real-valued output x[0..n) and the candidate's dequantized
+ * output x_hat[0..n) (both host, double):
+ *   q_db  = 10 log10(mean x^2 / mean (x - x_hat)^2)   quantization sensitivity, SQNR in dB (Eq. 18;
+ *           the factor follows the section's worked example: power 10^4 against error powers 100
+ *           and 60 gives 20 dB and 22.21 dB)
+ *   p     = sum (x - x_hat)^2                           quantization perturbation (Eq. 19)
+ *   c     = op_count                                    integer operations of the layer (Eq. 20)
+ *   n_*   = log(1 + exp(.)) of each                     Softplus (Eq. 17)
+ *   score = 3 / (1 / n_q + n_p + n_c)                   one term of Eq. 16
+ * The candidate with the highest score is assigned to the layer (iptq_unified_select: the first
+ * among equals), and the metric Omega of a model is the sum of its layers' assigned scores.
+ * mode IPTQ_METRIC_LITERAL takes p and c as above; with whole-layer values they are 10^3..10^9,
+ * n_p + n_c = p + c swamps 1 / n_q, and the cheapest candidate always wins.  The normalisation
+ * the paper uses is not printed; IPTQ_METRIC_PER_ELEMENT divides p and c by n.
+ * iptq_softmax_op_count / iptq_gelu_op_count: the library's count of arithmetic and bit
+ * operations of the steps listed at the parameter structs (softmax: 18, 22, 25 per score for
+ * variants 0, 1, 2 plus one division per row; GELU: 17, 18 per value); -1 on a bad argument.
+ */
+#define IPTQ_METRIC_LITERAL 0
+#define IPTQ_METRIC_PER_ELEMENT 1
+typedef struct {
+    double q_db, p, c;
+    double n_q, n_p, n_c;
+    double score;
+} iptq_metric_t;
+int iptq_unified_metric(const double *x, const double *x_hat, int64_t n, double op_count,
+                        int32_t mode, iptq_metric_t *out);
+int iptq_unified_select(const iptq_metric_t *candidates, int32_t n_candidates, int32_t *best);
+int64_t iptq_softmax_op_count(int32_t variant, int64_t rows, int32_t cols);
+int64_t iptq_gelu_op_count(int32_t variant, int64_t n);
 
 #ifdef __cplusplus
 }

@@ -48,10 +48,19 @@ class GeluParams(ctypes.Structure):
                 ("algo", ctypes.c_int32)]
 
 
+class Metric(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in ("q_db", "p", "c", "n_q", "n_p", "n_c", "score")]
+
+
+METRIC_LITERAL = 0
+METRIC_PER_ELEMENT = 1
+
+
 class SoftmaxProblem(ctypes.Structure):
     _fields_ = [("d_scores", ctypes.c_void_p), ("d_bias", ctypes.c_void_p),
                 ("bias_period_rows", ctypes.c_int64), ("d_out", ctypes.c_void_p),
-                ("rows", ctypes.c_int64), ("params", SoftmaxParams)]
+                ("rows", ctypes.c_int64), ("params", SoftmaxParams), ("d_mask", ctypes.c_void_p),
+                ("n_windows", ctypes.c_int32), ("heads", ctypes.c_int32)]
 
 
 class GeluProblem(ctypes.Structure):
@@ -81,6 +90,9 @@ def load():
     lib.iptq_strerror.argtypes = [ctypes.c_int]
     lib.iptq_requant.argtypes = [vp, vp, i64, i32, ctypes.POINTER(Dyadic), vp]
     lib.iptq_softmax_i32.argtypes = [vp, vp, i64, vp, i64, i32, ctypes.POINTER(SoftmaxParams), vp]
+    lib.iptq_softmax_i32_windowed.argtypes = [vp, vp, i64, vp, i32, i32, vp, i64, i32,
+                                              ctypes.POINTER(SoftmaxParams), vp]
+    lib.iptq_softmax_i32_windowed.restype = ctypes.c_int
     lib.iptq_gelu_i8.argtypes = [vp, vp, i64, ctypes.POINTER(GeluParams), vp]
     lib.iptq_gelu_i32.argtypes = [vp, vp, i64, ctypes.POINTER(GeluParams), vp]
     lib.iptq_softmax_i32_layers.argtypes = [vp, i64, vp, i64, i64, i32, i32,
@@ -93,6 +105,17 @@ def load():
                                          ctypes.POINTER(SoftmaxParams)]
     lib.iptq_gelu_prepare.argtypes = [ctypes.c_double, ctypes.c_double, i32, i32, i32, i32,
                                       ctypes.POINTER(GeluParams)]
+    lib.iptq_unified_metric.argtypes = [vp, vp, i64, ctypes.c_double, i32, ctypes.POINTER(Metric)]
+    lib.iptq_unified_metric.restype = ctypes.c_int
+    lib.iptq_unified_select.argtypes = [ctypes.POINTER(Metric), i32, ctypes.POINTER(i32)]
+    lib.iptq_unified_select.restype = ctypes.c_int
+    lib.iptq_softmax_op_count.argtypes = [i32, i64, i32]
+    lib.iptq_softmax_op_count.restype = ctypes.c_int64
+    lib.iptq_gelu_op_count.argtypes = [i32, i64]
+    lib.iptq_gelu_op_count.restype = ctypes.c_int64
+    lib.iptq_softmax_kernel_family.argtypes = [i32, ctypes.POINTER(i32), ctypes.POINTER(i32),
+                                               ctypes.POINTER(i32)]
+    lib.iptq_softmax_kernel_family.restype = ctypes.c_int
     for name in ("iptq_requant", "iptq_softmax_i32", "iptq_gelu_i8", "iptq_gelu_i32",
                  "iptq_softmax_i32_layers", "iptq_gelu_i8_layers", "iptq_softmax_i32_batch",
                  "iptq_gelu_i8_batch", "iptq_make_dyadic",
@@ -163,23 +186,46 @@ def gelu_prepare(s_in: float, s_out: float, zp_in: int, zp_out: int, variant: in
     return p
 
 
+def unified_metric(x, x_hat, op_count: float, mode: int = METRIC_LITERAL) -> Metric:
+    """x, x_hat: contiguous float64 numpy arrays of the same size (host)."""
+    import numpy as np
+    assert isinstance(x, np.ndarray) and isinstance(x_hat, np.ndarray)
+    assert x.dtype == np.float64 and x_hat.dtype == np.float64 and x.size == x_hat.size
+    assert x.flags["C_CONTIGUOUS"] and x_hat.flags["C_CONTIGUOUS"]
+    out = Metric()
+    _check(load().iptq_unified_metric(x.ctypes.data_as(ctypes.c_void_p), x_hat.ctypes.data_as(ctypes.c_void_p),
+                                      x.size, float(op_count), mode, ctypes.byref(out)),
+           "iptq_unified_metric")
+    return out
+
+
+def unified_select(candidates: Sequence[Metric]) -> int:
+    arr = (Metric * max(len(candidates), 1))(*candidates)
+    best = ctypes.c_int32()
+    _check(load().iptq_unified_select(arr, len(candidates), ctypes.byref(best)), "iptq_unified_select")
+    return best.value
+
+
+def softmax_op_count(variant: int, rows: int, cols: int) -> int:
+    return int(load().iptq_softmax_op_count(variant, rows, cols))
+
+
+def gelu_op_count(variant: int, n: int) -> int:
+    return int(load().iptq_gelu_op_count(variant, n))
+
+
 # ----------------------------------------------------------------------------- device calls
 def softmax_kernel_family(cols: int) -> str:
     """Which softmax kernel serves 16-byte aligned tensors of this row length."""
-    fn = load().iptq_debug_softmax_layout
-    fn.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
-    fn.restype = ctypes.c_int
-    out = (ctypes.c_int32 * 12)()
-    _check(fn(cols, out), "iptq_debug_softmax_layout")
-    if out[7]:
-        return "compiled row length"
-    if out[0]:
-        return "slab, %d lanes x %d blocks per row" % (out[1], out[2])
-    if out[4]:
-        return "wavefront per row, %d passes" % out[5]
-    if out[9]:
-        return "workgroup of %d wavefronts per row, %d passes" % (out[10], out[11])
-    return "three-pass"
+    fn = load().iptq_softmax_kernel_family
+    fam, lanes, blocks = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(fn(cols, ctypes.byref(fam), ctypes.byref(lanes), ctypes.byref(blocks)),
+           "iptq_softmax_kernel_family")
+    names = {0: "compiled row length", 1: "slab, %d lanes x %d blocks per row",
+             2: "wavefront per row (%d lanes), %d passes", 3: "workgroup of %d lanes per row, %d passes",
+             4: "three-pass"}
+    text = names[fam.value]
+    return text % (lanes.value, blocks.value) if "%d" in text else text
 
 
 def requant(d_in, d_out, n: int, out_is_signed: int, p: Dyadic):
@@ -202,6 +248,24 @@ def softmax_i32(d_scores, d_bias, bias_period_rows: int, d_out, rows: int, cols:
         assert d_bias.numel() >= bias_period_rows * cols
     _check(load().iptq_softmax_i32(_dptr(d_scores), _dptr(d_bias), bias_period_rows, _dptr(d_out),
                                    rows, cols, ctypes.byref(p), _stream()), "iptq_softmax_i32")
+
+
+def softmax_i32_windowed(d_scores, d_bias, bias_period_rows: int, d_mask, n_windows: int, heads: int,
+                         d_out, rows: int, cols: int, p: SoftmaxParams):
+    import torch
+    _need(d_scores, torch.int32, "d_scores")
+    _need(d_out, torch.int8 if p.out_is_signed else torch.uint8, "d_out")
+    assert d_scores.numel() >= rows * cols and d_out.numel() >= rows * cols
+    if d_bias is not None:
+        _need(d_bias, torch.int32, "d_bias")
+        assert d_bias.numel() >= bias_period_rows * cols
+    if d_mask is not None:
+        _need(d_mask, torch.int32, "d_mask")
+        assert d_mask.numel() >= n_windows * cols * cols
+    _check(load().iptq_softmax_i32_windowed(_dptr(d_scores), _dptr(d_bias), bias_period_rows,
+                                            _dptr(d_mask), n_windows, heads, _dptr(d_out), rows,
+                                            cols, ctypes.byref(p), _stream()),
+           "iptq_softmax_i32_windowed")
 
 
 def gelu_i8(d_in, d_out, n: int, p: GeluParams):
@@ -253,7 +317,7 @@ def gelu_i8_layers(d_in, in_stride: int, d_out, out_stride: int, n: int, n_layer
 
 
 def softmax_problem(d_scores, d_bias, bias_period_rows: int, d_out, rows: int, cols: int,
-                    p: SoftmaxParams) -> SoftmaxProblem:
+                    p: SoftmaxParams, d_mask=None, n_windows: int = 0, heads: int = 0) -> SoftmaxProblem:
     """One entry of a softmax batch (same checks as softmax_i32)."""
     import torch
     _need(d_scores, torch.int32, "d_scores")
@@ -262,8 +326,12 @@ def softmax_problem(d_scores, d_bias, bias_period_rows: int, d_out, rows: int, c
     if d_bias is not None:
         _need(d_bias, torch.int32, "d_bias")
         assert d_bias.numel() >= bias_period_rows * cols
+    if d_mask is not None:
+        _need(d_mask, torch.int32, "d_mask")
+        assert d_mask.numel() >= n_windows * cols * cols
     return SoftmaxProblem(d_scores.data_ptr(), None if d_bias is None else d_bias.data_ptr(),
-                          bias_period_rows, d_out.data_ptr(), rows, p)
+                          bias_period_rows, d_out.data_ptr(), rows, p,
+                          None if d_mask is None else d_mask.data_ptr(), n_windows, heads)
 
 
 def gelu_problem(d_in, d_out, n: int, p: GeluParams) -> GeluProblem:

@@ -22,7 +22,8 @@ SOURCES = ["softmax_wgrow_w4_hi.hip", "softmax_wgrow_w8_hi.hip", "softmax_wgrow_
            "softmax_rows_144.hip", "softmax_rows_49.hip", "softmax_rows_197_k8.hip", "softmax_rows_198_k8.hip",
            "softmax_rowsdyn_k2.hip", "softmax_rowsdyn_k1.hip", "softmax_rowsdyn_k4.hip", "softmax_rowsdyn_k8.hip",
            "softmax_rowsdyn_k16.hip", "softmax_kernels.hip", "elementwise_kernels.hip",
-           "softmax_rowsdyn.hip", "softmax_wide.hip", "softmax_wgrow.hip", "api.hip", "plan.cpp"]
+           "softmax_rowsdyn.hip", "softmax_wide.hip", "softmax_wgrow.hip", "api.hip", "debug_hooks.hip",
+           "plan.cpp", "metric.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Wno-unused-parameter",
          # packed-FP32 instructions stay off: the kernels are integer-only anyway

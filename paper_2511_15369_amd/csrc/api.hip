@@ -36,11 +36,18 @@ extern "C" int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t
 // Validates one softmax problem and fills its launch record.  rows == 0 is valid.
 static int softmax_call(const int32_t *d_scores, const int32_t *d_bias, int64_t bias_period_rows,
                         void *d_out, int64_t rows, int32_t cols, const iptq_softmax_params_t *p,
-                        SoftmaxCall *out)
+                        SoftmaxCall *out, const int32_t *d_mask = nullptr, int64_t n_windows = 0,
+                        int64_t heads = 0)
 {
     if (!p) return IPTQ_ERR_NULL;
     int rc = plan_softmax(p, rows, cols, d_bias != nullptr, bias_period_rows, &out->P);
     if (rc != IPTQ_OK) return rc;
+    if (d_mask) {
+        rc = plan_softmax_mask(n_windows, heads, cols, &out->P);
+        if (rc != IPTQ_OK) return rc;
+        if (reinterpret_cast<uintptr_t>(d_mask) & 3) return IPTQ_ERR_ALIGN;
+    }
+    out->mask = d_mask;
     out->scores = d_scores; out->bias = d_bias; out->out = static_cast<uint8_t *>(d_out);
     out->rows = rows; out->out_bits = p->out_bits; out->algo = p->algo;
     if (rows == 0) return IPTQ_OK;
@@ -75,6 +82,18 @@ extern "C" int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias,
     return hip_rc(softmax_dispatch(&call, 1, cols, static_cast<hipStream_t>(stream)));
 }
 
+extern "C" int iptq_softmax_i32_windowed(const int32_t *d_scores, const int32_t *d_bias,
+                                         int64_t bias_period_rows, const int32_t *d_mask,
+                                         int32_t n_windows, int32_t heads, void *d_out, int64_t rows,
+                                         int32_t cols, const iptq_softmax_params_t *p, void *stream)
+{
+    SoftmaxCall call;
+    int rc = softmax_call(d_scores, d_bias, bias_period_rows, d_out, rows, cols, p, &call, d_mask,
+                          n_windows, heads);
+    if (rc != IPTQ_OK || rows == 0) return rc;
+    return hip_rc(softmax_dispatch(&call, 1, cols, static_cast<hipStream_t>(stream)));
+}
+
 extern "C" int iptq_softmax_i32_batch(const iptq_softmax_problem_t *problems, int32_t n_problems,
                                       int32_t cols, void *stream)
 {
@@ -87,7 +106,7 @@ extern "C" int iptq_softmax_i32_batch(const iptq_softmax_problem_t *problems, in
     for (int32_t i = 0; i < n_problems; ++i) {           // every problem is checked before any launch
         const iptq_softmax_problem_t &q = problems[i];
         int rc = softmax_call(q.d_scores, q.d_bias, q.bias_period_rows, q.d_out, q.rows, cols,
-                              &q.params, &calls[n]);
+                              &q.params, &calls[n], q.d_mask, q.n_windows, q.heads);
         if (rc != IPTQ_OK) return rc;
         if (q.rows > 0) ++n;
     }
@@ -199,85 +218,17 @@ extern "C" int iptq_gelu_i8_layers(const int8_t *d_in, int64_t in_stride, int8_t
     return IPTQ_OK;
 }
 
-// ---- host-side test hooks (not part of the public header): the same source the kernels
-// run, compiled for the host, so that integer helpers can be checked exhaustively without
-// a GPU.
-extern "C" uint32_t iptq_debug_floor_pow2_div(int32_t m_bits, uint32_t sigma)
+extern "C" int iptq_softmax_kernel_family(int32_t cols, int32_t *family, int32_t *lanes,
+                                          int32_t *blocks)
 {
-    return floor_pow2_div(m_bits, sigma);
-}
-
-extern "C" int iptq_debug_softmax_plan(const iptq_softmax_params_t *p, int64_t rows, int32_t cols,
-                                       int32_t has_bias, int64_t bias_period_rows, int64_t *out12)
-{
-    SoftmaxDev dev;
-    int rc = plan_softmax(p, rows, cols, has_bias, bias_period_rows, &dev);
-    if (rc != IPTQ_OK || !out12) return rc;
-    out12[0] = dev.magic; out12[1] = dev.magic_sh; out12[2] = dev.d_clamp; out12[3] = dev.i0n;
-    out12[4] = dev.p_shift; out12[5] = dev.period_magic; out12[6] = dev.period_sh;
-    out12[7] = neg_qp_of(dev.d_clamp);
-    out12[8] = dev.mode16; out12[9] = dev.mg24; out12[10] = dev.t16; out12[11] = 0;
-    return rc;
-}
-
-// Layout the run-time-row-length kernels would use for a row length:
-// out12 = {slab ok, its lanes per row, its blocks per lane, the same again, wide ok, wide passes, wide slots,
-//          1 if the row length has a compiled kernel, 0, workgroup-per-row ok, its wavefronts,
-//          its slots}.
-extern "C" int iptq_debug_softmax_layout(int32_t cols, int32_t *out9)
-{
-    if (!out9) return IPTQ_ERR_NULL;
+    if (!family || !lanes || !blocks) return IPTQ_ERR_NULL;
     if (cols < 1 || cols > IPTQ_COLS_MAX) return IPTQ_ERR_SHAPE;
     int a = 0, b = 0;
-    out9[0] = rowsdyn_geometry(cols, &a, &b) ? 1 : 0;
-    out9[1] = a; out9[2] = b; out9[3] = b;
-    a = b = 0;
-    out9[4] = wide_geometry(cols, &a, &b) ? 1 : 0;
-    out9[5] = a; out9[6] = b;
-    a = b = 0;
-    out9[7] = softmax_rows_compiled(cols) ? 1 : 0;
-    out9[8] = 0;
-    a = b = 0;
-    out9[9] = wgrow_geometry(cols, &a, &b) ? 1 : 0;
-    out9[10] = a; out9[11] = b;
+    *lanes = 0; *blocks = 0;
+    if (softmax_rows_compiled(cols)) { *family = IPTQ_FAMILY_COMPILED; return IPTQ_OK; }
+    if (rowsdyn_geometry(cols, &a, &b)) { *family = IPTQ_FAMILY_SLAB; *lanes = a; *blocks = b; return IPTQ_OK; }
+    if (wide_geometry(cols, &a, &b)) { *family = IPTQ_FAMILY_WAVEFRONT_PER_ROW; *lanes = 64; *blocks = a; return IPTQ_OK; }
+    if (wgrow_geometry(cols, &a, &b)) { *family = IPTQ_FAMILY_WORKGROUP_PER_ROW; *lanes = 64 * a; *blocks = b; return IPTQ_OK; }
+    *family = IPTQ_FAMILY_THREE_PASS;
     return IPTQ_OK;
-}
-
-// Exponentials of an array of stabilised scores (row maximum 0) through both arithmetic
-// paths of the softmax kernels: out32 from the 32-bit lanes, out16 from the packed 16-bit
-// lanes (pairs (2i, 2i+1); 0xFFFFFFFF where the plan does not enable that path).  n even.
-__global__ void __launch_bounds__(256)
-debug_bit_exp_kernel(const int32_t *delta, uint32_t *out32, uint32_t *out16, int64_t n, SoftmaxDev P)
-{
-    const int64_t i = 2 * ((int64_t)blockIdx.x * 256 + threadIdx.x);
-    if (i + 1 >= n + 1 || i >= n) return;
-    const int32_t xa = delta[i], xb = delta[i + 1];
-    const int32_t lower = -P.d_clamp;
-    if (P.variant == 0) {
-        out32[i] = bit_exp_dev<0, true>(xa, lower, 0, P);
-        out32[i + 1] = bit_exp_dev<0, true>(xb, lower, 0, P);
-    } else {
-        out32[i] = bit_exp_dev<1, true>(xa, lower, 0, P);
-        out32[i + 1] = bit_exp_dev<1, true>(xb, lower, 0, P);
-    }
-    if (P.mode16 == 0) {
-        out16[i] = out16[i + 1] = 0xFFFFFFFFu;
-    } else {
-        const u16x2 e = P.variant == 0 ? bit_exp_pair<0, true>(xa, xb, 0, P) : bit_exp_pair<1, true>(xa, xb, 0, P);
-        out16[i] = e.x;
-        out16[i + 1] = e.y;
-    }
-}
-
-extern "C" int iptq_debug_bit_exp(const int32_t *d_delta, uint32_t *d_out32, uint32_t *d_out16,
-                                  int64_t n, const iptq_softmax_params_t *p, void *stream)
-{
-    if (!p || !d_delta || !d_out32 || !d_out16) return IPTQ_ERR_NULL;
-    if (n < 0 || (n & 1)) return IPTQ_ERR_SHAPE;
-    SoftmaxDev dev;
-    int rc = plan_softmax(p, 1, 1, 0, 0, &dev);
-    if (rc != IPTQ_OK || n == 0) return rc;
-    hipLaunchKernelGGL(debug_bit_exp_kernel, dim3((unsigned)((n / 2 + 255) / 256)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), d_delta, d_out32, d_out16, n, dev);
-    return hip_rc(hipGetLastError());
 }

@@ -18,26 +18,15 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Streaming accesses: every byte is touched once, so the loads and stores carry the
 // non-temporal hint and do not displace reusable lines (the bias table) from the caches.
-#ifndef IPTQ_NONTEMPORAL
-#define IPTQ_NONTEMPORAL 1
-#endif
 template <typename T>
 __device__ __forceinline__ T stream_load(const T *p)
 {
-#if IPTQ_NONTEMPORAL
     return __builtin_nontemporal_load(p);
-#else
-    return *p;
-#endif
 }
 template <typename T>
 __device__ __forceinline__ void stream_store(T v, T *p)
 {
-#if IPTQ_NONTEMPORAL
     __builtin_nontemporal_store(v, p);
-#else
-    *p = v;
-#endif
 }
 
 // 16-byte and 4-byte accesses at addresses that are only as aligned as their elements: a
@@ -49,11 +38,7 @@ typedef u32x4 __attribute__((aligned(1))) u32x4_a1;
 typedef uint32_t __attribute__((aligned(1))) u32_a1;
 __device__ __forceinline__ i32x4 stream_load_i32x4(const int32_t *p)
 {
-#if IPTQ_NONTEMPORAL
     return __builtin_nontemporal_load(reinterpret_cast<const i32x4_a4 *>(p));
-#else
-    return *reinterpret_cast<const i32x4_a4 *>(p);
-#endif
 }
 __device__ __forceinline__ i32x4 load_i32x4(const int32_t *p)
 {
@@ -61,19 +46,11 @@ __device__ __forceinline__ i32x4 load_i32x4(const int32_t *p)
 }
 __device__ __forceinline__ void stream_store_bytes16(u32x4 v, uint8_t *p)
 {
-#if IPTQ_NONTEMPORAL
     __builtin_nontemporal_store(v, reinterpret_cast<u32x4_a1 *>(p));
-#else
-    *reinterpret_cast<u32x4_a1 *>(p) = v;
-#endif
 }
 __device__ __forceinline__ void stream_store_bytes4(uint32_t v, uint8_t *p)
 {
-#if IPTQ_NONTEMPORAL
     __builtin_nontemporal_store(v, reinterpret_cast<u32_a1 *>(p));
-#else
-    *reinterpret_cast<u32_a1 *>(p) = v;
-#endif
 }
 
 IPTQ_HD uint32_t mulhi_u32(uint32_t a, uint32_t b)
@@ -158,6 +135,23 @@ IPTQ_DEV int32_t clamp_i32(int32_t v, int32_t lo, int32_t hi)
 IPTQ_DEV int32_t sat_add_i32(int32_t a, int32_t b)
 {
     return __builtin_elementwise_add_sat(a, b);
+}
+
+// score + t for one entry t of an additive table (relative-position bias, window mask): minus
+// infinity if either is, else the saturating sum.
+IPTQ_DEV int32_t add_table_entry(int32_t x, int32_t t)
+{
+    const int32_t s = sat_add_i32(x, t);
+    return min(x, t) == kI32Min ? kI32Min : s;
+}
+
+IPTQ_DEV i32x4 add_table_chunk(i32x4 v, i32x4 t)
+{
+    v.x = add_table_entry(v.x, t.x);
+    v.y = add_table_entry(v.y, t.y);
+    v.z = add_table_entry(v.z, t.z);
+    v.w = add_table_entry(v.w, t.w);
+    return v;
 }
 
 // ---- cross-lane exchange on the DPP path (no LDS traffic) -----------------------------

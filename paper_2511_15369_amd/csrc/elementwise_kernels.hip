@@ -76,9 +76,7 @@ IPTQ_DEV int32_t sbyte(uint32_t w, int i) { return (int32_t)(int8_t)(w >> (8 * i
 // offset (in place, or views cut at the same element); if not, its 16-byte loads are
 // unaligned ones.  in and out may be the same buffer.
 constexpr int kGeluBatchMax = 16;
-#ifndef IPTQ_GELU_TABLE_GRID_CAP
-#define IPTQ_GELU_TABLE_GRID_CAP (256 * 56)
-#endif
+constexpr int64_t kGeluTableGridCap = 256 * 56;
 struct GeluItem {
     const uint8_t *in;
     uint8_t *out;
@@ -250,9 +248,7 @@ gelu_i32_kernel(const int32_t *in, uint8_t *out, int64_t n, int32_t head, GeluDe
 // workgroup evaluates the polynomial once for every possible q with the exact formula, and an
 // element costs one multiply-shift, a clamp and a byte gather from LDS.
 constexpr int kGelu32TableMaxQ = 511;
-#ifndef IPTQ_GELU32_TABLE_GRID_CAP
-#define IPTQ_GELU32_TABLE_GRID_CAP (256 * 64)
-#endif
+constexpr int64_t kGelu32TableGridCap = 256 * 64;
 template <bool ALIGNED>
 __global__ void __launch_bounds__(256)
 gelu_i32_table_kernel(const int32_t *in, uint8_t *out, int64_t n, int32_t head, GeluDev P)
@@ -363,7 +359,7 @@ hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stre
             it.in = uin + head; it.out = uout + head; it.n = g.n - head; it.P = g.P;
             it.head = head;
             it.first_wg = total_wgs;
-            it.n_wgs = grid_for(it.n >> 4, 256, IPTQ_GELU_TABLE_GRID_CAP);
+            it.n_wgs = grid_for(it.n >> 4, 256, kGeluTableGridCap);
             total_wgs += it.n_wgs;
         }
     }
@@ -393,7 +389,7 @@ hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const Ge
     if (aligned) {
         const dim3 grid(grid_for(n >> 2, 256, 256 * 64)), block(256);
         if (table)
-            hipLaunchKernelGGL(gelu_i32_table_kernel<true>, dim3(grid_for(n >> 2, 256, IPTQ_GELU32_TABLE_GRID_CAP)),
+            hipLaunchKernelGGL(gelu_i32_table_kernel<true>, dim3(grid_for(n >> 2, 256, kGelu32TableGridCap)),
                                block, 0, stream, in, uout, n, head, P);
         else if (mode == 0) hipLaunchKernelGGL((gelu_i32_kernel<true, 0>), grid, block, 0, stream, in, uout, n, head, P);
         else if (mode == 1) hipLaunchKernelGGL((gelu_i32_kernel<true, 1>), grid, block, 0, stream, in, uout, n, head, P);

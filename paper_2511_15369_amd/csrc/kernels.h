@@ -12,6 +12,7 @@ namespace iptq {
 struct SoftmaxCall {
     const int32_t *scores;
     const int32_t *bias;
+    const int32_t *mask;  // per-window mask or nullptr (its shape is in P)
     uint8_t *out;
     int64_t rows;
     int out_bits;

@@ -68,7 +68,8 @@ int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int
     if (cols < 1 || cols > IPTQ_COLS_MAX) return IPTQ_ERR_SHAPE;
     if (has_bias && (bias_period_rows < 1 || bias_period_rows >= ((int64_t)1 << 31)))
         return IPTQ_ERR_SHAPE;
-    if (p->variant != IPTQ_SOFTMAX_SHIFT_LINEAR && p->variant != IPTQ_SOFTMAX_EFFICIENT_BITEXP)
+    if (p->variant != IPTQ_SOFTMAX_SHIFT_LINEAR && p->variant != IPTQ_SOFTMAX_EFFICIENT_BITEXP &&
+        p->variant != IPTQ_SOFTMAX_BITEXP_DEGREE2)
         return IPTQ_ERR_PARAM;
     if (p->algo != IPTQ_ALGO_AUTO && p->algo != IPTQ_ALGO_GENERIC &&
         p->algo != IPTQ_ALGO_DYNAMIC && p->algo != IPTQ_ALGO_WIDE && p->algo != IPTQ_ALGO_SLAB)
@@ -84,6 +85,8 @@ int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int
     if (rc != IPTQ_OK) return rc;
     const int64_t i0n = (int64_t)p->i0 << p->n_shift;
     if ((int64_t)cols * i0n > ((int64_t)1 << p->m_bits)) return IPTQ_ERR_RANGE;
+    // second-degree form: the square of Phi(-r) (|Phi| < 0.6875 i0) must stay below 2^31
+    if (p->variant == IPTQ_SOFTMAX_BITEXP_DEGREE2 && p->i0 >= (1 << 16)) return IPTQ_ERR_RANGE;
 
     // Deltas at or below -D shift every bit of (base << N) out: q >= bitlen(i0 << N).
     // n(d) grows by 1 or 2 per step of d (< i0), so the first such d has q == L exactly.
@@ -138,12 +141,18 @@ int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int
     out->post_xor = (p->out_is_signed == 1 && p->post.m == 1 && p->post.s == 0 && p->post.zp == -128 &&
                      p->post.qmin == -128 && p->post.qmax >= 0) ? 0x80808080u : 0u;
     out->variant = p->variant;
+    out->d2_magic = 0;
+    out->d2_sh = 0;
+    if (p->variant == IPTQ_SOFTMAX_BITEXP_DEGREE2 &&
+        !make_magic_u32((uint32_t)(2 * p->i0), 31, &out->d2_magic, &out->d2_sh))
+        return IPTQ_ERR_RANGE;
     // Packed 16-bit path: clamped delta, n and (i0 << N) must fit 16 bits, the per-row factor
     // shifted to the top byte must fit 24 bits, and a 24-bit divider multiplier must be exact.
     out->mode16 = 0;
     out->mg24 = 0;
     out->t16 = 0;
-    if (D <= 32767 && i0n < (1 << 15) && out->p_shift <= 24 && i0n >= ((int64_t)1 << p->out_bits)) {
+    if (p->variant != IPTQ_SOFTMAX_BITEXP_DEGREE2 && D <= 32767 && i0n < (1 << 15) &&
+        out->p_shift <= 24 && i0n >= ((int64_t)1 << p->out_bits)) {
         for (int t = 0; t <= 12; ++t) {
             const uint64_t two = (uint64_t)1 << (32 - t);
             const uint64_t mg = two / (uint64_t)p->i0 + 1;
@@ -166,6 +175,27 @@ int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int
         if (!make_magic_u32((uint32_t)bias_period_rows, 31, &out->period_magic, &out->period_sh))
             return IPTQ_ERR_RANGE;
     }
+    return IPTQ_OK;
+}
+
+int plan_softmax_mask(int64_t n_windows, int64_t heads, int32_t cols, SoftmaxDev *out)
+{
+    if (n_windows < 1 || heads < 1) return IPTQ_ERR_SHAPE;
+    const int64_t group = heads * (int64_t)cols;
+    if (heads >= ((int64_t)1 << 31) || n_windows >= ((int64_t)1 << 31) ||
+        group >= ((int64_t)1 << 31) || group * n_windows >= ((int64_t)1 << 31) ||
+        n_windows * (int64_t)cols * cols >= ((int64_t)1 << 31))
+        return IPTQ_ERR_SHAPE;
+    out->n_windows = (int32_t)n_windows;
+    out->group_rows = (int32_t)group;
+    out->mask_period_rows = (int32_t)(group * n_windows);
+    out->mperiod_magic = out->group_magic = 0;
+    out->mperiod_sh = out->group_sh = 0;
+    if (out->mask_period_rows >= 2 &&
+        !make_magic_u32((uint32_t)out->mask_period_rows, 31, &out->mperiod_magic, &out->mperiod_sh))
+        return IPTQ_ERR_RANGE;
+    if (group >= 2 && !make_magic_u32((uint32_t)group, 31, &out->group_magic, &out->group_sh))
+        return IPTQ_ERR_RANGE;
     return IPTQ_OK;
 }
 
@@ -247,9 +277,10 @@ extern "C" int iptq_softmax_prepare(double s_delta, int32_t cols, int32_t varian
     if (!out) return IPTQ_ERR_NULL;
     if (!(s_delta > 0.0) || isinf(s_delta)) return IPTQ_ERR_PARAM;
     if (cols < 1 || cols > IPTQ_COLS_MAX) return IPTQ_ERR_SHAPE;
-    if (variant != 0 && variant != 1) return IPTQ_ERR_PARAM;
+    if (variant != 0 && variant != 1 && variant != 2) return IPTQ_ERR_PARAM;
     const double inv = floor(1.0 / s_delta);
     if (inv < 16.0 || inv >= 16777216.0) return IPTQ_ERR_RANGE;
+    if (variant == 2 && inv >= 65536.0) return IPTQ_ERR_RANGE;
     const int32_t i0 = (int32_t)inv;
     int n = 15 - iptq::bitlen64((uint64_t)i0);
     if (n < 0) n = 0;

@@ -35,10 +35,22 @@ struct SoftmaxDev {
     // are at most 128 it is one exclusive-or.  0x80808080 then, else 0.
     uint32_t post_xor;
     int32_t variant;
+    // second-degree form (variant 2): floor(y^2 / (2 i0)) == mulhi(y^2, d2_magic) >> d2_sh for y^2 < 2^31
+    uint32_t d2_magic;
+    int32_t d2_sh;
     // bias addressing: row index modulo the period by multiply-high
     int32_t bias_period_rows;
     uint32_t period_magic;
     int32_t period_sh;
+    // per-window mask [n_windows, cols, cols] (0: none): rows are ordered [image, window, head,
+    // query]; row r lies in window (r mod mask_period_rows) div group_rows and is query
+    // (r mod group_rows) mod cols of it.  group_rows = heads * cols, mask_period_rows =
+    // n_windows * group_rows; both divisions by multiply-high.
+    int32_t n_windows;
+    int32_t group_rows;
+    int32_t mask_period_rows;
+    uint32_t mperiod_magic, group_magic;
+    int32_t mperiod_sh, group_sh;
 };
 
 // Constants of one GELU launch (Section 4.3).
@@ -71,6 +83,8 @@ int check_dyadic(const iptq_dyadic_t *p, int out_is_signed);
 int plan_requant(const iptq_dyadic_t *p, int out_is_signed, DyadicDev *out);
 int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int has_bias,
                  int64_t bias_period_rows, SoftmaxDev *out);
+// Adds the per-window mask's addressing constants to a plan made by plan_softmax.
+int plan_softmax_mask(int64_t n_windows, int64_t heads, int32_t cols, SoftmaxDev *out);
 int plan_gelu(const iptq_gelu_params_t *p, int is_i8_entry, GeluDev *out);
 
 }  // namespace iptq

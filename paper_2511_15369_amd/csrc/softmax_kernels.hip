@@ -20,8 +20,8 @@ namespace iptq {
 template <int VARIANT>
 __global__ void __launch_bounds__(256)
 softmax_generic_kernel(const int32_t *__restrict__ scores, const int32_t *__restrict__ bias,
-                       uint8_t *__restrict__ out, int64_t row_begin, int64_t row_end, int32_t cols,
-                       int32_t has_bias, int32_t has_pre, SoftmaxDev P)
+                       const int32_t *__restrict__ mask, uint8_t *__restrict__ out, int64_t row_begin,
+                       int64_t row_end, int32_t cols, int32_t has_bias, int32_t has_pre, SoftmaxDev P)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = row_begin + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -29,10 +29,25 @@ softmax_generic_kernel(const int32_t *__restrict__ scores, const int32_t *__rest
     const int32_t *srow = scores + row * cols;
     const int32_t *brow = nullptr;
     if (has_bias) brow = bias + (int64_t)row_mod_period((uint32_t)row, P) * cols;
+    const int32_t *mrow = nullptr;
+    if (mask) {
+        // rows are ordered [image, window, head, query]: window (r mod period) div (heads * cols),
+        // query (r mod (heads * cols)) mod cols; cols is a run-time value here, so the last one is
+        // a subtraction loop over the heads in front (once per row)
+        const uint32_t r = (uint32_t)row;
+        uint32_t rm = 0;
+        if (P.mask_period_rows >= 2)
+            rm = r - (mulhi_u32(r, P.mperiod_magic) >> P.mperiod_sh) * (uint32_t)P.mask_period_rows;
+        const uint32_t w = P.group_rows >= 2 ? mulhi_u32(rm, P.group_magic) >> P.group_sh : rm;
+        uint32_t q = rm - w * (uint32_t)P.group_rows;
+        while (q >= (uint32_t)cols) q -= (uint32_t)cols;
+        mrow = mask + ((int64_t)w * cols + q) * cols;
+    }
 
     auto fetch = [&](int c) -> int32_t {
         int32_t v = srow[c];
-        if (has_bias && v != kI32Min) v = sat_add_i32(v, brow[c]);
+        if (has_bias) v = add_table_entry(v, brow[c]);
+        if (mrow) v = add_table_entry(v, mrow[c]);
         if (has_pre && v != kI32Min) v = pre_requant_dev(v, P.pre_m, P.pre_s);
         return v;
     };
@@ -68,18 +83,21 @@ static int post_mode_of(const SoftmaxDev &P, int out_bits)
     return (P.qmax == 127 && out_bits == 8) ? PM_CLAMP127 : PM_GENERAL;
 }
 
-static hipError_t launch_generic(const int32_t *scores, const int32_t *bias, uint8_t *out,
-                                 int64_t row_begin, int64_t row_end, int32_t cols, bool has_bias,
-                                 bool has_pre, const SoftmaxDev &P, hipStream_t stream)
+static hipError_t launch_generic(const int32_t *scores, const int32_t *bias, const int32_t *mask,
+                                 uint8_t *out, int64_t row_begin, int64_t row_end, int32_t cols,
+                                 bool has_bias, bool has_pre, const SoftmaxDev &P, hipStream_t stream)
 {
     const int64_t n = row_end - row_begin;
     if (n <= 0) return hipSuccess;
     const dim3 grid((unsigned)((n + 3) / 4)), block(256);
     if (P.variant == 0)
-        hipLaunchKernelGGL(softmax_generic_kernel<0>, grid, block, 0, stream, scores, bias, out,
+        hipLaunchKernelGGL(softmax_generic_kernel<0>, grid, block, 0, stream, scores, bias, mask, out,
+                           row_begin, row_end, cols, (int32_t)has_bias, (int32_t)has_pre, P);
+    else if (P.variant == 1)
+        hipLaunchKernelGGL(softmax_generic_kernel<1>, grid, block, 0, stream, scores, bias, mask, out,
                            row_begin, row_end, cols, (int32_t)has_bias, (int32_t)has_pre, P);
     else
-        hipLaunchKernelGGL(softmax_generic_kernel<1>, grid, block, 0, stream, scores, bias, out,
+        hipLaunchKernelGGL(softmax_generic_kernel<2>, grid, block, 0, stream, scores, bias, mask, out,
                            row_begin, row_end, cols, (int32_t)has_bias, (int32_t)has_pre, P);
     return hipGetLastError();
 }
@@ -104,7 +122,10 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
     // 4.1 / 4.9 us against 5.5 / 5.3 / 4.9 us with the slab kernel; 392 to 3136 rows of 49 with a
     // table: 3.5-4.2 against 5.3-4.7 us; the slab kernels win from about 4000 rows on).
     constexpr int64_t kTinyRows = 3072;
-    if (n_calls == 1 && calls[0].algo == IPTQ_ALGO_AUTO && calls[0].rows <= kTinyRows) {
+    // (a per-window mask and the second-degree exponential exist in the compiled-row-length and
+    // the three-pass kernels only)
+    auto slab_only = [](const SoftmaxCall &c) { return c.mask != nullptr || c.P.variant == 2; };
+    if (n_calls == 1 && calls[0].algo == IPTQ_ALGO_AUTO && calls[0].rows <= kTinyRows && !slab_only(calls[0])) {
         int64_t served = 0;
         const hipError_t e = softmax_wide_launch(calls[0], cols, post_mode_of(calls[0].P, calls[0].out_bits),
                                                  &served, stream);
@@ -112,7 +133,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
         if (served == calls[0].rows) return hipSuccess;      // every row or none
     }
     int rpw = 0;                                      // rows per wavefront of the compiled row length
-    hipError_t (*launch)(const SoftmaxBatch &, unsigned, bool, int, int, hipStream_t) = nullptr;
+    hipError_t (*launch)(const SoftmaxBatch &, unsigned, bool, bool, int, int, hipStream_t) = nullptr;
 #define IPTQ_PICK_ROWS_SHAPE(COLS, K)                                                             \
     if (cols == COLS) { rpw = 64 / K; launch = launch_softmax_rows<COLS, K>; }
     IPTQ_ROWS_SHAPES(IPTQ_PICK_ROWS_SHAPE)
@@ -125,12 +146,12 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
     SoftmaxBatch B;
     B.n_items = 0;
     unsigned total_wgs = 0;
-    bool g_bias = false;
+    bool g_bias = false, g_mask = false;
     int g_pm = 0, g_mode = 0;
     hipError_t err = hipSuccess;
     auto flush = [&]() {
         if (B.n_items == 0 || err != hipSuccess) return;
-        err = launch(B, total_wgs, g_bias, g_mode, g_pm, stream);
+        err = launch(B, total_wgs, g_bias, g_mask, g_mode, g_pm, stream);
         B.n_items = 0;
         total_wgs = 0;
     };
@@ -150,26 +171,39 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
                                        (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 31) &&
                                                c.P.bias_period_rows >= rpw);
             const bool slab_algo = c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_SLAB;
-            if (rpw == 0 || !slab_algo || !aligned || !bias_ok) continue;
+            const bool has_mask = c.mask != nullptr;
+            // the mask is compiled in beside a bias, for window sizes whose slab has no more rows
+            // than a window has queries
+            const bool mask_ok = !has_mask || (has_bias && rows_mask_compiled(cols) && rpw <= cols &&
+                                               (reinterpret_cast<uintptr_t>(c.mask) & 3) == 0);
+            if (rpw == 0 || !slab_algo || !aligned || !bias_ok || !mask_ok) continue;
             const int64_t n_slabs = (c.rows + rpw - 1) / rpw;    // a partial last slab is served too
             if (n_slabs == 0) continue;
             const int pm = post_mode_of(c.P, c.out_bits);
             const int mode = c.P.mode16;
-            const bool compatible = B.n_items == 0 || (has_bias == g_bias && pm == g_pm &&
+            const bool compatible = B.n_items == 0 || (has_bias == g_bias && has_mask == g_mask && pm == g_pm &&
                                                        (mode == 0) == (g_mode == 0));
             if (!compatible || B.n_items == kBatchMax) flush();
-            if (B.n_items == 0) { g_bias = has_bias; g_pm = pm; g_mode = mode; }
+            if (B.n_items == 0) { g_bias = has_bias; g_mask = has_mask; g_pm = pm; g_mode = mode; }
             else if (mode > g_mode) g_mode = mode;       // 2 covers 1: items with t16 == 0 shift by 0
             SoftmaxItem &it = B.item[B.n_items++];
-            it.scores = c.scores; it.bias = c.bias; it.out = c.out;
+            it.scores = c.scores; it.bias = c.bias; it.mask = c.mask; it.out = c.out;
             it.n_slabs = n_slabs; it.first_wg = total_wgs; it.P = c.P;
             it.tail_rows = (int32_t)(c.rows % rpw);
             it.share_q = 0; it.share_magic = 0; it.share_sh = 0;
             int64_t n_wgs = (n_slabs + kRowsWpb - 1) / kRowsWpb;
             if (has_bias) {
-                int64_t a = c.P.bias_period_rows, b = rpw;
+                // rows after which the tables repeat: the bias period, or with a mask the least
+                // common multiple of both periods
+                int64_t period = c.P.bias_period_rows;
+                if (has_mask) {
+                    int64_t a = period, b = c.P.mask_period_rows;
+                    while (b != 0) { const int64_t t = a % b; a = b; b = t; }
+                    period = period / a * c.P.mask_period_rows;
+                }
+                int64_t a = period, b = rpw;
                 while (b != 0) { const int64_t t = a % b; a = b; b = t; }      // a = gcd
-                const int64_t q = c.P.bias_period_rows / a;
+                const int64_t q = period / a;
                 if (q >= 2 && q < 65536 && q * kRowsWpb <= n_slabs &&
                     make_magic_u32((uint32_t)q, 31, &it.share_magic, &it.share_sh)) {
                     it.share_q = (uint32_t)q;
@@ -184,19 +218,19 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             const SoftmaxCall &c = calls[base + i];
             const bool has_pre = !(c.P.pre_m == 1 && c.P.pre_s == 0);
             // a call no compiled row length served goes to the run-time-row-length kernels
-            if (done[i] == 0 && (c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_DYNAMIC || c.algo == IPTQ_ALGO_SLAB)) {
+            if (done[i] == 0 && !slab_only(c) && (c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_DYNAMIC || c.algo == IPTQ_ALGO_SLAB)) {
                 err = softmax_rowsdyn_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
                 if (err != hipSuccess) break;
             }
-            if (done[i] == 0 && (c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_WIDE)) {
+            if (done[i] == 0 && !slab_only(c) && (c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_WIDE)) {
                 err = softmax_wide_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
                 if (err != hipSuccess) break;
             }
-            if (done[i] == 0 && (c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_WIDE)) {
+            if (done[i] == 0 && !slab_only(c) && (c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_WIDE)) {
                 err = softmax_wgrow_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
                 if (err != hipSuccess) break;
             }
-            err = launch_generic(c.scores, c.bias, c.out, done[i], c.rows, cols, c.bias != nullptr,
+            err = launch_generic(c.scores, c.bias, c.mask, c.out, done[i], c.rows, cols, c.bias != nullptr,
                                  has_pre, c.P, stream);
         }
         if (err != hipSuccess) return err;

@@ -37,13 +37,11 @@ enum { PM_NONE = 0, PM_CLAMP127 = 1, PM_GENERAL = 2 };
 constexpr int kBatchMax = 16;
 // wavefronts per workgroup of the row kernel; they do not cooperate, so this only sets the
 // granularity at which the dispatcher hands out work and LDS
-#ifndef IPTQ_ROWS_WPB
-#define IPTQ_ROWS_WPB 4
-#endif
-constexpr int kRowsWpb = IPTQ_ROWS_WPB;
+constexpr int kRowsWpb = 4;
 struct SoftmaxItem {
     const int32_t *scores;
     const int32_t *bias;
+    const int32_t *mask;  // per-window mask [n_windows, cols, cols] or nullptr
     uint8_t *out;
     int64_t n_slabs;      // the last one may be partial
     uint32_t first_wg;
@@ -85,7 +83,9 @@ IPTQ_DEV uint32_t bit_exp_dev(int32_t x, int32_t lower, int32_t mx, const Softma
     const uint32_t q = mulhi_u32((uint32_t)n, P.magic) >> P.magic_sh;   // Eq. 8: n div i0
     const int32_t nr = (int32_t)__umul24(q, (uint32_t)P.i0) - n;        // -r in (-i0, 0]
     int32_t fr = nr >> 1;                              // Eq. 10: x / 2
-    if (VARIANT == 1) fr += (nr >> 3) + (nr >> 4);     // Eq. 13: (0.1011)b x
+    if (VARIANT >= 1) fr += (nr >> 3) + (nr >> 4);     // Eq. 13: (0.1011)b x
+    if (VARIANT == 2)                                  // Eq. 11 with D = 2: + floor(y^2 / (2 i0))
+        fr += (int32_t)(mulhi_u32((uint32_t)(fr * fr), P.d2_magic) >> P.d2_sh);
     const uint32_t base = ((uint32_t)fr << P.n_shift) + (uint32_t)P.i0n;  // Eq. 14, << N
     uint32_t e = base >> q;                            // Eq. 9 (q <= 31 by the clamp)
     if (EXPLICIT_MASK) e = (x == kI32Min) ? 0u : e;
@@ -129,6 +129,71 @@ IPTQ_DEV i32x4 bias_chunk_wrapping(const int32_t *bias, uint32_t o, uint32_t pe,
     r.z = sh == 0 ? A.z : (sh == 1 ? A.w : (sh == 2 ? first4.x : first4.y));
     r.w = sh == 0 ? A.w : (sh == 1 ? first4.x : (sh == 2 ? first4.y : first4.z));
     return r;
+}
+
+// Where the rows of a slab find their rows of the per-window mask.  Consecutive score rows are
+// consecutive mask rows until the query index wraps (every `cols` rows: the next head of the
+// same window starts over at the window's first mask row, the next window at its own), and a slab
+// has fewer rows than a window has queries, so a slab's mask entries are at most two contiguous
+// runs: slab elements [0, e1) take mask[off1 + e], the rest mask[off2 + (e - e1)].  If e1 is not
+// a multiple of four, one 16-byte chunk (slab elements o_s .. o_s+3) holds entries of both runs;
+// its four entries are put together once per wavefront (`straddle`), every other chunk is one load.
+struct MaskRuns {
+    uint32_t off1, off2;  // element offsets into the mask
+    uint32_t e1;          // a multiple of cols; at least the slab size when there is no second run
+    uint32_t o_s;         // first slab element of the chunk that straddles, or 0xffffffff
+    i32x4 straddle;
+};
+template <int COLS, int RPW>
+IPTQ_DEV MaskRuns mask_runs_of_slab(const int32_t *mask, uint32_t row0, const SoftmaxDev &P)
+{
+    uint32_t rm = 0;                                  // row modulo the mask period
+    if (P.mask_period_rows >= 2)
+        rm = row0 - (mulhi_u32(row0, P.mperiod_magic) >> P.mperiod_sh) * (uint32_t)P.mask_period_rows;
+    const uint32_t w1 = P.group_rows >= 2 ? mulhi_u32(rm, P.group_magic) >> P.group_sh : rm;   // window of row0
+    const uint32_t rin = rm - w1 * (uint32_t)P.group_rows;       // row inside [head, query] of that window
+    const uint32_t q0 = rin % (uint32_t)COLS;                    // compile-time divisor: a multiply-high
+    const uint32_t rd = (uint32_t)COLS - q0;                     // rows until the query index wraps
+    uint32_t w2 = w1;
+    if (rin + rd >= (uint32_t)P.group_rows) w2 = (w1 + 1 == (uint32_t)P.n_windows) ? 0u : w1 + 1;
+    MaskRuns R;
+    R.off1 = (w1 * (uint32_t)COLS + q0) * (uint32_t)COLS;
+    R.off2 = w2 * (uint32_t)(COLS * COLS);
+    R.e1 = rd * (uint32_t)COLS;
+    R.o_s = 0xffffffffu;
+    R.straddle = (i32x4){0, 0, 0, 0};
+    const uint32_t c1 = R.e1 & 3u;                    // entries of the straddling chunk in the first run
+    if (R.e1 < (uint32_t)(RPW * COLS) && c1 != 0) {
+        R.o_s = R.e1 - c1;
+        const i32x4 A = load_i32x4(mask + R.off1 + R.e1 - 4u);    // the first run's last four entries
+        const i32x4 F = load_i32x4(mask + R.off2);                // the second run's first four
+        R.straddle.x = c1 == 1 ? A.w : (c1 == 2 ? A.z : A.y);
+        R.straddle.y = c1 == 1 ? F.x : (c1 == 2 ? A.w : A.z);
+        R.straddle.z = c1 == 1 ? F.y : (c1 == 2 ? F.x : A.w);
+        R.straddle.w = c1 == 1 ? F.z : (c1 == 2 ? F.y : F.x);
+    }
+    return R;
+}
+
+// Mask entries of the chunk that starts at slab element o.  Branch-free: the load of the
+// straddling chunk is placed inside the first run and its result replaced.
+IPTQ_DEV i32x4 mask_chunk(const int32_t *mask, const MaskRuns &R, uint32_t o)
+{
+    const uint32_t off = o >= R.e1 ? R.off2 + (o - R.e1) : R.off1 + min(o, R.e1 - 4u);
+    i32x4 m = load_i32x4(mask + off);
+    const bool st = o == R.o_s;
+    m.x = st ? R.straddle.x : m.x;
+    m.y = st ? R.straddle.y : m.y;
+    m.z = st ? R.straddle.z : m.z;
+    m.w = st ? R.straddle.w : m.w;
+    return m;
+}
+
+// score + bias + mask entries with "minus infinity if any is": one test for the three
+IPTQ_DEV int32_t add_two_table_entries(int32_t x, int32_t b, int32_t m)
+{
+    const int32_t s = sat_add_i32(sat_add_i32(x, b), m);
+    return min(min(x, b), m) == kI32Min ? kI32Min : s;
 }
 
 // bytes 3 of (a, b, c, d) -> one dword (a in byte 0)
@@ -197,7 +262,7 @@ IPTQ_DEV u16x2 bit_exp_pair(int32_t xa, int32_t xb, int32_t mx, const SoftmaxDev
     const unsigned short i0 = (unsigned short)P.i0;
     const s16x2 nr = (s16x2)(q * (u16x2){i0, i0} - n);         // -r in (-i0, 0]
     s16x2 fr = nr >> 1;                                        // Eq. 10
-    if (VARIANT == 1) fr = fr + (nr >> 3) + (nr >> 4);         // Eq. 13
+    if (VARIANT >= 1) fr = fr + (nr >> 3) + (nr >> 4);         // Eq. 13 (the second-degree form never runs packed)
     const unsigned short sc = (unsigned short)(1u << P.n_shift), one = (unsigned short)P.i0n;
     const u16x2 base = (u16x2)fr * (u16x2){sc, sc} + (u16x2){one, one};   // Eq. 14, << N
     return base >> q;                                          // Eq. 9 (q <= 15)
@@ -277,7 +342,7 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
     }
 }
 
-template <int COLS, int K, int MODE, bool BIAS, int POSTMODE>
+template <int COLS, int K, int MODE, bool BIAS, int POSTMODE, bool MASK = false>
 __global__ void __launch_bounds__(64 * kRowsWpb)
 softmax_rows_kernel(SoftmaxBatch B)
 {
@@ -304,6 +369,7 @@ softmax_rows_kernel(SoftmaxBatch B)
     const int32_t *__restrict__ scores = I.scores;
     const int32_t *__restrict__ bias = I.bias;
     uint8_t *__restrict__ out = I.out;
+    static_assert(!MASK || RPW <= COLS, "a slab may cross one wrap of the query index at most");
     const uint32_t lw = blockIdx.x - I.first_wg;
     int64_t slab = (int64_t)lw * kRowsWpb + wv;
     if (BIAS && I.share_q != 0) {
@@ -336,6 +402,9 @@ softmax_rows_kernel(SoftmaxBatch B)
     if (BIAS) boff = row_mod_period((uint32_t)(slab * RPW), P) * (uint32_t)COLS;
     const uint32_t pe = (uint32_t)P.bias_period_rows * (uint32_t)COLS;
     const bool straddle = BIAS && (pe & 3u) != 0 && boff + (uint32_t)SLAB > pe;    // wavefront-uniform
+    // the per-window mask: at most two runs of entries (MaskRuns)
+    MaskRuns MR = {};
+    if (MASK) MR = mask_runs_of_slab<COLS, RPW>(I.mask, (uint32_t)(slab * RPW), P);
     auto copy_in = [&](auto tag, auto straddle_tag) {
         constexpr bool PARTIAL = decltype(tag)::value;
         constexpr bool STRADDLE = decltype(straddle_tag)::value;
@@ -362,14 +431,24 @@ softmax_rows_kernel(SoftmaxBatch B)
                 if (4 * idx + 1 < valid_el) v.y = s[1];
                 if (4 * idx + 2 < valid_el) v.z = s[2];
             }
+            i32x4 bv = {0, 0, 0, 0};
             if (BIAS) {
                 uint32_t o = boff + 4u * (uint32_t)li;
                 if (o >= pe) o -= pe;
-                const i32x4 bv = STRADDLE ? bias_chunk_wrapping(bias, o, pe, first4) : load_i32x4(bias + o);
-                v.x = v.x == kI32Min ? v.x : sat_add_i32(v.x, bv.x);
-                v.y = v.y == kI32Min ? v.y : sat_add_i32(v.y, bv.y);
-                v.z = v.z == kI32Min ? v.z : sat_add_i32(v.z, bv.z);
-                v.w = v.w == kI32Min ? v.w : sat_add_i32(v.w, bv.w);
+                bv = STRADDLE ? bias_chunk_wrapping(bias, o, pe, first4) : load_i32x4(bias + o);
+            }
+            if (MASK) {
+                const i32x4 mv = mask_chunk(I.mask, MR, 4u * (uint32_t)li);
+                if (BIAS) {
+                    v.x = add_two_table_entries(v.x, bv.x, mv.x);
+                    v.y = add_two_table_entries(v.y, bv.y, mv.y);
+                    v.z = add_two_table_entries(v.z, bv.z, mv.z);
+                    v.w = add_two_table_entries(v.w, bv.w, mv.w);
+                } else {
+                    v = add_table_chunk(v, mv);
+                }
+            } else if (BIAS) {
+                v = add_table_chunk(v, bv);
             }
             lds4[li] = v;
         }
@@ -442,7 +521,8 @@ softmax_rows_kernel(SoftmaxBatch B)
     uint32_t w[SLOTS];                                // four output bytes per block
 
     if (P.variant == 0) softmax_slab_math<K, SLOTS, MODE, 0, POSTMODE>(x, w, mx, lower, any_low, lut, P);
-    else softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE>(x, w, mx, lower, any_low, lut, P);
+    else if (MODE != 0 || P.variant == 1) softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE>(x, w, mx, lower, any_low, lut, P);
+    else softmax_slab_math<K, SLOTS, MODE, 2, POSTMODE>(x, w, mx, lower, any_low, lut, P);   // 32-bit lanes only
     if (POSTMODE == PM_NONE && P.post_xor != 0) {     // signed output around the zero-point -128
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) w[s] ^= P.post_xor;
@@ -496,10 +576,11 @@ softmax_rows_kernel(SoftmaxBatch B)
 }
 
 // Launch helper, defined once per row length in softmax_rows_<cols>.hip so that the
-// instantiations compile in parallel.  mode: 0 / 1 / 2 as above; all items share has_bias.
+// instantiations compile in parallel.  mode: 0 / 1 / 2 as above; all items share has_bias and
+// has_mask.
 template <int COLS, int K>
-hipError_t launch_softmax_rows(const SoftmaxBatch &B, unsigned total_wgs, bool has_bias, int mode,
-                               int post_mode, hipStream_t stream);
+hipError_t launch_softmax_rows(const SoftmaxBatch &B, unsigned total_wgs, bool has_bias, bool has_mask,
+                               int mode, int post_mode, hipStream_t stream);
 
 // The compiled row lengths with their lanes per row: ViT / DeiT at 224^2 (197; 198 with a
 // distillation token), Swin 7x7 and 12x12 windows (49, 144), ViT-L/14 (257), 384^2 / 16 (577).
@@ -511,25 +592,28 @@ hipError_t launch_softmax_rows(const SoftmaxBatch &B, unsigned total_wgs, bool h
 // kRowsAltMaxElements elements use these instead (softmax_rows_<cols>_k<K>.hip).
 #define IPTQ_ROWS_SHAPES_ALT(X) X(197, 8) X(198, 8)
 constexpr int64_t kRowsAltMaxElements = 90 * 1000 * 1000;
+// The per-window mask is compiled in for the window sizes of shifted-window attention only
+// (7 x 7 and 12 x 12 tokens), with the bias table beside it.
+constexpr bool rows_mask_compiled(int cols) { return cols == 49 || cols == 144; }
 #define IPTQ_DECLARE_ROWS_LAUNCHER(COLS, K)                                                       \
     template <>                                                                                   \
-    hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &, unsigned, bool, int, int, hipStream_t);
+    hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &, unsigned, bool, bool, int, int, hipStream_t);
 IPTQ_ROWS_SHAPES(IPTQ_DECLARE_ROWS_LAUNCHER)
 IPTQ_ROWS_SHAPES_ALT(IPTQ_DECLARE_ROWS_LAUNCHER)
 
-#define IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM)                                                 \
-    hipLaunchKernelGGL((softmax_rows_kernel<COLS, K, MODE, BIAS, PM>), grid, block, 0, stream, B)
+#define IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM, MASK)                                           \
+    hipLaunchKernelGGL((softmax_rows_kernel<COLS, K, MODE, BIAS, PM, MASK>), grid, block, 0, stream, B)
 
-template <int COLS, int K, bool BIAS>
+template <int COLS, int K, bool BIAS, bool MASK>
 static hipError_t launch_rows_b(const SoftmaxBatch &B, unsigned total_wgs, int mode, int post_mode,
                                 hipStream_t stream)
 {
     const dim3 grid(total_wgs), block(64 * kRowsWpb);
 #define IPTQ_ROWS_LAUNCH_PM(MODE)                                                                 \
     switch (post_mode) {                                                                          \
-    case PM_NONE: IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM_NONE); break;                          \
-    case PM_CLAMP127: IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM_CLAMP127); break;                  \
-    default: IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM_GENERAL); break;                            \
+    case PM_NONE: IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM_NONE, MASK); break;                    \
+    case PM_CLAMP127: IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM_CLAMP127, MASK); break;            \
+    default: IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM_GENERAL, MASK); break;                      \
     }
     if (mode == 0) { IPTQ_ROWS_LAUNCH_PM(0) }
     else if (mode == 1) { IPTQ_ROWS_LAUNCH_PM(1) }
@@ -538,14 +622,23 @@ static hipError_t launch_rows_b(const SoftmaxBatch &B, unsigned total_wgs, int m
     return hipGetLastError();
 }
 
+template <int COLS, int K>
+static hipError_t launch_rows_masked(const SoftmaxBatch &B, unsigned total_wgs, int mode, int post_mode,
+                                     hipStream_t stream)
+{
+    if constexpr (rows_mask_compiled(COLS)) return launch_rows_b<COLS, K, true, true>(B, total_wgs, mode, post_mode, stream);
+    else return hipErrorInvalidValue;                 // the dispatcher never asks for it
+}
+
 #define IPTQ_DEFINE_ROWS_LAUNCHER(COLS, K)                                                        \
     template <>                                                                                   \
     hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &B, unsigned total_wgs,            \
-                                            bool has_bias, int mode, int post_mode,               \
-                                            hipStream_t stream)                                   \
+                                            bool has_bias, bool has_mask, int mode,               \
+                                            int post_mode, hipStream_t stream)                    \
     {                                                                                             \
-        return has_bias ? launch_rows_b<COLS, K, true>(B, total_wgs, mode, post_mode, stream)     \
-                        : launch_rows_b<COLS, K, false>(B, total_wgs, mode, post_mode, stream);   \
+        if (has_mask) return launch_rows_masked<COLS, K>(B, total_wgs, mode, post_mode, stream);  \
+        return has_bias ? launch_rows_b<COLS, K, true, false>(B, total_wgs, mode, post_mode, stream)     \
+                        : launch_rows_b<COLS, K, false, false>(B, total_wgs, mode, post_mode, stream);   \
     }
 
 }  // namespace iptq

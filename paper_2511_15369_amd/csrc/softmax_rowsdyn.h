@@ -77,10 +77,7 @@ softmax_rowsdyn_kernel(DynArgs A)
     // the first LDS write and none sits behind a branch: in the last two passes the lanes
     // beyond the slab's last chunk load that chunk again and write it to its place again.
     auto add_bias = [](i32x4 v, const i32x4 bv) {
-        v.x = v.x == kI32Min ? v.x : sat_add_i32(v.x, bv.x);
-        v.y = v.y == kI32Min ? v.y : sat_add_i32(v.y, bv.y);
-        v.z = v.z == kI32Min ? v.z : sat_add_i32(v.z, bv.z);
-        v.w = v.w == kI32Min ? v.w : sat_add_i32(v.w, bv.w);
+        v = add_table_chunk(v, bv);
         return v;
     };
     auto copy_in = [&](auto bias_tag, auto straddle_tag) {

@@ -94,10 +94,7 @@ softmax_wide_kernel(WideArgs A)
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
             const i32x4 bv = bsrc[block_of(s, nb)];
-            v[s].x = v[s].x == kI32Min ? kI32Min : sat_add_i32(v[s].x, bv.x);
-            v[s].y = v[s].y == kI32Min ? kI32Min : sat_add_i32(v[s].y, bv.y);
-            v[s].z = v[s].z == kI32Min ? kI32Min : sat_add_i32(v[s].z, bv.z);
-            v[s].w = v[s].w == kI32Min ? kI32Min : sat_add_i32(v[s].w, bv.w);
+            v[s] = add_table_chunk(v[s], bv);
         }
     }
 

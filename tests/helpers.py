@@ -76,3 +76,16 @@ def gpu_requant(x: np.ndarray, d: ref.Dyadic, out_is_signed: int) -> np.ndarray:
     ip.requant(d_in, d_out, x.size, out_is_signed, lib_dyadic(d))
     torch.cuda.synchronize()
     return d_out.cpu().numpy()
+
+
+def gpu_softmax_windowed(scores: np.ndarray, p: ref.SoftmaxParams, bias, period, mask, heads, algo=0) -> np.ndarray:
+    import torch
+    rows, cols = scores.shape
+    d_in = torch.from_numpy(np.ascontiguousarray(scores)).cuda()
+    d_bias = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias)).cuda()
+    d_mask = None if mask is None else torch.from_numpy(np.ascontiguousarray(mask)).cuda()
+    n_w = 0 if mask is None else mask.shape[0]
+    d_out = torch.full((rows, cols), 0x5A, dtype=torch.int8 if p.out_is_signed else torch.uint8, device="cuda")
+    ip.softmax_i32_windowed(d_in, d_bias, period, d_mask, n_w, heads, d_out, rows, cols, lib_softmax(p, algo))
+    torch.cuda.synchronize()
+    return d_out.cpu().numpy()

@@ -1,0 +1,152 @@
+"""GPU parity of the softmax with a per-window mask beside the relative-position bias
+(shifted-window attention; iptq_softmax_i32_windowed) against the oracle, bit for bit, through
+the C ABI: small ragged cases on every route, every discontinuity of the mask rows inside a
+slab, and the Swin-B stages at full size in the launch configuration the benchmark times."""
+import numpy as np
+import pytest
+
+import workloads
+from oracle import prepare, ref
+from tests.helpers import gpu_softmax, gpu_softmax_windowed, lib_softmax
+
+pytestmark = pytest.mark.gpu
+INT32_MIN = -(2 ** 31)
+
+
+def _case(rng, images, side, heads, win=7, shift=3, drop=0, spread=600.0):
+    t = win * win
+    mask = workloads.shifted_window_mask(side, side, win, shift)
+    n_w = mask.shape[0]
+    rows = images * n_w * heads * t - drop
+    scores = np.rint(rng.standard_normal((rows, t)) * spread).astype(np.int32)
+    bias = np.rint(rng.standard_normal((heads * t, t)) * 8).astype(np.int32)
+    return scores, bias, mask
+
+
+@pytest.mark.parametrize("heads,side", [(4, 14), (3, 14), (8, 21), (1, 14), (6, 28)])
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_windowed_small(heads, side, variant):
+    """Row counts that leave a partial slab; 3 and 6 heads give a bias table whose size is not a
+    multiple of four (its own straddling chunk beside the mask's)."""
+    rng = np.random.default_rng(heads * 1000 + side * 10 + variant)
+    scores, bias, mask = _case(rng, 3, side, heads, drop=int(rng.integers(0, 40)))
+    scores[rng.random(scores.shape) < 0.01] = INT32_MIN
+    for signed in (0, 1):
+        p = prepare.softmax_prepare(2.0 ** -6.5, 49, variant, signed)
+        want = ref.softmax_i32_windowed(scores, p, bias, heads * 49, mask, heads)
+        for algo in (0, 1):
+            got = gpu_softmax_windowed(scores, p, bias, heads * 49, mask, heads, algo=algo)
+            assert np.array_equal(got, want), (heads, side, variant, signed, algo)
+    # masked keys get probability 0 and every row keeps mass
+    blocked = np.tile(mask[:, None] == INT32_MIN, (3, heads, 1, 1)).reshape(-1, 49)[:scores.shape[0]]
+    assert not want[blocked].any()
+
+
+def test_windowed_equals_a_combined_table_on_the_gpu():
+    rng = np.random.default_rng(5)
+    heads, side = 4, 14
+    scores, bias, mask = _case(rng, 5, side, heads)
+    n_w = mask.shape[0]
+    table = np.empty((n_w, heads, 49, 49), np.int64)
+    table[:] = bias.reshape(1, heads, 49, 49).astype(np.int64) + mask[:, None].astype(np.int64)
+    table = np.clip(table, INT32_MIN, 2 ** 31 - 1)
+    table[np.broadcast_to(mask[:, None] == INT32_MIN, table.shape)] = INT32_MIN
+    table = table.astype(np.int32).reshape(n_w * heads * 49, 49)
+    p = prepare.softmax_prepare(2.0 ** -7.5, 49, 1)
+    got = gpu_softmax_windowed(scores, p, bias, heads * 49, mask, heads)
+    assert np.array_equal(got, gpu_softmax(scores, p, table, n_w * heads * 49))
+    assert np.array_equal(got, ref.softmax_i32_windowed(scores, p, bias, heads * 49, mask, heads))
+
+
+def test_windowed_general_values_full_mask_rows_and_no_bias():
+    """Finite mask values are ordinary addends; a query whose every key is masked yields the
+    zero-point although its scores are positive; a mask without a bias is served too."""
+    rng = np.random.default_rng(6)
+    heads, t, n_w, images = 2, 49, 5, 4
+    rows = images * n_w * heads * t
+    scores = np.abs(np.rint(rng.standard_normal((rows, t)) * 300)).astype(np.int32) + 1
+    bias = np.rint(rng.standard_normal((heads * t, t)) * 8).astype(np.int32)
+    bias[rng.random(bias.shape) < 0.02] = INT32_MIN
+    mask = np.where(rng.random((n_w, t, t)) < 0.3, INT32_MIN, 0).astype(np.int32)
+    mask[1] = np.rint(rng.standard_normal((t, t)) * 200).astype(np.int32)       # additive, finite
+    mask[2, 5, :] = INT32_MIN                                                    # fully masked query
+    mask[4, :, :] = INT32_MIN + 1                                                # huge but finite
+    p = prepare.softmax_prepare(2.0 ** -6, t, 1)
+    p.post = ref.Dyadic(1, 0, 3, 0, 255)
+    want = ref.softmax_i32_windowed(scores, p, bias, heads * t, mask, heads)
+    r = ((0 * n_w + 2) * heads + 1) * t + 5
+    assert want[r].tolist() == [3] * t
+    for algo in (0, 1):
+        assert np.array_equal(gpu_softmax_windowed(scores, p, bias, heads * t, mask, heads, algo=algo), want)
+    want = ref.softmax_i32_windowed(scores, p, None, 0, mask, heads)
+    assert np.array_equal(gpu_softmax_windowed(scores, p, None, 0, mask, heads), want)
+    # bias only through the same entry point
+    want = ref.softmax_i32_windowed(scores, p, bias, heads * t, None, heads)
+    assert np.array_equal(gpu_softmax_windowed(scores, p, bias, heads * t, None, heads), want)
+
+
+def test_windowed_12x12_windows():
+    rng = np.random.default_rng(8)
+    heads = 3
+    scores, bias, mask = _case(rng, 2, 48, heads, win=12, shift=6, drop=7, spread=300.0)
+    assert mask.shape == (16, 144, 144)
+    p = prepare.softmax_prepare(2.0 ** -6, 144, 1)
+    want = ref.softmax_i32_windowed(scores, p, bias, heads * 144, mask, heads)
+    assert np.array_equal(gpu_softmax_windowed(scores, p, bias, heads * 144, mask, heads), want)
+
+
+def test_windowed_other_row_length_takes_the_three_pass_kernel():
+    rng = np.random.default_rng(9)
+    t, heads, n_w = 16, 2, 3
+    rows = 4 * n_w * heads * t
+    scores = np.rint(rng.standard_normal((rows, t)) * 300).astype(np.int32)
+    bias = np.rint(rng.standard_normal((heads * t, t)) * 8).astype(np.int32)
+    mask = np.where(rng.random((n_w, t, t)) < 0.3, INT32_MIN, 0).astype(np.int32)
+    p = prepare.softmax_prepare(2.0 ** -6, t, 0)
+    want = ref.softmax_i32_windowed(scores, p, bias, heads * t, mask, heads)
+    assert np.array_equal(gpu_softmax_windowed(scores, p, bias, heads * t, mask, heads), want)
+
+
+@pytest.mark.parametrize("stage", [0, 1, 2])
+def test_windowed_swin_b_full_size(stage):
+    """Swin-B at batch 64, shifted-window blocks of stages 1-3 (64, 16 and 4 windows per image),
+    the benchmark's score generator, one launch."""
+    import torch
+    import paper_2511_15369_amd as ip
+    case = workloads.softmax_case("swin_b", stage)
+    heads = workloads.CONFIGS["swin_b"]["heads"][stage]
+    side = workloads.SWIN_B_MAP_SIDE[stage]
+    mask = workloads.shifted_window_mask(side, side)
+    assert mask.shape[0] == workloads.CONFIGS["swin_b"]["windows"][stage]
+    rows, cols = case.scores.shape
+    for variant in (1, 0):
+        p = prepare.softmax_prepare(case.s_delta, cols, variant)
+        want = ref.softmax_i32_windowed(case.scores, p, case.bias, case.bias_period_rows, mask, heads)
+        got = gpu_softmax_windowed(case.scores, p, case.bias, case.bias_period_rows, mask, heads)
+        assert np.array_equal(got, want), (stage, variant)
+    # the batched entry point carries the mask too
+    d_s = torch.from_numpy(case.scores).cuda()
+    d_b = torch.from_numpy(case.bias).cuda()
+    d_m = torch.from_numpy(mask).cuda()
+    d_o = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
+    prob = ip.softmax_problem(d_s, d_b, case.bias_period_rows, d_o, rows, cols, lib_softmax(p), d_m, mask.shape[0], heads)
+    ip.softmax_i32_batch([prob], 1, cols)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_o.cpu().numpy(), want)
+
+
+def test_windowed_argument_checks():
+    import ctypes
+    import torch
+    import paper_2511_15369_amd as ip
+    t = 49
+    d_s = torch.zeros((98, t), dtype=torch.int32, device="cuda")
+    d_o = torch.zeros((98, t), dtype=torch.uint8, device="cuda")
+    d_m = torch.zeros((2, t, t), dtype=torch.int32, device="cuda")
+    p = lib_softmax(prepare.softmax_prepare(2.0 ** -6, t, 1))
+    fn = ip.load().iptq_softmax_i32_windowed
+    for n_w, heads in ((0, 1), (1, 0), (-1, 1), (2 ** 30, 4)):
+        rc = fn(d_s.data_ptr(), None, 0, d_m.data_ptr(), n_w, heads, d_o.data_ptr(), 98, t, ctypes.byref(p), None)
+        assert rc == -2, (n_w, heads)
+    torch.cuda.synchronize()
+    assert not d_o.any()                                     # nothing was launched

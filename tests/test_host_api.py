@@ -18,9 +18,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     lib = ip.load()
-    header = open(os.path.join(ROOT, "include", "iptq.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    names = set(re.findall(r"\b(iptq_[a-z0-9_]+)\s*\(", header))
+    names = set()
+    for h in sorted(os.listdir(os.path.join(ROOT, "include"))):      # iptq.h and the test hooks' header
+        header = open(os.path.join(ROOT, "include", h)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        names |= set(re.findall(r"\b(iptq_[a-z0-9_]+)\s*\(", header))
+    assert any(n.startswith("iptq_debug_") for n in names)
     assert {"iptq_softmax_i32", "iptq_gelu_i8", "iptq_gelu_i32", "iptq_requant",
             "iptq_softmax_i32_layers", "iptq_gelu_i8_layers", "iptq_make_dyadic",
             "iptq_softmax_prepare", "iptq_gelu_prepare", "iptq_strerror",
@@ -160,7 +163,7 @@ def test_softmax_argument_errors_without_a_gpu():
     assert _softmax_rc(good, cols=0) == -2
     assert _softmax_rc(good, cols=65537) == -2
     assert _softmax_rc(good, rows=0, bias=ctypes.c_void_p(16), period=0) == -2
-    for field, val in (("variant", 2), ("i0", 15), ("i0", 2 ** 24), ("n_shift", -1), ("n_shift", 21),
+    for field, val in (("variant", 3), ("variant", -1), ("i0", 15), ("i0", 2 ** 24), ("n_shift", -1), ("n_shift", 21),
                        ("out_bits", 1), ("out_bits", 9), ("m_bits", 32), ("m_bits", 6), ("pre_m", 0),
                        ("pre_m", 32768), ("pre_s", 63), ("out_is_signed", 2), ("algo", 7)):
         bad = lib_softmax(ref.SoftmaxParams())
@@ -170,6 +173,17 @@ def test_softmax_argument_errors_without_a_gpu():
     assert _softmax_rc(bad) == -3                             # i0 << N >= 2^24
     bad = lib_softmax(ref.SoftmaxParams(post=ref.Dyadic(1, 0, 0, -1, 255)))
     assert _softmax_rc(bad) == -3                             # qmin outside uint8
+    bad = lib_softmax(ref.SoftmaxParams(variant=2, i0=2 ** 16, n_shift=0))
+    assert _softmax_rc(bad) == -4                             # the second-degree form needs i0 < 2^16
+    assert _softmax_rc(lib_softmax(ref.SoftmaxParams(variant=2, i0=2 ** 16 - 1, n_shift=0))) == 0
+    wnd = ip.load().iptq_softmax_i32_windowed
+    m = ctypes.c_void_p(64)
+    assert wnd(None, None, 0, m, 4, 2, None, 0, 49, ctypes.byref(good), None) == 0      # no rows: a no-op
+    assert wnd(None, None, 0, m, 0, 2, None, 0, 49, ctypes.byref(good), None) == -2
+    assert wnd(None, None, 0, m, 4, 0, None, 0, 49, ctypes.byref(good), None) == -2
+    assert wnd(None, None, 0, m, 2 ** 20, 2 ** 10, None, 0, 49, ctypes.byref(good), None) == -2
+    assert wnd(None, None, 0, ctypes.c_void_p(66), 4, 2, None, 0, 49, ctypes.byref(good), None) == -6
+    assert wnd(None, None, 0, None, 0, 0, None, 0, 49, ctypes.byref(good), None) == 0    # no mask: plain call
     bad = lib_softmax(ref.SoftmaxParams(i0=2 ** 14, n_shift=9, m_bits=24))
     assert _softmax_rc(bad, cols=4) == -4                     # cols * (i0 << N) > 2^M
     assert _softmax_rc(good, rows=3, scores=ctypes.c_void_p(6), out=ctypes.c_void_p(64)) == -6

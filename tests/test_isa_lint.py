@@ -16,7 +16,7 @@ FORBIDDEN = re.compile(r"^\s+(v_[a-z0-9_]*_(f16|f32|f64|bf16)\b|v_cvt_(?!pk_[iu]
                        r"v_exp|v_log|v_pk_[a-z]+_f|v_dot[0-9]*_f|v_fma|v_mad_f|v_mac_f|v_div_)", re.M)
 
 
-SOURCES = sorted(f for f in os.listdir(CSRC) if f.endswith(".hip") and f != "api.hip")
+SOURCES = sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
 def _compile(src, out_dir):

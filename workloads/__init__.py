@@ -21,4 +21,6 @@ from .generators import (  # noqa: F401
     softmax_qk,
     swin_bias,
     detection_key_mask,
+    shifted_window_mask,
+    SWIN_B_MAP_SIDE,
 )

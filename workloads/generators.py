@@ -111,6 +111,33 @@ def detection_key_mask(map_h: int = 200, map_w: int = 334, win: int = 7) -> np.n
     return pad.reshape(nh, win, nw, win).transpose(0, 2, 1, 3).reshape(nh * nw, win * win)
 
 
+def shifted_window_mask(map_h: int, map_w: int, win: int = 7, shift: int = 3) -> np.ndarray:
+    """int32 [windows, win*win, win*win]: the additive attention mask of a shifted-window block.
+
+    After the token map is rolled by `shift`, a window at the map's border holds tokens from up
+    to four regions that were not neighbours before the roll; a query may only attend to keys of
+    its own region.  Entry 0 where query and key share a region, INT32_MIN elsewhere.  Windows
+    are numbered row-major over the map; a map of exactly one window has nothing to mask.
+    """
+    assert map_h % win == 0 and map_w % win == 0 and 0 < shift < win
+    region = np.zeros((map_h, map_w), dtype=np.int64)
+    edges_h = (0, map_h - win, map_h - shift, map_h)
+    edges_w = (0, map_w - win, map_w - shift, map_w)
+    rid = 0
+    for a in range(3):
+        for b in range(3):
+            region[edges_h[a]:edges_h[a + 1], edges_w[b]:edges_w[b + 1]] = rid
+            rid += 1
+    nh, nw = map_h // win, map_w // win
+    per_window = region.reshape(nh, win, nw, win).transpose(0, 2, 1, 3).reshape(nh * nw, win * win)
+    same = per_window[:, :, None] == per_window[:, None, :]
+    return np.where(same, 0, -(2 ** 31)).astype(np.int32)
+
+
+# token map side of each Swin-B stage at 224 x 224 (stage 4 is a single window: no mask)
+SWIN_B_MAP_SIDE = (56, 28, 14, 7)
+
+
 _GELU_BLOCK_TOKENS = 2048
 
 
