@@ -15,6 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libiptq.so")
+TIMELINE_LIB = os.path.join(HERE, "libiptq_timeline.so")
 # the slowest translation units first (the pool takes them in this order)
 SOURCES = ["softmax_wgrow_w4_hi.hip", "softmax_wgrow_w8_hi.hip", "softmax_wgrow_w16.hip", "softmax_wgrow_w4_lo.hip", "softmax_wgrow_w8_lo.hip",
            "softmax_wide_p14_16.hip", "softmax_wide_p11_13.hip", "softmax_wide_p7_10.hip", "softmax_wide_p1_6.hip", "softmax_rowsdyn_k16_long.hip",
@@ -30,24 +31,33 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextr
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def _compile(src: str, extra) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = ["hipcc", "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj] + FLAGS + list(extra)
-    subprocess.check_call(cmd)
-    return obj
+def build(extra_flags=(), verbose: bool = False, lib: str = LIB, obj_dir: str = OBJ) -> str:
+    os.makedirs(obj_dir, exist_ok=True)
 
+    def one(src):
+        obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+        subprocess.check_call(["hipcc", "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj] + FLAGS
+                              + list(extra_flags))
+        return obj
 
-def build(extra_flags=(), verbose: bool = False) -> str:
-    os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=8) as ex:
-        objs = list(ex.map(lambda s: _compile(s, extra_flags), SOURCES))
-    tmp = LIB + ".tmp%d" % os.getpid()
+        objs = list(ex.map(one, SOURCES))
+    tmp = lib + ".tmp%d" % os.getpid()
     subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs)
-    os.replace(tmp, LIB)
+    os.replace(tmp, lib)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", lib)
+    return lib
+
+
+def build_timeline(verbose: bool = False) -> str:
+    """The instrumented library for `python -m paper_2511_15369_amd.timeline` (per-wavefront phase
+    timestamps in the compiled-row-length softmax kernels); never loaded by the product path."""
+    return build(["-DIPTQ_TIMELINE"], verbose, TIMELINE_LIB, OBJ + "_timeline")
 
 
 if __name__ == "__main__":
-    build(sys.argv[1:], verbose=True)
+    if sys.argv[1:] == ["timeline"]:
+        build_timeline(verbose=True)
+    else:
+        build(sys.argv[1:], verbose=True)

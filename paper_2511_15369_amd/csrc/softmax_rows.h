@@ -179,7 +179,10 @@ IPTQ_DEV MaskRuns mask_runs_of_slab(const int32_t *mask, uint32_t row0, const So
 // straddling chunk is placed inside the first run and its result replaced.
 IPTQ_DEV i32x4 mask_chunk(const int32_t *mask, const MaskRuns &R, uint32_t o)
 {
-    const uint32_t off = o >= R.e1 ? R.off2 + (o - R.e1) : R.off1 + min(o, R.e1 - 4u);
+    // (a bit select, not `?:`: the compiler turned the conditional into a lane-divergent branch,
+    // which cut the copy loop into blocks and left one pass of loads in flight at a time)
+    const uint32_t in2 = 0u - (uint32_t)(o >= R.e1);
+    const uint32_t off = ((R.off2 + (o - R.e1)) & in2) | ((R.off1 + min(o, R.e1 - 4u)) & ~in2);
     i32x4 m = load_i32x4(mask + off);
     const bool st = o == R.o_s;
     m.x = st ? R.straddle.x : m.x;
@@ -342,10 +345,24 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
     }
 }
 
-template <int COLS, int K, int MODE, bool BIAS, int POSTMODE, bool MASK = false>
-__global__ void __launch_bounds__(64 * kRowsWpb)
-softmax_rows_kernel(SoftmaxBatch B)
+// Instrumented build (`python -m paper_2511_15369_amd.build timeline` -> libiptq_timeline.so; read
+// with `python -m paper_2511_15369_amd.timeline`): each wavefront records the device-wide clock
+// at entry, when its slab has landed in LDS, after the arithmetic, after its last store is
+// issued and after that store is acknowledged, for the first kTimelineSlabs slabs of a launch.
+#ifdef IPTQ_TIMELINE
+constexpr int kTimelineSlabs = 65536;
+static __device__ uint64_t g_timeline[5 * kTimelineSlabs];
+#define IPTQ_TL(k, t) do { if (lane == 0 && slab < kTimelineSlabs) g_timeline[5 * slab + (k)] = (t); } while (0)
+#else
+#define IPTQ_TL(k, t) do { } while (0)
+#endif
+
+template <int COLS, int K, int MODE, bool BIAS, int POSTMODE, bool MASK>
+IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
 {
+#ifdef IPTQ_TIMELINE
+    const uint64_t t_entry = wall_clock64();
+#endif
     constexpr int RPW = 64 / K;                       // rows per wavefront
     constexpr int SLAB = RPW * COLS;                  // elements per slab
     static_assert(RPW % 4 == 0, "slab must start on a 16-byte boundary of the int32 input");
@@ -378,6 +395,9 @@ softmax_rows_kernel(SoftmaxBatch B)
     }
     if (slab >= I.n_slabs) return;                    // no workgroup barrier below
 
+#ifdef IPTQ_TIMELINE
+    IPTQ_TL(0, t_entry);
+#endif
     uint8_t *lds = lds_all[wv];
     uint8_t *lut = lut_all[wv];
     if (POSTMODE == PM_GENERAL) {                     // ordered before its use by the fences below
@@ -411,8 +431,30 @@ softmax_rows_kernel(SoftmaxBatch B)
         i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
         i32x4 first4 = {0, 0, 0, 0};
         if (BIAS && STRADDLE) first4 = load_i32x4(bias);
+        constexpr int NPASS = (IN_CHUNKS + 63) / 64;
+        // With the mask there are three loads per chunk, more than the registers hold in flight
+        // at once: the scores (the loads that go to HBM) are all issued first, the two tables'
+        // entries (cache hits) follow pass by pass.
+        i32x4 sv[MASK ? NPASS : 1];
+        if (MASK) {
 #pragma unroll
-        for (int i = 0; i < (IN_CHUNKS + 63) / 64; ++i) {
+            for (int i = 0; i < NPASS; ++i) {
+                const int idx = i * 64 + lane;
+                const bool full_pass = (i + 1) * 64 <= IN_CHUNKS;
+                const int li = (PARTIAL || full_pass) ? idx : min(idx, IN_CHUNKS - 1);
+                if (!PARTIAL || 4 * idx + 3 < valid_el) {
+                    sv[i] = stream_load_i32x4(src + 4 * li);
+                } else {
+                    const int32_t *s = src + 4 * idx;
+                    sv[i] = (i32x4){0, 0, 0, 0};
+                    if (4 * idx < valid_el) sv[i].x = s[0];
+                    if (4 * idx + 1 < valid_el) sv[i].y = s[1];
+                    if (4 * idx + 2 < valid_el) sv[i].z = s[2];
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NPASS; ++i) {
             const int idx = i * 64 + lane;
             const bool full_pass = (i + 1) * 64 <= IN_CHUNKS;
             if (PARTIAL && !(full_pass || idx < IN_CHUNKS)) continue;
@@ -422,7 +464,9 @@ softmax_rows_kernel(SoftmaxBatch B)
             // memory round trip per wavefront.
             const int li = (PARTIAL || full_pass) ? idx : min(idx, IN_CHUNKS - 1);
             i32x4 v;
-            if (!PARTIAL || 4 * idx + 3 < valid_el) {
+            if (MASK) {
+                v = sv[i];
+            } else if (!PARTIAL || 4 * idx + 3 < valid_el) {
                 v = stream_load_i32x4(src + 4 * li);
             } else {
                 const int32_t *s = src + 4 * idx;
@@ -458,6 +502,7 @@ softmax_rows_kernel(SoftmaxBatch B)
     else if (straddle) copy_in(std::false_type{}, std::true_type{});
     else copy_in(std::false_type{}, std::false_type{});
 
+    IPTQ_TL(1, wall_clock64());
     // ---- this lane's blocks; elements outside the row become "minus infinity"
     int32_t x[SLOTS][4];
 #pragma unroll
@@ -528,6 +573,7 @@ softmax_rows_kernel(SoftmaxBatch B)
         for (int s = 0; s < SLOTS; ++s) w[s] ^= P.post_xor;
     }
 
+    IPTQ_TL(2, wall_clock64());
     // ---- assemble the slab's bytes in LDS
     uint32_t *lds32 = reinterpret_cast<uint32_t *>(lds);
 #pragma unroll
@@ -573,6 +619,28 @@ softmax_rows_kernel(SoftmaxBatch B)
     };
     if (partial) copy_out(std::true_type{});
     else copy_out(std::false_type{});
+#ifdef IPTQ_TIMELINE
+    IPTQ_TL(3, wall_clock64());
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    IPTQ_TL(4, wall_clock64());
+#endif
+}
+
+template <int COLS, int K, int MODE, bool BIAS, int POSTMODE>
+__global__ void __launch_bounds__(64 * kRowsWpb)
+softmax_rows_kernel(SoftmaxBatch B)
+{
+    softmax_rows_body<COLS, K, MODE, BIAS, POSTMODE, false>(B);
+}
+
+// The same with the per-window mask beside the bias: three loads per chunk.  Compiled for five
+// wavefronts per SIMD instead of the six the LDS staging would allow, so that a wavefront has
+// the registers to keep all its loads in flight at once.
+template <int COLS, int K, int MODE, int POSTMODE>
+__global__ void __launch_bounds__(64 * kRowsWpb) __attribute__((amdgpu_waves_per_eu(4, 5)))
+softmax_rows_masked_kernel(SoftmaxBatch B)
+{
+    softmax_rows_body<COLS, K, MODE, true, POSTMODE, true>(B);
 }
 
 // Launch helper, defined once per row length in softmax_rows_<cols>.hip so that the
@@ -602,7 +670,12 @@ IPTQ_ROWS_SHAPES(IPTQ_DECLARE_ROWS_LAUNCHER)
 IPTQ_ROWS_SHAPES_ALT(IPTQ_DECLARE_ROWS_LAUNCHER)
 
 #define IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM, MASK)                                           \
-    hipLaunchKernelGGL((softmax_rows_kernel<COLS, K, MODE, BIAS, PM, MASK>), grid, block, 0, stream, B)
+    do {                                                                                          \
+        if constexpr (MASK)                                                                       \
+            hipLaunchKernelGGL((softmax_rows_masked_kernel<COLS, K, MODE, PM>), grid, block, 0, stream, B);   \
+        else                                                                                      \
+            hipLaunchKernelGGL((softmax_rows_kernel<COLS, K, MODE, BIAS, PM>), grid, block, 0, stream, B);    \
+    } while (0)
 
 template <int COLS, int K, bool BIAS, bool MASK>
 static hipError_t launch_rows_b(const SoftmaxBatch &B, unsigned total_wgs, int mode, int post_mode,
@@ -630,7 +703,20 @@ static hipError_t launch_rows_masked(const SoftmaxBatch &B, unsigned total_wgs, 
     else return hipErrorInvalidValue;                 // the dispatcher never asks for it
 }
 
+#ifdef IPTQ_TIMELINE
+// copies the timestamps of the last launches of this translation unit's kernels to the host
+#define IPTQ_DEFINE_TIMELINE_READER(COLS, K)                                                      \
+    extern "C" int iptq_debug_timeline_##COLS##_##K(uint64_t *host, int n)                        \
+    {                                                                                             \
+        if (!host || n < 0 || n > 5 * kTimelineSlabs) return IPTQ_ERR_SHAPE;                      \
+        return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timeline), (size_t)n * 8) == hipSuccess ? IPTQ_OK : IPTQ_ERR_HIP;  \
+    }
+#else
+#define IPTQ_DEFINE_TIMELINE_READER(COLS, K)
+#endif
+
 #define IPTQ_DEFINE_ROWS_LAUNCHER(COLS, K)                                                        \
+    IPTQ_DEFINE_TIMELINE_READER(COLS, K)                                                          \
     template <>                                                                                   \
     hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &B, unsigned total_wgs,            \
                                             bool has_bias, bool has_mask, int mode,               \
