@@ -22,7 +22,9 @@ uint32_t iptq_debug_floor_pow2_div(int32_t m_bits, uint32_t sigma);
 
 /* The constants the host derives for one softmax launch.  out12 (12 values, may be NULL):
  * {divider multiplier, its shift, clamp D, i0 << N, p shift, period multiplier, its shift,
- *  n(D), packed-16-bit mode, its 24-bit multiplier, its pre-shift, 0}. */
+ *  n(D), packed-16-bit mode, its 24-bit multiplier, its pre-shift,
+ *  the clamp of the raw score difference when the requantization in front is folded into Eq. 6
+ *  (0: it is not)}. */
 int iptq_debug_softmax_plan(const iptq_softmax_params_t *p, int64_t rows, int32_t cols,
                             int32_t has_bias, int64_t bias_period_rows, int64_t *out12);
 

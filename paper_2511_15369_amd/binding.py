@@ -83,6 +83,10 @@ def load():
     if not os.path.exists(_LIB_PATH):
         raise ImportError("libiptq.so is not built: run `python -m paper_2511_15369_amd.build` "
                           "(there is no fallback path)")
+    # torch first: it brings its own copy of the HIP runtime, and the library must bind to that
+    # one (the device buffers and streams come from it).  Loaded before torch, libiptq.so would
+    # pull in the system's copy and every launch would go to a second runtime that has no device.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
     lib.iptq_version.restype = ctypes.c_int

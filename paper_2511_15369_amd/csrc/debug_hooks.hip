@@ -26,7 +26,8 @@ extern "C" int iptq_debug_softmax_plan(const iptq_softmax_params_t *p, int64_t r
     out12[0] = dev.magic; out12[1] = dev.magic_sh; out12[2] = dev.d_clamp; out12[3] = dev.i0n;
     out12[4] = dev.p_shift; out12[5] = dev.period_magic; out12[6] = dev.period_sh;
     out12[7] = neg_qp_of(dev.d_clamp);
-    out12[8] = dev.mode16; out12[9] = dev.mg24; out12[10] = dev.t16; out12[11] = 0;
+    out12[8] = dev.mode16; out12[9] = dev.mg24; out12[10] = dev.t16;
+    out12[11] = dev.pre_rowconst ? (int64_t)dev.pre_dmax : 0;
     return rc;
 }
 

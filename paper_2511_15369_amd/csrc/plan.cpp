@@ -168,6 +168,16 @@ int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int
             break;
         }
     }
+    out->pre_rowconst = 0;
+    out->pre_dmax = 0;
+    if (out->pre_mode == 1 && out->mode16 != 0 && p->pre_s <= 31) {
+        const int64_t two_s = (int64_t)1 << p->pre_s;
+        const int64_t dmax = (D * two_s + p->pre_m - 1) / p->pre_m;
+        if (dmax < ((int64_t)1 << 24) && dmax * p->pre_m + two_s <= ((int64_t)1 << 32)) {
+            out->pre_rowconst = 1;
+            out->pre_dmax = (uint32_t)dmax;
+        }
+    }
     out->bias_period_rows = has_bias ? (int32_t)bias_period_rows : 1;
     out->period_magic = 0;
     out->period_sh = 0;

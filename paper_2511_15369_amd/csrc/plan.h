@@ -29,6 +29,12 @@ struct SoftmaxDev {
     int32_t pre_mul;
     int32_t pre_sh2;
     int64_t pre_rnd;
+    // pre-requantization folded into Eq. 6 (pre_rowconst 1; pre_s in [16, 31], packed path only):
+    // with d = max - x >= 0 on the raw scores, r(x) - r(max) == -((d * pre_m + c) >> pre_s), c a
+    // constant of the row (2^s - 1 - ((max * pre_m + 2^(s-1)) mod 2^s)); d is clamped at pre_dmax =
+    // ceil(D 2^s / pre_m), beyond which the exponential is 0 anyway, so the product fits 32 bits.
+    int32_t pre_rowconst;
+    uint32_t pre_dmax;
     int32_t post_m, post_s, post_zp, qmin, qmax;
     // The post step "minus 128, no clip inside [-128, 0]" (signed int8 probabilities around a
     // zero-point of -128, the operand form of a signed 8-bit matrix instruction): on bytes that

@@ -133,7 +133,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
         if (served == calls[0].rows) return hipSuccess;      // every row or none
     }
     int rpw = 0;                                      // rows per wavefront of the compiled row length
-    hipError_t (*launch)(const SoftmaxBatch &, unsigned, bool, bool, int, int, hipStream_t) = nullptr;
+    hipError_t (*launch)(const SoftmaxBatch &, unsigned, bool, bool, bool, int, int, hipStream_t) = nullptr;
 #define IPTQ_PICK_ROWS_SHAPE(COLS, K)                                                             \
     if (cols == COLS) { rpw = 64 / K; launch = launch_softmax_rows<COLS, K>; }
     IPTQ_ROWS_SHAPES(IPTQ_PICK_ROWS_SHAPE)
@@ -146,12 +146,13 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
     SoftmaxBatch B;
     B.n_items = 0;
     unsigned total_wgs = 0;
-    bool g_bias = false, g_mask = false;
+    bool g_bias = false, g_mask = false, g_fold = false;
     int g_pm = 0, g_mode = 0;
     hipError_t err = hipSuccess;
     auto flush = [&]() {
         if (B.n_items == 0 || err != hipSuccess) return;
-        err = launch(B, total_wgs, g_bias, g_mask, g_mode, g_pm, stream);
+        err = launch(B, total_wgs, g_bias, g_mask, g_fold, g_mode, g_pm, stream);
+        g_fold = false;
         B.n_items = 0;
         total_wgs = 0;
     };
@@ -186,6 +187,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             if (!compatible || B.n_items == kBatchMax) flush();
             if (B.n_items == 0) { g_bias = has_bias; g_mask = has_mask; g_pm = pm; g_mode = mode; }
             else if (mode > g_mode) g_mode = mode;       // 2 covers 1: items with t16 == 0 shift by 0
+            if (c.P.pre_rowconst != 0) g_fold = true;
             SoftmaxItem &it = B.item[B.n_items++];
             it.scores = c.scores; it.bias = c.bias; it.mask = c.mask; it.out = c.out;
             it.n_slabs = n_slabs; it.first_wg = total_wgs; it.P = c.P;

@@ -247,12 +247,10 @@ IPTQ_DEV uint32_t mulhi_u24(uint32_t a, uint32_t b)   // both below 2^24: bits 4
 // Two exponentials at once in packed 16-bit lanes.  Preconditions (checked on the host,
 // SoftmaxDev::p16): D <= 32767, n_max <= 65535 >> t16, i0 << N < 2^15 (so q <= 15 at the
 // clamp), divider multiplier mg24 < 2^24 exact for (n << t16).
+// From the two stabilised scores of Eq. 6 (any value in [-32768, 0]) on.
 template <int VARIANT, bool SHIFTED>
-IPTQ_DEV u16x2 bit_exp_pair(int32_t xa, int32_t xb, int32_t mx, const SoftmaxDev &P)
+IPTQ_DEV u16x2 bit_exp_pair_of_deltas(s16x2 dl, const SoftmaxDev &P)
 {
-    const int32_t da = __builtin_elementwise_sub_sat(xa, mx);
-    const int32_t db = __builtin_elementwise_sub_sat(xb, mx);
-    s16x2 dl = __builtin_amdgcn_cvt_pk_i16(da, db);            // saturates to 16 bits
     const short nd = (short)(-P.d_clamp);
     dl = __builtin_elementwise_max(dl, (s16x2){nd, nd});       // Eq. 6 with the clamp at -D
     const s16x2 s1 = dl >> 1, s4 = dl >> 4;
@@ -271,6 +269,27 @@ IPTQ_DEV u16x2 bit_exp_pair(int32_t xa, int32_t xb, int32_t mx, const SoftmaxDev
     return base >> q;                                          // Eq. 9 (q <= 15)
 }
 
+template <int VARIANT, bool SHIFTED>
+IPTQ_DEV u16x2 bit_exp_pair(int32_t xa, int32_t xb, int32_t mx, const SoftmaxDev &P)
+{
+    const int32_t da = __builtin_elementwise_sub_sat(xa, mx);
+    const int32_t db = __builtin_elementwise_sub_sat(xb, mx);
+    return bit_exp_pair_of_deltas<VARIANT, SHIFTED>(__builtin_amdgcn_cvt_pk_i16(da, db), P);   // saturating pack
+}
+
+// The same with the requantization of the scores folded in (SoftmaxDev::pre_rowconst): xa, xb
+// and mx are raw scores, c_row the row's constant.
+template <int VARIANT, bool SHIFTED>
+IPTQ_DEV u16x2 bit_exp_pair_requant(int32_t xa, int32_t xb, int32_t mx, uint32_t c_row, const SoftmaxDev &P)
+{
+    const uint32_t da = min((uint32_t)mx - (uint32_t)xa, P.pre_dmax);      // mx >= x: exact as unsigned
+    const uint32_t db = min((uint32_t)mx - (uint32_t)xb, P.pre_dmax);
+    const uint32_t ea = (__umul24(da, (uint32_t)P.pre_m) + c_row) >> P.pre_s;   // r(mx) - r(x), at most D + 1
+    const uint32_t eb = (__umul24(db, (uint32_t)P.pre_m) + c_row) >> P.pre_s;
+    const s16x2 e = {(short)ea, (short)eb};
+    return bit_exp_pair_of_deltas<VARIANT, SHIFTED>((s16x2){0, 0} - e, P);
+}
+
 // The arithmetic of one wavefront's slab once its rows sit in registers: exponentials, row
 // sum, reciprocal, probabilities -> four output bytes per block in w[].
 // Row sum over the K lanes that share a row (the default reducer of softmax_slab_math).
@@ -280,10 +299,12 @@ struct LaneGroupSum {
 };
 
 // SUM: how the per-lane partial sums of a row are combined.
-template <int K, int SLOTS, int MODE, int VARIANT, int POSTMODE, class SUM = LaneGroupSum<K>>
+// PRE: x and mx are raw scores and the requantization in front is folded into the exponentials
+// (packed path only; the caller has checked SoftmaxDev::pre_rowconst and that no row is "low").
+template <int K, int SLOTS, int MODE, int VARIANT, int POSTMODE, class SUM = LaneGroupSum<K>, bool PRE = false>
 IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], int32_t mx,
                                 int32_t lower, bool any_low, const uint8_t *lut, const SoftmaxDev &P,
-                                const SUM &row_sum = SUM())
+                                const SUM &row_sum = SUM(), uint32_t c_row = 0)
 {
     if (MODE != 0 && !any_low) {
         // ---- packed 16-bit path
@@ -293,7 +314,8 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
         for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const u16x2 qe = bit_exp_pair<VARIANT, MODE == 2>(x[s][2 * h], x[s][2 * h + 1], mx, P);
+                const u16x2 qe = PRE ? bit_exp_pair_requant<VARIANT, MODE == 2>(x[s][2 * h], x[s][2 * h + 1], mx, c_row, P)
+                                     : bit_exp_pair<VARIANT, MODE == 2>(x[s][2 * h], x[s][2 * h + 1], mx, P);
                 sum = __builtin_amdgcn_udot2(qe, (u16x2){1, 1}, sum, false);
                 e2[s][h] = __builtin_bit_cast(uint32_t, qe);
             }
@@ -357,7 +379,7 @@ static __device__ uint64_t g_timeline[5 * kTimelineSlabs];
 #define IPTQ_TL(k, t) do { } while (0)
 #endif
 
-template <int COLS, int K, int MODE, bool BIAS, int POSTMODE, bool MASK>
+template <int COLS, int K, int MODE, bool BIAS, int POSTMODE, bool MASK, bool PRE = false>
 IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
 {
 #ifdef IPTQ_TIMELINE
@@ -525,6 +547,33 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     }
     wave_lds_fence();                                 // the slab area is reused for the output
 
+    uint32_t w[SLOTS];                                // four output bytes per block
+    bool done = false;                                // wavefront-uniform
+    // ---- fused requantization of the scores, folded into Eq. 6 (PRE instantiations, parameters
+    // with SoftmaxDev::pre_rowconst): the maximum is taken over the raw scores (the
+    // requantization is monotone), each delta costs one 24-bit multiply-add and a shift.  Rows
+    // whose raw maximum lies within pre_dmax of INT32_MIN (the clamp could not tell their masked
+    // entries from live ones) send the wavefront down the ordinary route below.
+    if (PRE && P.pre_rowconst != 0) {
+        int32_t mr = kI32Min;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mr = max(mr, x[s][e]);
+        mr = group_max_i32<K>(mr);
+        const bool low = ((uint32_t)mr ^ 0x80000000u) < P.pre_dmax;        // mr - INT32_MIN as unsigned
+        if (__builtin_amdgcn_ballot_w64(low) == 0) {
+            const int64_t t = (int64_t)mr * (int64_t)P.pre_m + ((int64_t)1 << (P.pre_s - 1));
+            const uint32_t smask = (1u << P.pre_s) - 1u;                   // pre_s <= 31 here
+            const uint32_t c_row = smask - ((uint32_t)t & smask);
+            if (P.variant == 0)
+                softmax_slab_math<K, SLOTS, MODE, 0, POSTMODE, LaneGroupSum<K>, true>(x, w, mr, 0, false, lut, P, LaneGroupSum<K>(), c_row);
+            else
+                softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE, LaneGroupSum<K>, true>(x, w, mr, 0, false, lut, P, LaneGroupSum<K>(), c_row);
+            done = true;
+        }
+    }
+    if (!done) {
     // ---- fused requantization of the scores (after the bias, before the maximum).  Done on
     // the registers, not in the copy loop, so that every load of the slab stays in flight;
     // computed for every element and selected, so that it compiles without branches.
@@ -563,11 +612,11 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     const bool low_row = mx < kI32Min + D;
     const int32_t lower = low_row ? kI32Min : mx - D;
     const bool any_low = __builtin_amdgcn_ballot_w64(low_row) != 0;
-    uint32_t w[SLOTS];                                // four output bytes per block
 
     if (P.variant == 0) softmax_slab_math<K, SLOTS, MODE, 0, POSTMODE>(x, w, mx, lower, any_low, lut, P);
     else if (MODE != 0 || P.variant == 1) softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE>(x, w, mx, lower, any_low, lut, P);
     else softmax_slab_math<K, SLOTS, MODE, 2, POSTMODE>(x, w, mx, lower, any_low, lut, P);   // 32-bit lanes only
+    }
     if (POSTMODE == PM_NONE && P.post_xor != 0) {     // signed output around the zero-point -128
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) w[s] ^= P.post_xor;
@@ -643,12 +692,21 @@ softmax_rows_masked_kernel(SoftmaxBatch B)
     softmax_rows_body<COLS, K, MODE, true, POSTMODE, true>(B);
 }
 
+// The same with the requantization of the scores folded into Eq. 6 where the parameters allow it
+// (no tables, packed arithmetic, identity or clip post step).
+template <int COLS, int K, int MODE, int POSTMODE>
+__global__ void __launch_bounds__(64 * kRowsWpb)
+softmax_rows_requant_kernel(SoftmaxBatch B)
+{
+    softmax_rows_body<COLS, K, MODE, false, POSTMODE, false, true>(B);
+}
+
 // Launch helper, defined once per row length in softmax_rows_<cols>.hip so that the
 // instantiations compile in parallel.  mode: 0 / 1 / 2 as above; all items share has_bias and
-// has_mask.
+// has_mask; fold_pre: some item has SoftmaxDev::pre_rowconst.
 template <int COLS, int K>
 hipError_t launch_softmax_rows(const SoftmaxBatch &B, unsigned total_wgs, bool has_bias, bool has_mask,
-                               int mode, int post_mode, hipStream_t stream);
+                               bool fold_pre, int mode, int post_mode, hipStream_t stream);
 
 // The compiled row lengths with their lanes per row: ViT / DeiT at 224^2 (197; 198 with a
 // distillation token), Swin 7x7 and 12x12 windows (49, 144), ViT-L/14 (257), 384^2 / 16 (577).
@@ -665,7 +723,7 @@ constexpr int64_t kRowsAltMaxElements = 90 * 1000 * 1000;
 constexpr bool rows_mask_compiled(int cols) { return cols == 49 || cols == 144; }
 #define IPTQ_DECLARE_ROWS_LAUNCHER(COLS, K)                                                       \
     template <>                                                                                   \
-    hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &, unsigned, bool, bool, int, int, hipStream_t);
+    hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &, unsigned, bool, bool, bool, int, int, hipStream_t);
 IPTQ_ROWS_SHAPES(IPTQ_DECLARE_ROWS_LAUNCHER)
 IPTQ_ROWS_SHAPES_ALT(IPTQ_DECLARE_ROWS_LAUNCHER)
 
@@ -696,6 +754,22 @@ static hipError_t launch_rows_b(const SoftmaxBatch &B, unsigned total_wgs, int m
 }
 
 template <int COLS, int K>
+static hipError_t launch_rows_requant(const SoftmaxBatch &B, unsigned total_wgs, int mode, int post_mode,
+                                      hipStream_t stream)
+{
+    const dim3 grid(total_wgs), block(64 * kRowsWpb);
+    if (mode == 1 && post_mode == PM_NONE)
+        hipLaunchKernelGGL((softmax_rows_requant_kernel<COLS, K, 1, PM_NONE>), grid, block, 0, stream, B);
+    else if (mode == 1)
+        hipLaunchKernelGGL((softmax_rows_requant_kernel<COLS, K, 1, PM_CLAMP127>), grid, block, 0, stream, B);
+    else if (post_mode == PM_NONE)
+        hipLaunchKernelGGL((softmax_rows_requant_kernel<COLS, K, 2, PM_NONE>), grid, block, 0, stream, B);
+    else
+        hipLaunchKernelGGL((softmax_rows_requant_kernel<COLS, K, 2, PM_CLAMP127>), grid, block, 0, stream, B);
+    return hipGetLastError();
+}
+
+template <int COLS, int K>
 static hipError_t launch_rows_masked(const SoftmaxBatch &B, unsigned total_wgs, int mode, int post_mode,
                                      hipStream_t stream)
 {
@@ -719,10 +793,12 @@ static hipError_t launch_rows_masked(const SoftmaxBatch &B, unsigned total_wgs, 
     IPTQ_DEFINE_TIMELINE_READER(COLS, K)                                                          \
     template <>                                                                                   \
     hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &B, unsigned total_wgs,            \
-                                            bool has_bias, bool has_mask, int mode,               \
-                                            int post_mode, hipStream_t stream)                    \
+                                            bool has_bias, bool has_mask, bool fold_pre,          \
+                                            int mode, int post_mode, hipStream_t stream)          \
     {                                                                                             \
         if (has_mask) return launch_rows_masked<COLS, K>(B, total_wgs, mode, post_mode, stream);  \
+        if (fold_pre && !has_bias && mode != 0 && post_mode != PM_GENERAL)                        \
+            return launch_rows_requant<COLS, K>(B, total_wgs, mode, post_mode, stream);           \
         return has_bias ? launch_rows_b<COLS, K, true, false>(B, total_wgs, mode, post_mode, stream)     \
                         : launch_rows_b<COLS, K, false, false>(B, total_wgs, mode, post_mode, stream);   \
     }

@@ -700,3 +700,26 @@ def test_elementwise_views_at_every_offset():
         ip.gelu_i8(d_io[5:5 + n], d_io[5:5 + n], n, lib_gelu(gp8))
         torch.cuda.synchronize()
         assert np.array_equal(d_io.cpu().numpy()[5:5 + n], want_g8), ("in place", n)
+
+
+def test_library_loaded_before_torch_binds_to_torchs_hip_runtime():
+    """A process that loads the library first and imports torch afterwards must still launch on
+    the runtime torch's buffers belong to (torch ships its own copy of the HIP runtime)."""
+    import os
+    import subprocess
+    import sys
+    code = (
+        "import paper_2511_15369_amd as ip\n"
+        "ip.load()\n"
+        "import torch\n"
+        "x = torch.arange(-4000, 3880, dtype=torch.int32, device='cuda').reshape(40, 197)\n"
+        "o = torch.zeros((40, 197), dtype=torch.uint8, device='cuda')\n"
+        "ip.softmax_i32(x, None, 0, o, 40, 197, ip.softmax_prepare(2.0 ** -6, 197, 1, 0))\n"
+        "torch.cuda.synchronize()\n"
+        "print('sum', int(o.sum()))\n")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=240)
+    assert r.returncode == 0, r.stderr[-2000:]
+    x = np.arange(-4000, 3880, dtype=np.int32).reshape(40, 197)
+    want = ref.softmax_i32(x, prepare.softmax_prepare(2.0 ** -6, 197, 1))
+    assert "sum %d" % int(want.sum()) in r.stdout
