@@ -172,6 +172,20 @@ def time_steps(fn, reps, before_each=None):
     return ev[0].elapsed_time(ev[reps]) / reps, each[len(each) // 2], each[0]
 
 
+def warm(fn, seconds=0.2):
+    """Runs fn() for a while, untimed: after host-side set-up the clocks need some tens of
+    milliseconds of work to reach their steady state."""
+    import torch
+    t_end = time.perf_counter() + seconds
+    i = 0
+    while time.perf_counter() < t_end:
+        fn()
+        i += 1
+        if i % 8 == 0:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+
+
 def time_region(fn, reps):
     return time_steps(fn, reps)[0]
 
@@ -208,8 +222,7 @@ def measure_fused(steps):
 
     res = {}
     for name, fn in (("softmax_pre_requant", softmax_pre), ("gelu_i32", gelu_i32)):
-        for _ in range(3):
-            fn()
+        warm(fn)
         mean, med, mn = time_steps(fn, steps)
         el = units[0].softmax_elements
         gb = SOFTMAX_BYTES_PER_EL * el / (mean / len(units) * 1e-3) / 1e9
@@ -217,7 +230,6 @@ def measure_fused(steps):
                      "median_launch_us": med / len(units) * 1e3, "min_launch_us": mn / len(units) * 1e3,
                      "gbps": gb, "pct_of_hbm_peak": pct(gb)}
     del units, d_y32
-    torch.cuda.empty_cache()
     return res
 
 
@@ -255,14 +267,12 @@ def measure_softmax_forms(steps):
             for u, (p, signed), o8 in zip(units, params, out_i8):
                 ip.softmax_i32(u.d_scores, None, 0, o8 if signed else u.d_probs, u.rows, u.cols, p)
 
-        for _ in range(2):
-            fn()
+        warm(fn)
         mean, med, mn = time_steps(fn, steps)
         gb = SOFTMAX_BYTES_PER_EL * el / (mean / len(units) * 1e-3) / 1e9
         res[kind] = {"avg_launch_us": mean / len(units) * 1e3, "median_launch_us": med / len(units) * 1e3,
                      "min_launch_us": mn / len(units) * 1e3, "gbps": gb, "pct_of_hbm_peak": pct(gb)}
     del units, out_i8
-    torch.cuda.empty_cache()
     return res
 
 
@@ -286,14 +296,13 @@ def measure_gelu_per_element(steps):
             for u, gp in zip(units, gps):
                 ip.gelu_i8(u.d_x, u.d_y, u.gelu_n, gp)
 
-        fn()
+        warm(fn)
         mean, med, mn = time_steps(fn, steps)
         gb = GELU_BYTES_PER_EL * units[0].gelu_n / (mean / len(units) * 1e-3) / 1e9
         res["degree_%d" % (2 if variant == 0 else 4)] = {
             "avg_launch_us": mean / len(units) * 1e3, "median_launch_us": med / len(units) * 1e3,
             "min_launch_us": mn / len(units) * 1e3, "gbps": gb, "pct_of_hbm_peak": pct(gb)}
     del units
-    torch.cuda.empty_cache()
     return res
 
 
@@ -322,14 +331,13 @@ def measure_swin_shifted(steps):
 
         out = {}
         for name, f in (("bias_and_mask", fn), ("bias_only", plain)):
-            f()
+            warm(f)
             mean, med, mn = (t / 4 for t in time_steps(f, steps))
             gb = SOFTMAX_BYTES_PER_EL * u.softmax_elements / (mean * 1e-3) / 1e9
             out[name] = {"avg_launch_us": mean * 1e3, "median_launch_us": med * 1e3, "min_launch_us": mn * 1e3,
                          "gbps": gb, "pct_of_hbm_peak": pct(gb)}
         res["stage_%d" % (s + 1)] = out
     del units, masks
-    torch.cuda.empty_cache()
     return res
 
 
@@ -354,14 +362,13 @@ def measure_row_lengths(steps):
             for x, y in zip(ins, outs):
                 ip.softmax_i32(x, None, 0, y, rows, cols, sp)
 
-        fn()
+        warm(fn, 0.1)
         ms = time_region(fn, max(1, steps // 2)) / len(ins)
         el = rows * cols
         res[str(cols)] = {"rows": rows, "kernel": ip.softmax_kernel_family(cols),
                           "avg_launch_us": ms * 1e3,
                           "pct_of_hbm_peak": pct(SOFTMAX_BYTES_PER_EL * el / (ms * 1e-3) / 1e9)}
         del ins, outs
-    torch.cuda.empty_cache()
     return res
 
 
@@ -576,14 +583,13 @@ def main():
             for u in units:
                 ip.requant(u.d_scores.view(-1), u.d_probs.view(-1), u.softmax_elements, 0, dy)
 
-        requant_all()
+        warm(requant_all, 0.05)
         rq = time_steps(requant_all, max(1, args.steps // 2), rotate)
         res["stream_ceiling"] = {"what": "iptq_requant (int32 -> uint8, the softmax's 5 B/element mix) over the "
                                          "same score tensors, one launch per unit",
                                  "gbps": SOFTMAX_BYTES_PER_EL * sm_el / (rq[0] * 1e-3) / 1e9,
                                  "avg_launch_us": rq[0] / n * 1e3, "median_launch_us": rq[1] / n * 1e3}
         del units
-        torch.cuda.empty_cache()
         return res
 
     main_res = measure(args.workload, both_variants=args.workload in ("vit_b", "swin_b", "swin_s_det"))
