@@ -184,6 +184,43 @@ def softmax_i32_windowed(scores: np.ndarray, p: SoftmaxParams, bias: Optional[np
     return out
 
 
+def pack_window_mask(mask: np.ndarray) -> np.ndarray:
+    """One bit per key of a 0 / INT32_MIN window mask [n_windows, cols, cols]: uint64
+    [n_windows, cols, ceil(cols / 64)], bit (k mod 64) of word (k div 64) of row [w, q] set where
+    mask[w, q, k] == INT32_MIN (any other value counts as "not masked").  Plain loops."""
+    mask = np.asarray(mask, dtype=np.int32)
+    n_w, cols, cols2 = mask.shape
+    assert cols == cols2
+    words = (cols + 63) // 64
+    out = np.zeros((n_w, cols, words), dtype=np.uint64)
+    for w in range(n_w):
+        for q in range(cols):
+            for k in range(cols):
+                if int(mask[w, q, k]) == -(2 ** 31):
+                    out[w, q, k // 64] |= np.uint64(1) << np.uint64(k % 64)
+    return out
+
+
+def unpack_window_mask(bits: np.ndarray, cols: int) -> np.ndarray:
+    """The 0 / INT32_MIN mask a packed one stands for (bits beyond `cols` are ignored)."""
+    bits = np.asarray(bits, dtype=np.uint64)
+    n_w = bits.shape[0]
+    out = np.zeros((n_w, cols, cols), dtype=np.int32)
+    for w in range(n_w):
+        for q in range(cols):
+            for k in range(cols):
+                if (int(bits[w, q, k // 64]) >> (k % 64)) & 1:
+                    out[w, q, k] = -(2 ** 31)
+    return out
+
+
+def softmax_i32_windowed_bits(scores, p, bias, bias_period_rows, bits, heads) -> np.ndarray:
+    """The windowed softmax with the mask given one bit per key: by definition the windowed
+    softmax with the 0 / INT32_MIN mask those bits stand for."""
+    cols = scores.shape[1]
+    return softmax_i32_windowed(scores, p, bias, bias_period_rows, unpack_window_mask(bits, cols), heads)
+
+
 def gelu_i8(x: np.ndarray, p: GeluParams) -> np.ndarray:
     x = np.ascontiguousarray(x, dtype=np.int8)
     out = np.empty(x.shape, dtype=np.int8)

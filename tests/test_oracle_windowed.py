@@ -75,3 +75,41 @@ def test_general_additive_mask_values():
     # row 0: deltas 0, -20 -> variant 0 of row A in the golden file: Qexp 16 and 5, sum 21,
     # f = floor(2^30 / 21) = 51130563, p = (16 f) >> 23 = 97, (5 f) >> 23 = 30
     assert got.tolist() == [[97, 30], [64, 64]]
+
+
+def test_packed_mask_by_hand_and_round_trip():
+    # 2 windows of 3 tokens: window 0 unmasked; window 1: query 0 masks key 2, query 2 masks keys 0, 1
+    mask = np.zeros((2, 3, 3), np.int32)
+    mask[1, 0, 2] = INT32_MIN
+    mask[1, 2, 0] = mask[1, 2, 1] = INT32_MIN
+    mask[0, 1, 1] = -7                                   # a finite addend is "not masked"
+    bits = ref.pack_window_mask(mask)
+    assert bits.shape == (2, 3, 1) and bits.dtype == np.uint64
+    assert bits[:, :, 0].tolist() == [[0, 0, 0], [4, 0, 3]]
+    back = ref.unpack_window_mask(bits, 3)
+    want = mask.copy()
+    want[0, 1, 1] = 0
+    assert np.array_equal(back, want)
+    # more than 64 keys: two words per row, bit 64 is bit 0 of the second word
+    big = np.zeros((1, 70, 70), np.int32)
+    big[0, 5, 63] = big[0, 5, 64] = big[0, 5, 69] = INT32_MIN
+    b = ref.pack_window_mask(big)
+    assert b.shape == (1, 70, 2)
+    assert int(b[0, 5, 0]) == 1 << 63 and int(b[0, 5, 1]) == (1 << 0) | (1 << 5)
+    assert np.array_equal(ref.unpack_window_mask(b, 70), big)
+    rng = np.random.default_rng(3)
+    m = np.where(rng.random((3, 49, 49)) < 0.3, INT32_MIN, 0).astype(np.int32)
+    assert np.array_equal(ref.unpack_window_mask(ref.pack_window_mask(m), 49), m)
+
+
+def test_softmax_with_packed_mask_equals_the_int32_mask():
+    rng = np.random.default_rng(4)
+    cols, heads, n_w = 6, 2, 3
+    rows = 2 * n_w * heads * cols
+    scores = np.rint(rng.standard_normal((rows, cols)) * 100).astype(np.int32)
+    bias = np.rint(rng.standard_normal((heads * cols, cols)) * 10).astype(np.int32)
+    mask = np.where(rng.random((n_w, cols, cols)) < 0.3, INT32_MIN, 0).astype(np.int32)
+    p = ref.SoftmaxParams(variant=1, i0=64, n_shift=8)
+    a = ref.softmax_i32_windowed(scores, p, bias, heads * cols, mask, heads)
+    b = ref.softmax_i32_windowed_bits(scores, p, bias, heads * cols, ref.pack_window_mask(mask), heads)
+    assert np.array_equal(a, b)
