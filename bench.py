@@ -307,8 +307,9 @@ def measure_gelu_per_element(steps):
 
 
 def measure_swin_shifted(steps):
-    """Swin-B stages 1-3 with the shifted-window mask beside the bias (iptq_softmax_i32_windowed),
-    one launch per stage, two tensor sets."""
+    """Swin-B stages 1-3 with the shifted-window mask beside the bias (iptq_softmax_i32_windowed: the
+    int32 mask; iptq_softmax_i32_windowed_bits: one bit per key), one launch per stage, four
+    tensor sets."""
     import torch
 
     import paper_2511_15369_amd as ip
@@ -316,13 +317,24 @@ def measure_swin_shifted(steps):
     units = [Unit("swin_b", u, sets=4) for u in range(3)]
     masks = [torch.from_numpy(workloads.shifted_window_mask(workloads.SWIN_B_MAP_SIDE[u],
                                                             workloads.SWIN_B_MAP_SIDE[u])).cuda() for u in range(3)]
+    packed = []                                       # the same masks one bit per key, packed by the library
+    for u, m in zip(units, masks):
+        b = torch.empty((u.windows, u.cols, 1), dtype=torch.int64, device="cuda")
+        ip.pack_window_mask(m, u.windows, u.cols, b)
+        packed.append(b)
     res = {}
-    for s, (u, m) in enumerate(zip(units, masks)):
+    for s, (u, m, mb) in enumerate(zip(units, masks, packed)):
         def fn():
             for k in range(4):
                 u.use_set(k)
                 ip.softmax_i32_windowed(u.d_scores, u.d_bias, u.period, m, u.windows, u.heads, u.d_probs,
                                         u.rows, u.cols, u.sp)
+
+        def bits():
+            for k in range(4):
+                u.use_set(k)
+                ip.softmax_i32_windowed_bits(u.d_scores, u.d_bias, u.period, mb, u.windows, u.heads, u.d_probs,
+                                             u.rows, u.cols, u.sp)
 
         def plain():
             for k in range(4):
@@ -330,14 +342,14 @@ def measure_swin_shifted(steps):
                 u.softmax()
 
         out = {}
-        for name, f in (("bias_and_mask", fn), ("bias_only", plain)):
+        for name, f in (("bias_and_mask", fn), ("bias_and_mask_bits", bits), ("bias_only", plain)):
             warm(f)
             mean, med, mn = (t / 4 for t in time_steps(f, steps))
             gb = SOFTMAX_BYTES_PER_EL * u.softmax_elements / (mean * 1e-3) / 1e9
             out[name] = {"avg_launch_us": mean * 1e3, "median_launch_us": med * 1e3, "min_launch_us": mn * 1e3,
                          "gbps": gb, "pct_of_hbm_peak": pct(gb)}
         res["stage_%d" % (s + 1)] = out
-    del units, masks
+    del units, masks, packed
     return res
 
 

@@ -210,6 +210,30 @@ int iptq_softmax_i32_windowed(const int32_t *d_scores, const int32_t *d_bias,
                               const iptq_softmax_params_t *p, void *stream);
 
 /*
+ * The same with the mask handed over one bit per key, for masks whose entries are 0 or INT32_MIN
+ * only (a Swin model's are): d_mask_bits is a [n_windows, cols, ceil(cols / 64)] array of 64-bit
+ * words (device, 8-byte aligned); bit (k mod 64) of word (k div 64) of row [w, q] set means key k
+ * is masked for query q of window w; bits beyond `cols` are ignored.  Identical results to
+ * iptq_softmax_i32_windowed with the int32 mask those bits stand for; the mask then costs one
+ * 8-byte load per row instead of a third table read beside the scores.
+ * Speed: windows of 49 tokens with a bias run in the slab kernel; any other shape takes the slow
+ * three-pass kernel.
+ */
+int iptq_softmax_i32_windowed_bits(const int32_t *d_scores, const int32_t *d_bias,
+                                   int64_t bias_period_rows, const uint64_t *d_mask_bits,
+                                   int32_t n_windows, int32_t heads, void *d_out, int64_t rows,
+                                   int32_t cols, const iptq_softmax_params_t *p, void *stream);
+
+/*
+ * Packs a [n_windows, cols, cols] int32 mask (device) into that form: a bit is set where the
+ * entry equals INT32_MIN, any other entry counts as "not masked".  d_mask_bits:
+ * n_windows * cols * ceil(cols / 64) words (device, 8-byte aligned, caller-owned, must not
+ * overlap d_mask).  Done once per model, when the masks are built.  n_windows >= 0 (0: no-op).
+ */
+int iptq_pack_window_mask(const int32_t *d_mask, int32_t n_windows, int32_t cols,
+                          uint64_t *d_mask_bits, void *stream);
+
+/*
  * Integer GELU (Section 4.3, Eq. 3 and 5; steps listed at iptq_gelu_params_t) of n int8
  * activations.  d_out may equal d_in (in place); partial overlap is not allowed.
  */
@@ -239,6 +263,8 @@ typedef struct {
     const int32_t *d_mask;    /* NULL or the per-window mask of iptq_softmax_i32_windowed */
     int32_t n_windows;
     int32_t heads;
+    const uint64_t *d_mask_bits; /* NULL or the mask one bit per key (iptq_softmax_i32_windowed_bits);
+                                    at most one of d_mask and d_mask_bits */
 } iptq_softmax_problem_t;
 
 typedef struct {

@@ -60,7 +60,8 @@ class SoftmaxProblem(ctypes.Structure):
     _fields_ = [("d_scores", ctypes.c_void_p), ("d_bias", ctypes.c_void_p),
                 ("bias_period_rows", ctypes.c_int64), ("d_out", ctypes.c_void_p),
                 ("rows", ctypes.c_int64), ("params", SoftmaxParams), ("d_mask", ctypes.c_void_p),
-                ("n_windows", ctypes.c_int32), ("heads", ctypes.c_int32)]
+                ("n_windows", ctypes.c_int32), ("heads", ctypes.c_int32),
+                ("d_mask_bits", ctypes.c_void_p)]
 
 
 class GeluProblem(ctypes.Structure):
@@ -97,6 +98,11 @@ def load():
     lib.iptq_softmax_i32_windowed.argtypes = [vp, vp, i64, vp, i32, i32, vp, i64, i32,
                                               ctypes.POINTER(SoftmaxParams), vp]
     lib.iptq_softmax_i32_windowed.restype = ctypes.c_int
+    lib.iptq_softmax_i32_windowed_bits.argtypes = [vp, vp, i64, vp, i32, i32, vp, i64, i32,
+                                                   ctypes.POINTER(SoftmaxParams), vp]
+    lib.iptq_softmax_i32_windowed_bits.restype = ctypes.c_int
+    lib.iptq_pack_window_mask.argtypes = [vp, i32, i32, vp, vp]
+    lib.iptq_pack_window_mask.restype = ctypes.c_int
     lib.iptq_gelu_i8.argtypes = [vp, vp, i64, ctypes.POINTER(GeluParams), vp]
     lib.iptq_gelu_i32.argtypes = [vp, vp, i64, ctypes.POINTER(GeluParams), vp]
     lib.iptq_softmax_i32_layers.argtypes = [vp, i64, vp, i64, i64, i32, i32,
@@ -272,6 +278,34 @@ def softmax_i32_windowed(d_scores, d_bias, bias_period_rows: int, d_mask, n_wind
            "iptq_softmax_i32_windowed")
 
 
+def softmax_i32_windowed_bits(d_scores, d_bias, bias_period_rows: int, d_mask_bits, n_windows: int,
+                              heads: int, d_out, rows: int, cols: int, p: SoftmaxParams):
+    import torch
+    _need(d_scores, torch.int32, "d_scores")
+    _need(d_out, torch.int8 if p.out_is_signed else torch.uint8, "d_out")
+    assert d_scores.numel() >= rows * cols and d_out.numel() >= rows * cols
+    if d_bias is not None:
+        _need(d_bias, torch.int32, "d_bias")
+        assert d_bias.numel() >= bias_period_rows * cols
+    if d_mask_bits is not None:
+        _need(d_mask_bits, torch.int64, "d_mask_bits")        # torch has no uint64 arithmetic: the words travel as int64
+        assert d_mask_bits.numel() >= n_windows * cols * ((cols + 63) // 64)
+    _check(load().iptq_softmax_i32_windowed_bits(_dptr(d_scores), _dptr(d_bias), bias_period_rows,
+                                                 _dptr(d_mask_bits), n_windows, heads, _dptr(d_out),
+                                                 rows, cols, ctypes.byref(p), _stream()),
+           "iptq_softmax_i32_windowed_bits")
+
+
+def pack_window_mask(d_mask, n_windows: int, cols: int, d_mask_bits):
+    import torch
+    _need(d_mask, torch.int32, "d_mask")
+    _need(d_mask_bits, torch.int64, "d_mask_bits")
+    assert d_mask.numel() >= n_windows * cols * cols
+    assert d_mask_bits.numel() >= n_windows * cols * ((cols + 63) // 64)
+    _check(load().iptq_pack_window_mask(_dptr(d_mask), n_windows, cols, _dptr(d_mask_bits), _stream()),
+           "iptq_pack_window_mask")
+
+
 def gelu_i8(d_in, d_out, n: int, p: GeluParams):
     import torch
     _need(d_in, torch.int8, "d_in")
@@ -321,7 +355,8 @@ def gelu_i8_layers(d_in, in_stride: int, d_out, out_stride: int, n: int, n_layer
 
 
 def softmax_problem(d_scores, d_bias, bias_period_rows: int, d_out, rows: int, cols: int,
-                    p: SoftmaxParams, d_mask=None, n_windows: int = 0, heads: int = 0) -> SoftmaxProblem:
+                    p: SoftmaxParams, d_mask=None, n_windows: int = 0, heads: int = 0,
+                    d_mask_bits=None) -> SoftmaxProblem:
     """One entry of a softmax batch (same checks as softmax_i32)."""
     import torch
     _need(d_scores, torch.int32, "d_scores")
@@ -333,9 +368,13 @@ def softmax_problem(d_scores, d_bias, bias_period_rows: int, d_out, rows: int, c
     if d_mask is not None:
         _need(d_mask, torch.int32, "d_mask")
         assert d_mask.numel() >= n_windows * cols * cols
+    if d_mask_bits is not None:
+        _need(d_mask_bits, torch.int64, "d_mask_bits")
+        assert d_mask_bits.numel() >= n_windows * cols * ((cols + 63) // 64)
     return SoftmaxProblem(d_scores.data_ptr(), None if d_bias is None else d_bias.data_ptr(),
                           bias_period_rows, d_out.data_ptr(), rows, p,
-                          None if d_mask is None else d_mask.data_ptr(), n_windows, heads)
+                          None if d_mask is None else d_mask.data_ptr(), n_windows, heads,
+                          None if d_mask_bits is None else d_mask_bits.data_ptr())
 
 
 def gelu_problem(d_in, d_out, n: int, p: GeluParams) -> GeluProblem:

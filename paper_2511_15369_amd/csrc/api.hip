@@ -37,17 +37,20 @@ extern "C" int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t
 static int softmax_call(const int32_t *d_scores, const int32_t *d_bias, int64_t bias_period_rows,
                         void *d_out, int64_t rows, int32_t cols, const iptq_softmax_params_t *p,
                         SoftmaxCall *out, const int32_t *d_mask = nullptr, int64_t n_windows = 0,
-                        int64_t heads = 0)
+                        int64_t heads = 0, const uint64_t *d_mask_bits = nullptr)
 {
     if (!p) return IPTQ_ERR_NULL;
     int rc = plan_softmax(p, rows, cols, d_bias != nullptr, bias_period_rows, &out->P);
     if (rc != IPTQ_OK) return rc;
-    if (d_mask) {
+    if (d_mask && d_mask_bits) return IPTQ_ERR_PARAM;     // one form of the mask or the other
+    if (d_mask || d_mask_bits) {
         rc = plan_softmax_mask(n_windows, heads, cols, &out->P);
         if (rc != IPTQ_OK) return rc;
-        if (reinterpret_cast<uintptr_t>(d_mask) & 3) return IPTQ_ERR_ALIGN;
+        if ((reinterpret_cast<uintptr_t>(d_mask) & 3) || (reinterpret_cast<uintptr_t>(d_mask_bits) & 7))
+            return IPTQ_ERR_ALIGN;
     }
     out->mask = d_mask;
+    out->mask_bits = d_mask_bits;
     out->scores = d_scores; out->bias = d_bias; out->out = static_cast<uint8_t *>(d_out);
     out->rows = rows; out->out_bits = p->out_bits; out->algo = p->algo;
     if (rows == 0) return IPTQ_OK;
@@ -94,6 +97,35 @@ extern "C" int iptq_softmax_i32_windowed(const int32_t *d_scores, const int32_t 
     return hip_rc(softmax_dispatch(&call, 1, cols, static_cast<hipStream_t>(stream)));
 }
 
+extern "C" int iptq_softmax_i32_windowed_bits(const int32_t *d_scores, const int32_t *d_bias,
+                                              int64_t bias_period_rows, const uint64_t *d_mask_bits,
+                                              int32_t n_windows, int32_t heads, void *d_out,
+                                              int64_t rows, int32_t cols,
+                                              const iptq_softmax_params_t *p, void *stream)
+{
+    SoftmaxCall call;
+    int rc = softmax_call(d_scores, d_bias, bias_period_rows, d_out, rows, cols, p, &call, nullptr,
+                          n_windows, heads, d_mask_bits);
+    if (rc != IPTQ_OK || rows == 0) return rc;
+    return hip_rc(softmax_dispatch(&call, 1, cols, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" int iptq_pack_window_mask(const int32_t *d_mask, int32_t n_windows, int32_t cols,
+                                     uint64_t *d_mask_bits, void *stream)
+{
+    if (n_windows < 0 || cols < 1 || cols > IPTQ_COLS_MAX) return IPTQ_ERR_SHAPE;
+    if (n_windows == 0) return IPTQ_OK;
+    if (!d_mask || !d_mask_bits) return IPTQ_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(d_mask) & 3) || (reinterpret_cast<uintptr_t>(d_mask_bits) & 7))
+        return IPTQ_ERR_ALIGN;
+    const int64_t n_queries = (int64_t)n_windows * cols;
+    if (n_queries * cols >= ((int64_t)1 << 40)) return IPTQ_ERR_SHAPE;
+    if (overlap(d_mask, n_queries * cols * 4, d_mask_bits, n_queries * ((cols + 63) / 64) * 8))
+        return IPTQ_ERR_PARAM;
+    return hip_rc(pack_window_mask_dispatch(d_mask, n_queries, cols, d_mask_bits,
+                                            static_cast<hipStream_t>(stream)));
+}
+
 extern "C" int iptq_softmax_i32_batch(const iptq_softmax_problem_t *problems, int32_t n_problems,
                                       int32_t cols, void *stream)
 {
@@ -106,7 +138,7 @@ extern "C" int iptq_softmax_i32_batch(const iptq_softmax_problem_t *problems, in
     for (int32_t i = 0; i < n_problems; ++i) {           // every problem is checked before any launch
         const iptq_softmax_problem_t &q = problems[i];
         int rc = softmax_call(q.d_scores, q.d_bias, q.bias_period_rows, q.d_out, q.rows, cols,
-                              &q.params, &calls[n], q.d_mask, q.n_windows, q.heads);
+                              &q.params, &calls[n], q.d_mask, q.n_windows, q.heads, q.d_mask_bits);
         if (rc != IPTQ_OK) return rc;
         if (q.rows > 0) ++n;
     }

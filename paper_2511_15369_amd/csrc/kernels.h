@@ -13,6 +13,7 @@ struct SoftmaxCall {
     const int32_t *scores;
     const int32_t *bias;
     const int32_t *mask;  // per-window mask or nullptr (its shape is in P)
+    const uint64_t *mask_bits;   // or the same mask one bit per key, ceil(cols / 64) words per query
     uint8_t *out;
     int64_t rows;
     int out_bits;
@@ -49,6 +50,9 @@ bool wgrow_geometry(int32_t cols, int *waves, int *slots, bool off_grid = false)
 hipError_t gelu_i8_dispatch(const GeluCall *calls, int n_calls, hipStream_t stream);
 hipError_t gelu_i32_dispatch(const int32_t *in, int8_t *out, int64_t n, const GeluDev &P,
                              bool force_direct, hipStream_t stream);
+// [n_windows, cols, cols] int32 -> [n_windows, cols, ceil(cols / 64)] words, bit k set where the entry is INT32_MIN
+hipError_t pack_window_mask_dispatch(const int32_t *mask, int64_t n_queries, int32_t cols, uint64_t *bits,
+                                     hipStream_t stream);
 hipError_t requant_dispatch(const int32_t *in, void *out, int64_t n, const DyadicDev &P,
                             hipStream_t stream);
 

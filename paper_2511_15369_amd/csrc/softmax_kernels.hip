@@ -20,8 +20,9 @@ namespace iptq {
 template <int VARIANT>
 __global__ void __launch_bounds__(256)
 softmax_generic_kernel(const int32_t *__restrict__ scores, const int32_t *__restrict__ bias,
-                       const int32_t *__restrict__ mask, uint8_t *__restrict__ out, int64_t row_begin,
-                       int64_t row_end, int32_t cols, int32_t has_bias, int32_t has_pre, SoftmaxDev P)
+                       const int32_t *__restrict__ mask, const uint64_t *__restrict__ mask_bits,
+                       uint8_t *__restrict__ out, int64_t row_begin, int64_t row_end, int32_t cols,
+                       int32_t has_bias, int32_t has_pre, SoftmaxDev P)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = row_begin + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -30,7 +31,8 @@ softmax_generic_kernel(const int32_t *__restrict__ scores, const int32_t *__rest
     const int32_t *brow = nullptr;
     if (has_bias) brow = bias + (int64_t)row_mod_period((uint32_t)row, P) * cols;
     const int32_t *mrow = nullptr;
-    if (mask) {
+    const uint64_t *mbits = nullptr;                  // the row's mask one bit per key
+    if (mask || mask_bits) {
         // rows are ordered [image, window, head, query]: window (r mod period) div (heads * cols),
         // query (r mod (heads * cols)) mod cols; cols is a run-time value here, so the last one is
         // a subtraction loop over the heads in front (once per row)
@@ -41,13 +43,15 @@ softmax_generic_kernel(const int32_t *__restrict__ scores, const int32_t *__rest
         const uint32_t w = P.group_rows >= 2 ? mulhi_u32(rm, P.group_magic) >> P.group_sh : rm;
         uint32_t q = rm - w * (uint32_t)P.group_rows;
         while (q >= (uint32_t)cols) q -= (uint32_t)cols;
-        mrow = mask + ((int64_t)w * cols + q) * cols;
+        if (mask) mrow = mask + ((int64_t)w * cols + q) * cols;
+        else mbits = mask_bits + ((int64_t)w * cols + q) * ((cols + 63) >> 6);
     }
 
     auto fetch = [&](int c) -> int32_t {
         int32_t v = srow[c];
         if (has_bias) v = add_table_entry(v, brow[c]);
         if (mrow) v = add_table_entry(v, mrow[c]);
+        if (mbits && ((mbits[c >> 6] >> (c & 63)) & 1)) v = kI32Min;
         if (has_pre && v != kI32Min) v = pre_requant_dev(v, P.pre_m, P.pre_s);
         return v;
     };
@@ -72,6 +76,36 @@ softmax_generic_kernel(const int32_t *__restrict__ scores, const int32_t *__rest
 }
 
 // ---------------------------------------------------------------------------------------
+// A 0 / INT32_MIN window mask as one bit per key: thread x = query row, block y = word of that
+// row; each thread reads up to 64 entries of its mask row.  Run once per model (a few hundred
+// kilobytes), not on the inference path.
+__global__ void __launch_bounds__(256)
+pack_window_mask_kernel(const int32_t *__restrict__ mask, int64_t n_queries, int32_t cols,
+                        int32_t words, uint64_t *__restrict__ bits)
+{
+    const int64_t row = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (row >= n_queries) return;
+    const int32_t wd = (int32_t)blockIdx.y;
+    const int32_t *m = mask + row * cols;
+    const int32_t k0 = wd * 64;
+    const int32_t k1 = min(cols, k0 + 64);
+    uint64_t w = 0;
+    for (int32_t k = k0; k < k1; ++k)
+        if (m[k] == kI32Min) w |= (uint64_t)1 << (k - k0);
+    bits[row * words + wd] = w;
+}
+
+hipError_t pack_window_mask_dispatch(const int32_t *mask, int64_t n_queries, int32_t cols, uint64_t *bits,
+                                     hipStream_t stream)
+{
+    const int32_t words = (cols + 63) / 64;           // at most 1024
+    if (n_queries <= 0) return hipSuccess;
+    hipLaunchKernelGGL(pack_window_mask_kernel, dim3((unsigned)((n_queries + 255) / 256), (unsigned)words),
+                       dim3(256), 0, stream, mask, n_queries, cols, words, bits);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
 // Host-side dispatch.
 
 static int post_mode_of(const SoftmaxDev &P, int out_bits)
@@ -84,20 +118,20 @@ static int post_mode_of(const SoftmaxDev &P, int out_bits)
 }
 
 static hipError_t launch_generic(const int32_t *scores, const int32_t *bias, const int32_t *mask,
-                                 uint8_t *out, int64_t row_begin, int64_t row_end, int32_t cols,
+                                 const uint64_t *mask_bits, uint8_t *out, int64_t row_begin, int64_t row_end, int32_t cols,
                                  bool has_bias, bool has_pre, const SoftmaxDev &P, hipStream_t stream)
 {
     const int64_t n = row_end - row_begin;
     if (n <= 0) return hipSuccess;
     const dim3 grid((unsigned)((n + 3) / 4)), block(256);
     if (P.variant == 0)
-        hipLaunchKernelGGL(softmax_generic_kernel<0>, grid, block, 0, stream, scores, bias, mask, out,
+        hipLaunchKernelGGL(softmax_generic_kernel<0>, grid, block, 0, stream, scores, bias, mask, mask_bits, out,
                            row_begin, row_end, cols, (int32_t)has_bias, (int32_t)has_pre, P);
     else if (P.variant == 1)
-        hipLaunchKernelGGL(softmax_generic_kernel<1>, grid, block, 0, stream, scores, bias, mask, out,
+        hipLaunchKernelGGL(softmax_generic_kernel<1>, grid, block, 0, stream, scores, bias, mask, mask_bits, out,
                            row_begin, row_end, cols, (int32_t)has_bias, (int32_t)has_pre, P);
     else
-        hipLaunchKernelGGL(softmax_generic_kernel<2>, grid, block, 0, stream, scores, bias, mask, out,
+        hipLaunchKernelGGL(softmax_generic_kernel<2>, grid, block, 0, stream, scores, bias, mask, mask_bits, out,
                            row_begin, row_end, cols, (int32_t)has_bias, (int32_t)has_pre, P);
     return hipGetLastError();
 }
@@ -124,7 +158,9 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
     constexpr int64_t kTinyRows = 3072;
     // (a per-window mask and the second-degree exponential exist in the compiled-row-length and
     // the three-pass kernels only)
-    auto slab_only = [](const SoftmaxCall &c) { return c.mask != nullptr || c.P.variant == 2; };
+    auto slab_only = [](const SoftmaxCall &c) {
+        return c.mask != nullptr || c.mask_bits != nullptr || c.P.variant == 2;
+    };
     if (n_calls == 1 && calls[0].algo == IPTQ_ALGO_AUTO && calls[0].rows <= kTinyRows && !slab_only(calls[0])) {
         int64_t served = 0;
         const hipError_t e = softmax_wide_launch(calls[0], cols, post_mode_of(calls[0].P, calls[0].out_bits),
@@ -133,7 +169,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
         if (served == calls[0].rows) return hipSuccess;      // every row or none
     }
     int rpw = 0;                                      // rows per wavefront of the compiled row length
-    hipError_t (*launch)(const SoftmaxBatch &, unsigned, bool, bool, bool, int, int, hipStream_t) = nullptr;
+    hipError_t (*launch)(const SoftmaxBatch &, unsigned, bool, int, bool, int, int, hipStream_t) = nullptr;
 #define IPTQ_PICK_ROWS_SHAPE(COLS, K)                                                             \
     if (cols == COLS) { rpw = 64 / K; launch = launch_softmax_rows<COLS, K>; }
     IPTQ_ROWS_SHAPES(IPTQ_PICK_ROWS_SHAPE)
@@ -146,8 +182,8 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
     SoftmaxBatch B;
     B.n_items = 0;
     unsigned total_wgs = 0;
-    bool g_bias = false, g_mask = false, g_fold = false;
-    int g_pm = 0, g_mode = 0;
+    bool g_bias = false, g_fold = false;
+    int g_mask = 0, g_pm = 0, g_mode = 0;             // g_mask: 0 none, 1 int32 table, 2 one bit per key
     hipError_t err = hipSuccess;
     auto flush = [&]() {
         if (B.n_items == 0 || err != hipSuccess) return;
@@ -172,11 +208,16 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
                                        (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 31) &&
                                                c.P.bias_period_rows >= rpw);
             const bool slab_algo = c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_SLAB;
-            const bool has_mask = c.mask != nullptr;
+            const int has_mask = c.mask != nullptr ? 1 : (c.mask_bits != nullptr ? 2 : 0);
             // the mask is compiled in beside a bias, for window sizes whose slab has no more rows
-            // than a window has queries
-            const bool mask_ok = !has_mask || (has_bias && rows_mask_compiled(cols) && rpw <= cols &&
-                                               (reinterpret_cast<uintptr_t>(c.mask) & 3) == 0);
+            // than a window has queries (one bit per key: windows of 49 tokens)
+            bool mask_ok = true;
+            if (has_mask == 1)
+                mask_ok = has_bias && rows_mask_compiled(cols) && rpw <= cols &&
+                          (reinterpret_cast<uintptr_t>(c.mask) & 3) == 0;
+            else if (has_mask == 2)
+                mask_ok = has_bias && rows_maskbits_compiled(cols) &&
+                          (reinterpret_cast<uintptr_t>(c.mask_bits) & 7) == 0;
             if (rpw == 0 || !slab_algo || !aligned || !bias_ok || !mask_ok) continue;
             const int64_t n_slabs = (c.rows + rpw - 1) / rpw;    // a partial last slab is served too
             if (n_slabs == 0) continue;
@@ -189,7 +230,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             else if (mode > g_mode) g_mode = mode;       // 2 covers 1: items with t16 == 0 shift by 0
             if (c.P.pre_rowconst != 0) g_fold = true;
             SoftmaxItem &it = B.item[B.n_items++];
-            it.scores = c.scores; it.bias = c.bias; it.mask = c.mask; it.out = c.out;
+            it.scores = c.scores; it.bias = c.bias; it.mask = c.mask; it.mask_bits = c.mask_bits; it.out = c.out;
             it.n_slabs = n_slabs; it.first_wg = total_wgs; it.P = c.P;
             it.tail_rows = (int32_t)(c.rows % rpw);
             it.share_q = 0; it.share_magic = 0; it.share_sh = 0;
@@ -198,7 +239,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
                 // rows after which the tables repeat: the bias period, or with a mask the least
                 // common multiple of both periods
                 int64_t period = c.P.bias_period_rows;
-                if (has_mask) {
+                if (has_mask != 0) {
                     int64_t a = period, b = c.P.mask_period_rows;
                     while (b != 0) { const int64_t t = a % b; a = b; b = t; }
                     period = period / a * c.P.mask_period_rows;
@@ -232,7 +273,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
                 err = softmax_wgrow_launch(c, cols, post_mode_of(c.P, c.out_bits), &done[i], stream);
                 if (err != hipSuccess) break;
             }
-            err = launch_generic(c.scores, c.bias, c.mask, c.out, done[i], c.rows, cols, c.bias != nullptr,
+            err = launch_generic(c.scores, c.bias, c.mask, c.mask_bits, c.out, done[i], c.rows, cols, c.bias != nullptr,
                                  has_pre, c.P, stream);
         }
         if (err != hipSuccess) return err;

@@ -42,6 +42,7 @@ struct SoftmaxItem {
     const int32_t *scores;
     const int32_t *bias;
     const int32_t *mask;  // per-window mask [n_windows, cols, cols] or nullptr
+    const uint64_t *mask_bits;   // the same mask one bit per key, [n_windows, cols] words (cols <= 64), or nullptr
     uint8_t *out;
     int64_t n_slabs;      // the last one may be partial
     uint32_t first_wg;
@@ -379,9 +380,11 @@ static __device__ uint64_t g_timeline[5 * kTimelineSlabs];
 #define IPTQ_TL(k, t) do { } while (0)
 #endif
 
-template <int COLS, int K, int MODE, bool BIAS, int POSTMODE, bool MASK, bool PRE = false>
+// MASKKIND: 0 no per-window mask, 1 the int32 table read beside the bias, 2 one bit per key.
+template <int COLS, int K, int MODE, bool BIAS, int POSTMODE, int MASKKIND, bool PRE = false>
 IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
 {
+    constexpr bool MASK = MASKKIND == 1;
 #ifdef IPTQ_TIMELINE
     const uint64_t t_entry = wall_clock64();
 #endif
@@ -409,6 +412,7 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     const int32_t *__restrict__ bias = I.bias;
     uint8_t *__restrict__ out = I.out;
     static_assert(!MASK || RPW <= COLS, "a slab may cross one wrap of the query index at most");
+    static_assert(MASKKIND != 2 || COLS <= 64, "one 64-bit word per query");
     const uint32_t lw = blockIdx.x - I.first_wg;
     int64_t slab = (int64_t)lw * kRowsWpb + wv;
     if (BIAS && I.share_q != 0) {
@@ -432,6 +436,19 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     const int e_r = lr * COLS;                        // first element of the row in the slab
     const int b_r = e_r >> 2;                         // its 16-byte block
     const int phi = e_r & 3;                          // and its offset inside that block
+
+    // ---- the packed mask: this lane's row takes word [window, query]; loaded now, used after
+    // the slab has been read back from LDS
+    uint64_t mask_word = 0;
+    if (MASKKIND == 2) {
+        const uint32_t row = (uint32_t)(slab * RPW) + (uint32_t)lr;
+        uint32_t rm = 0;
+        if (P.mask_period_rows >= 2)
+            rm = row - (mulhi_u32(row, P.mperiod_magic) >> P.mperiod_sh) * (uint32_t)P.mask_period_rows;
+        const uint32_t w = P.group_rows >= 2 ? mulhi_u32(rm, P.group_magic) >> P.group_sh : rm;
+        const uint32_t q = (rm - w * (uint32_t)P.group_rows) % (uint32_t)COLS;
+        mask_word = I.mask_bits[w * (uint32_t)COLS + q];
+    }
 
     // ---- flat copy of the slab into LDS, bias added on the way.  A partial last slab (the
     // tensor's row count is not a multiple of RPW) reads nothing beyond its last valid
@@ -546,6 +563,25 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
         }
     }
     wave_lds_fence();                                 // the slab area is reused for the output
+
+    if (MASKKIND == 2) {
+        // element e of slot s is key 4 (s K + j) + e - phi: shift the word once so that its bit
+        // sits at the compile-time position 4 s K + e (keys below 0 and beyond the row read zeros;
+        // those elements are minus infinity already)
+        const int sh = 4 * j - phi;
+        const uint64_t aligned = sh >= 0 ? mask_word >> sh : mask_word << (-sh);
+        const uint32_t lo = (uint32_t)aligned, hi = (uint32_t)(aligned >> 32);
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int pos = 4 * s * K + e;
+                if (pos >= 64) continue;              // beyond the word: keys past the row
+                const uint32_t half = pos < 32 ? lo : hi;
+                const uint32_t m = 0u - ((half >> (pos & 31)) & 1u);           // all ones: masked
+                x[s][e] = (int32_t)(((uint32_t)x[s][e] & ~m) | (0x80000000u & m));
+            }
+    }
 
     uint32_t w[SLOTS];                                // four output bytes per block
     bool done = false;                                // wavefront-uniform
@@ -679,7 +715,7 @@ template <int COLS, int K, int MODE, bool BIAS, int POSTMODE>
 __global__ void __launch_bounds__(64 * kRowsWpb)
 softmax_rows_kernel(SoftmaxBatch B)
 {
-    softmax_rows_body<COLS, K, MODE, BIAS, POSTMODE, false>(B);
+    softmax_rows_body<COLS, K, MODE, BIAS, POSTMODE, 0>(B);
 }
 
 // The same with the per-window mask beside the bias: three loads per chunk.  Compiled for five
@@ -689,7 +725,16 @@ template <int COLS, int K, int MODE, int POSTMODE>
 __global__ void __launch_bounds__(64 * kRowsWpb) __attribute__((amdgpu_waves_per_eu(4, 5)))
 softmax_rows_masked_kernel(SoftmaxBatch B)
 {
-    softmax_rows_body<COLS, K, MODE, true, POSTMODE, true>(B);
+    softmax_rows_body<COLS, K, MODE, true, POSTMODE, 1>(B);
+}
+
+// The mask one bit per key (windows of at most 64 tokens): one 8-byte load per lane and two
+// instructions per score instead of a third table.
+template <int COLS, int K, int MODE, int POSTMODE>
+__global__ void __launch_bounds__(64 * kRowsWpb)
+softmax_rows_maskbits_kernel(SoftmaxBatch B)
+{
+    softmax_rows_body<COLS, K, MODE, true, POSTMODE, 2>(B);
 }
 
 // The same with the requantization of the scores folded into Eq. 6 where the parameters allow it
@@ -698,14 +743,14 @@ template <int COLS, int K, int MODE, int POSTMODE>
 __global__ void __launch_bounds__(64 * kRowsWpb)
 softmax_rows_requant_kernel(SoftmaxBatch B)
 {
-    softmax_rows_body<COLS, K, MODE, false, POSTMODE, false, true>(B);
+    softmax_rows_body<COLS, K, MODE, false, POSTMODE, 0, true>(B);
 }
 
 // Launch helper, defined once per row length in softmax_rows_<cols>.hip so that the
 // instantiations compile in parallel.  mode: 0 / 1 / 2 as above; all items share has_bias and
 // has_mask; fold_pre: some item has SoftmaxDev::pre_rowconst.
 template <int COLS, int K>
-hipError_t launch_softmax_rows(const SoftmaxBatch &B, unsigned total_wgs, bool has_bias, bool has_mask,
+hipError_t launch_softmax_rows(const SoftmaxBatch &B, unsigned total_wgs, bool has_bias, int mask_kind,
                                bool fold_pre, int mode, int post_mode, hipStream_t stream);
 
 // The compiled row lengths with their lanes per row: ViT / DeiT at 224^2 (197; 198 with a
@@ -721,21 +766,24 @@ constexpr int64_t kRowsAltMaxElements = 90 * 1000 * 1000;
 // The per-window mask is compiled in for the window sizes of shifted-window attention only
 // (7 x 7 and 12 x 12 tokens), with the bias table beside it.
 constexpr bool rows_mask_compiled(int cols) { return cols == 49 || cols == 144; }
+constexpr bool rows_maskbits_compiled(int cols) { return cols == 49; }
 #define IPTQ_DECLARE_ROWS_LAUNCHER(COLS, K)                                                       \
     template <>                                                                                   \
-    hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &, unsigned, bool, bool, bool, int, int, hipStream_t);
+    hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &, unsigned, bool, int, bool, int, int, hipStream_t);
 IPTQ_ROWS_SHAPES(IPTQ_DECLARE_ROWS_LAUNCHER)
 IPTQ_ROWS_SHAPES_ALT(IPTQ_DECLARE_ROWS_LAUNCHER)
 
 #define IPTQ_ROWS_LAUNCH(COLS, K, MODE, BIAS, PM, MASK)                                           \
     do {                                                                                          \
-        if constexpr (MASK)                                                                       \
+        if constexpr (MASK == 1)                                                                  \
             hipLaunchKernelGGL((softmax_rows_masked_kernel<COLS, K, MODE, PM>), grid, block, 0, stream, B);   \
+        else if constexpr (MASK == 2)                                                             \
+            hipLaunchKernelGGL((softmax_rows_maskbits_kernel<COLS, K, MODE, PM>), grid, block, 0, stream, B); \
         else                                                                                      \
             hipLaunchKernelGGL((softmax_rows_kernel<COLS, K, MODE, BIAS, PM>), grid, block, 0, stream, B);    \
     } while (0)
 
-template <int COLS, int K, bool BIAS, bool MASK>
+template <int COLS, int K, bool BIAS, int MASK>
 static hipError_t launch_rows_b(const SoftmaxBatch &B, unsigned total_wgs, int mode, int post_mode,
                                 hipStream_t stream)
 {
@@ -770,11 +818,16 @@ static hipError_t launch_rows_requant(const SoftmaxBatch &B, unsigned total_wgs,
 }
 
 template <int COLS, int K>
-static hipError_t launch_rows_masked(const SoftmaxBatch &B, unsigned total_wgs, int mode, int post_mode,
-                                     hipStream_t stream)
+static hipError_t launch_rows_masked(const SoftmaxBatch &B, unsigned total_wgs, int mask_kind, int mode,
+                                     int post_mode, hipStream_t stream)
 {
-    if constexpr (rows_mask_compiled(COLS)) return launch_rows_b<COLS, K, true, true>(B, total_wgs, mode, post_mode, stream);
-    else return hipErrorInvalidValue;                 // the dispatcher never asks for it
+    if constexpr (rows_mask_compiled(COLS)) {
+        if (mask_kind == 1) return launch_rows_b<COLS, K, true, 1>(B, total_wgs, mode, post_mode, stream);
+    }
+    if constexpr (rows_maskbits_compiled(COLS)) {
+        if (mask_kind == 2) return launch_rows_b<COLS, K, true, 2>(B, total_wgs, mode, post_mode, stream);
+    }
+    return hipErrorInvalidValue;                      // the dispatcher never asks for it
 }
 
 #ifdef IPTQ_TIMELINE
@@ -793,14 +846,15 @@ static hipError_t launch_rows_masked(const SoftmaxBatch &B, unsigned total_wgs, 
     IPTQ_DEFINE_TIMELINE_READER(COLS, K)                                                          \
     template <>                                                                                   \
     hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &B, unsigned total_wgs,            \
-                                            bool has_bias, bool has_mask, bool fold_pre,          \
+                                            bool has_bias, int mask_kind, bool fold_pre,          \
                                             int mode, int post_mode, hipStream_t stream)          \
     {                                                                                             \
-        if (has_mask) return launch_rows_masked<COLS, K>(B, total_wgs, mode, post_mode, stream);  \
+        if (mask_kind != 0)                                                                       \
+            return launch_rows_masked<COLS, K>(B, total_wgs, mask_kind, mode, post_mode, stream); \
         if (fold_pre && !has_bias && mode != 0 && post_mode != PM_GENERAL)                        \
             return launch_rows_requant<COLS, K>(B, total_wgs, mode, post_mode, stream);           \
-        return has_bias ? launch_rows_b<COLS, K, true, false>(B, total_wgs, mode, post_mode, stream)     \
-                        : launch_rows_b<COLS, K, false, false>(B, total_wgs, mode, post_mode, stream);   \
+        return has_bias ? launch_rows_b<COLS, K, true, 0>(B, total_wgs, mode, post_mode, stream)         \
+                        : launch_rows_b<COLS, K, false, 0>(B, total_wgs, mode, post_mode, stream);       \
     }
 
 }  // namespace iptq

@@ -89,3 +89,29 @@ def gpu_softmax_windowed(scores: np.ndarray, p: ref.SoftmaxParams, bias, period,
     ip.softmax_i32_windowed(d_in, d_bias, period, d_mask, n_w, heads, d_out, rows, cols, lib_softmax(p, algo))
     torch.cuda.synchronize()
     return d_out.cpu().numpy()
+
+
+def gpu_pack_window_mask(mask: np.ndarray):
+    """The library's packing of an int32 window mask; returns (device words as int64, host uint64 view)."""
+    import torch
+    n_w, cols, _ = mask.shape
+    d_mask = torch.from_numpy(np.ascontiguousarray(mask)).cuda()
+    d_bits = torch.full((n_w, cols, (cols + 63) // 64), 0x5A5A5A5A, dtype=torch.int64, device="cuda")
+    ip.pack_window_mask(d_mask, n_w, cols, d_bits)
+    torch.cuda.synchronize()
+    return d_bits, d_bits.cpu().numpy().view(np.uint64)
+
+
+def gpu_softmax_windowed_bits(scores: np.ndarray, p: ref.SoftmaxParams, bias, period, bits: np.ndarray, heads,
+                              algo=0) -> np.ndarray:
+    """bits: uint64 [n_windows, cols, words] on the host (the oracle's packing)."""
+    import torch
+    rows, cols = scores.shape
+    d_in = torch.from_numpy(np.ascontiguousarray(scores)).cuda()
+    d_bias = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias)).cuda()
+    d_bits = torch.from_numpy(np.ascontiguousarray(bits).view(np.int64)).cuda()
+    d_out = torch.full((rows, cols), 0x5A, dtype=torch.int8 if p.out_is_signed else torch.uint8, device="cuda")
+    ip.softmax_i32_windowed_bits(d_in, d_bias, period, d_bits, bits.shape[0], heads, d_out, rows, cols,
+                                 lib_softmax(p, algo))
+    torch.cuda.synchronize()
+    return d_out.cpu().numpy()

@@ -7,7 +7,8 @@ import pytest
 
 import workloads
 from oracle import prepare, ref
-from tests.helpers import gpu_softmax, gpu_softmax_windowed, lib_softmax
+from tests.helpers import (gpu_pack_window_mask, gpu_softmax, gpu_softmax_windowed, gpu_softmax_windowed_bits,
+                           lib_softmax)
 
 pytestmark = pytest.mark.gpu
 INT32_MIN = -(2 ** 31)
@@ -133,6 +134,134 @@ def test_windowed_swin_b_full_size(stage):
     ip.softmax_i32_batch([prob], 1, cols)
     torch.cuda.synchronize()
     assert np.array_equal(d_o.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("n_w,cols", [(4, 49), (3, 7), (2, 64), (2, 65), (1, 144), (5, 130), (1, 1)])
+def test_pack_window_mask_matches_the_oracle(n_w, cols):
+    """The packing kernel against the oracle's plain loops: one, two and three words per query,
+    finite entries and INT32_MIN + 1 count as "not masked", the buffer's other bytes stay."""
+    rng = np.random.default_rng(n_w * 1000 + cols)
+    mask = np.where(rng.random((n_w, cols, cols)) < 0.4, INT32_MIN, 0).astype(np.int32)
+    mask[rng.random(mask.shape) < 0.05] = INT32_MIN + 1
+    mask[rng.random(mask.shape) < 0.05] = -5
+    _, got = gpu_pack_window_mask(mask)
+    assert np.array_equal(got, ref.pack_window_mask(mask))
+
+
+@pytest.mark.parametrize("heads,side", [(4, 14), (3, 14), (8, 21), (1, 14), (6, 28)])
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_windowed_bits_small(heads, side, variant):
+    """The mask one bit per key on the slab route (49 keys, with a bias) and the three-pass route:
+    ragged row counts, masked scores, both output types; bits beyond the row length are ignored."""
+    rng = np.random.default_rng(heads * 1000 + side * 10 + variant + 7)
+    scores, bias, mask = _case(rng, 3, side, heads, drop=int(rng.integers(0, 40)))
+    scores[rng.random(scores.shape) < 0.01] = INT32_MIN
+    bits = ref.pack_window_mask(mask)
+    dirty = bits | np.uint64(0xFFFE000000000000)            # bits 49..63 set: no such keys
+    for signed in (0, 1):
+        p = prepare.softmax_prepare(2.0 ** -6.5, 49, variant, signed)
+        want = ref.softmax_i32_windowed_bits(scores, p, bias, heads * 49, bits, heads)
+        for algo in (0, 1):
+            for b in (bits, dirty):
+                got = gpu_softmax_windowed_bits(scores, p, bias, heads * 49, b, heads, algo=algo)
+                assert np.array_equal(got, want), (heads, side, variant, signed, algo)
+
+
+def test_windowed_bits_dense_random_masks_full_rows_and_no_bias():
+    """Random masks (every bit position used, at every lane offset), a query whose every key is
+    masked although its scores are positive, a mask without a bias, other row lengths with one
+    and with three words per query (three-pass kernel)."""
+    rng = np.random.default_rng(16)
+    heads, t, n_w, images = 2, 49, 5, 4
+    rows = images * n_w * heads * t - 13
+    scores = np.abs(np.rint(rng.standard_normal((rows, t)) * 300)).astype(np.int32) + 1
+    bias = np.rint(rng.standard_normal((heads * t, t)) * 8).astype(np.int32)
+    bias[rng.random(bias.shape) < 0.02] = INT32_MIN
+    mask = np.where(rng.random((n_w, t, t)) < 0.5, INT32_MIN, 0).astype(np.int32)
+    mask[2, 5, :] = INT32_MIN
+    mask[3, :, :] = 0
+    mask[3, np.arange(t), np.arange(t)] = INT32_MIN         # one key per query, a different one each
+    bits = ref.pack_window_mask(mask)
+    for variant in (0, 1):
+        p = prepare.softmax_prepare(2.0 ** -6, t, variant)
+        p.post = ref.Dyadic(1, 0, 3, 0, 255)
+        want = ref.softmax_i32_windowed(scores, p, bias, heads * t, mask, heads)
+        r = ((0 * n_w + 2) * heads + 1) * t + 5
+        assert want[r].tolist() == [3] * t
+        for algo in (0, 1):
+            assert np.array_equal(gpu_softmax_windowed_bits(scores, p, bias, heads * t, bits, heads, algo=algo), want)
+        want = ref.softmax_i32_windowed(scores, p, None, 0, mask, heads)
+        assert np.array_equal(gpu_softmax_windowed_bits(scores, p, None, 0, bits, heads), want)
+    for t2 in (16, 144, 130):
+        rows2 = 2 * 3 * heads * t2 - 5
+        sc = np.rint(rng.standard_normal((rows2, t2)) * 300).astype(np.int32)
+        bi = np.rint(rng.standard_normal((heads * t2, t2)) * 8).astype(np.int32)
+        mk = np.where(rng.random((3, t2, t2)) < 0.3, INT32_MIN, 0).astype(np.int32)
+        p = prepare.softmax_prepare(2.0 ** -6, t2, 1)
+        want = ref.softmax_i32_windowed(sc, p, bi, heads * t2, mk, heads)
+        assert np.array_equal(gpu_softmax_windowed_bits(sc, p, bi, heads * t2, ref.pack_window_mask(mk), heads), want), t2
+
+
+@pytest.mark.parametrize("stage", [0, 1, 2])
+def test_windowed_bits_swin_b_full_size(stage):
+    """Swin-B at batch 64, shifted-window blocks of stages 1-3, the mask packed by the library:
+    the launch the benchmark times, and the batched entry point."""
+    import torch
+    import paper_2511_15369_amd as ip
+    case = workloads.softmax_case("swin_b", stage)
+    heads = workloads.CONFIGS["swin_b"]["heads"][stage]
+    side = workloads.SWIN_B_MAP_SIDE[stage]
+    mask = workloads.shifted_window_mask(side, side)
+    rows, cols = case.scores.shape
+    d_bits, host_bits = gpu_pack_window_mask(mask)
+    assert np.array_equal(host_bits, ref.pack_window_mask(mask))
+    d_s = torch.from_numpy(case.scores).cuda()
+    d_b = torch.from_numpy(case.bias).cuda()
+    for variant in (1, 0):
+        p = prepare.softmax_prepare(case.s_delta, cols, variant)
+        want = ref.softmax_i32_windowed(case.scores, p, case.bias, case.bias_period_rows, mask, heads)
+        d_o = torch.full((rows, cols), 0x5A, dtype=torch.uint8, device="cuda")
+        ip.softmax_i32_windowed_bits(d_s, d_b, case.bias_period_rows, d_bits, mask.shape[0], heads, d_o, rows, cols,
+                                     lib_softmax(p))
+        torch.cuda.synchronize()
+        assert np.array_equal(d_o.cpu().numpy(), want), (stage, variant)
+    d_o = torch.full((rows, cols), 0x5A, dtype=torch.uint8, device="cuda")
+    prob = ip.softmax_problem(d_s, d_b, case.bias_period_rows, d_o, rows, cols, lib_softmax(p), None, mask.shape[0],
+                              heads, d_bits)
+    ip.softmax_i32_batch([prob], 1, cols)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_o.cpu().numpy(), want)
+
+
+def test_windowed_bits_argument_checks():
+    import ctypes
+    import torch
+    import paper_2511_15369_amd as ip
+    t = 49
+    d_s = torch.zeros((98, t), dtype=torch.int32, device="cuda")
+    d_o = torch.zeros((98, t), dtype=torch.uint8, device="cuda")
+    d_m = torch.zeros((2, t, t), dtype=torch.int32, device="cuda")
+    d_w = torch.zeros((2, t, 1), dtype=torch.int64, device="cuda")
+    p = lib_softmax(prepare.softmax_prepare(2.0 ** -6, t, 1))
+    lib = ip.load()
+    fn = lib.iptq_softmax_i32_windowed_bits
+    for n_w, heads in ((0, 1), (1, 0), (-1, 1), (2 ** 30, 4)):
+        rc = fn(d_s.data_ptr(), None, 0, d_w.data_ptr(), n_w, heads, d_o.data_ptr(), 98, t, ctypes.byref(p), None)
+        assert rc == -2, (n_w, heads)
+    rc = fn(d_s.data_ptr(), None, 0, d_w.data_ptr() + 4, 2, 1, d_o.data_ptr(), 98, t, ctypes.byref(p), None)
+    assert rc == -6                                          # words are 8-byte aligned
+    # both forms of the mask in one problem of a batch: refused
+    prob = ip.softmax_problem(d_s, None, 0, d_o, 98, t, p, d_m, 2, 1, d_w)
+    arr = (ip.SoftmaxProblem * 1)(prob)
+    assert lib.iptq_softmax_i32_batch(arr, 1, t, None) == -3
+    pk = lib.iptq_pack_window_mask
+    assert pk(d_m.data_ptr(), -1, t, d_w.data_ptr(), None) == -2
+    assert pk(d_m.data_ptr(), 2, 0, d_w.data_ptr(), None) == -2
+    assert pk(None, 2, t, d_w.data_ptr(), None) == -1
+    assert pk(d_m.data_ptr(), 2, t, d_m.data_ptr(), None) == -3           # overlap
+    assert pk(d_m.data_ptr(), 0, t, None, None) == 0
+    torch.cuda.synchronize()
+    assert not d_o.any() and not d_w.any()                   # nothing was launched
 
 
 def test_windowed_argument_checks():
