@@ -61,6 +61,35 @@ def test_other_variant_at_full_size():
         assert np.array_equal(u.d_y.cpu().numpy(), ref.gelu_i8(gc.x.reshape(-1), gp))
 
 
+@pytest.mark.parametrize("name,unit", [("vit_b", 3), ("swin_b", 0)])
+def test_six_bit_and_second_degree_forms_at_full_size(name, unit):
+    """The softmax forms the benchmark times beside the default one, on the two target shapes at
+    full size: 6-bit probabilities (b = 6 of Eq. 15), the int8 output that clips 128 to 127, the
+    signed codes p - 128, and the second-degree Bit-exp."""
+    from tests.helpers import gpu_softmax
+    sc = workloads.softmax_case(name, unit)
+    cols = sc.scores.shape[1]
+    forms = []
+    p6 = prepare.softmax_prepare(sc.s_delta, cols, sc.variant)
+    p6.out_bits = 6
+    p6.post = ref.Dyadic(1, 0, 0, 0, 63)
+    forms.append(("out_bits 6", p6))
+    p6b = prepare.softmax_prepare(sc.s_delta, cols, sc.variant)
+    p6b.out_bits, p6b.m_bits = 6, 29                       # the form the benchmark times: M - (b - 1) = 24
+    p6b.post = ref.Dyadic(1, 0, 0, 0, 63)
+    forms.append(("out_bits 6, M 29", p6b))
+    forms.append(("int8 clip", prepare.softmax_prepare(sc.s_delta, cols, sc.variant, 1)))
+    ps = prepare.softmax_prepare(sc.s_delta, cols, sc.variant, 1)
+    ps.post = ref.Dyadic(1, 0, -128, -128, 127)
+    forms.append(("p - 128", ps))
+    forms.append(("second degree", prepare.softmax_prepare(sc.s_delta, cols, 2)))
+    for what, p in forms:
+        print("full-size parity", name, unit, what, flush=True)
+        want = ref.softmax_i32(sc.scores, p, sc.bias, sc.bias_period_rows)
+        got = gpu_softmax(sc.scores, p, sc.bias, sc.bias_period_rows, algo=4)
+        assert np.array_equal(got, want), (name, unit, what)
+
+
 def test_batched_launch_configuration_at_full_size():
     """bench.py's batched form: the four Swin-B stages through one softmax and one GELU call."""
     import torch
