@@ -67,14 +67,19 @@ debug_bit_exp_kernel(const int32_t *delta, uint32_t *out32, uint32_t *out16, int
     if (P.variant == 0) {
         out32[i] = bit_exp_dev<0, true>(xa, lower, 0, P);
         out32[i + 1] = bit_exp_dev<0, true>(xb, lower, 0, P);
-    } else {
+    } else if (P.variant == 1) {
         out32[i] = bit_exp_dev<1, true>(xa, lower, 0, P);
         out32[i + 1] = bit_exp_dev<1, true>(xb, lower, 0, P);
+    } else {
+        out32[i] = bit_exp_dev<2, true>(xa, lower, 0, P);
+        out32[i + 1] = bit_exp_dev<2, true>(xb, lower, 0, P);
     }
     if (P.mode16 == 0) {
         out16[i] = out16[i + 1] = 0xFFFFFFFFu;
     } else {
-        const u16x2 e = P.variant == 0 ? bit_exp_pair<0, true>(xa, xb, 0, P) : bit_exp_pair<1, true>(xa, xb, 0, P);
+        const u16x2 e = P.variant == 0 ? bit_exp_pair<0, true>(xa, xb, 0, P)
+                      : P.variant == 1 ? bit_exp_pair<1, true>(xa, xb, 0, P)
+                                       : bit_exp_pair<2, true>(xa, xb, 0, P);
         out16[i] = e.x;
         out16[i + 1] = e.y;
     }

@@ -151,8 +151,7 @@ int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int
     out->mode16 = 0;
     out->mg24 = 0;
     out->t16 = 0;
-    if (p->variant != IPTQ_SOFTMAX_BITEXP_DEGREE2 && D <= 32767 && i0n < (1 << 15) &&
-        out->p_shift <= 24 && i0n >= ((int64_t)1 << p->out_bits)) {
+    if (D <= 32767 && i0n < (1 << 15) && out->p_shift <= 24 && i0n >= ((int64_t)1 << p->out_bits)) {
         for (int t = 0; t <= 12; ++t) {
             const uint64_t two = (uint64_t)1 << (32 - t);
             const uint64_t mg = two / (uint64_t)p->i0 + 1;
@@ -170,7 +169,8 @@ int plan_softmax(const iptq_softmax_params_t *p, int64_t rows, int32_t cols, int
     }
     out->pre_rowconst = 0;
     out->pre_dmax = 0;
-    if (out->pre_mode == 1 && out->mode16 != 0 && p->pre_s <= 31) {
+    // (the folded requantization is instantiated for the first-degree exponentials only)
+    if (out->pre_mode == 1 && out->mode16 != 0 && p->pre_s <= 31 && p->variant != IPTQ_SOFTMAX_BITEXP_DEGREE2) {
         const int64_t two_s = (int64_t)1 << p->pre_s;
         const int64_t dmax = (D * two_s + p->pre_m - 1) / p->pre_m;
         if (dmax < ((int64_t)1 << 24) && dmax * p->pre_m + two_s <= ((int64_t)1 << 32)) {

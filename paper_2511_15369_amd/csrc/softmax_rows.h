@@ -264,7 +264,16 @@ IPTQ_DEV u16x2 bit_exp_pair_of_deltas(s16x2 dl, const SoftmaxDev &P)
     const unsigned short i0 = (unsigned short)P.i0;
     const s16x2 nr = (s16x2)(q * (u16x2){i0, i0} - n);         // -r in (-i0, 0]
     s16x2 fr = nr >> 1;                                        // Eq. 10
-    if (VARIANT >= 1) fr = fr + (nr >> 3) + (nr >> 4);         // Eq. 13 (the second-degree form never runs packed)
+    if (VARIANT >= 1) fr = fr + (nr >> 3) + (nr >> 4);         // Eq. 13
+    if (VARIANT == 2) {
+        // Eq. 11 with D = 2: + floor(y^2 / (2 i0)).  |y| < 0.6875 i0 < 2^15, so the square needs a
+        // 32-bit lane per element (24-bit multiply, multiply-high by the reciprocal of 2 i0); the
+        // quotient is below i0 / 4 and goes back into the packed pair.
+        const int32_t ya = fr.x, yb = fr.y;
+        const uint32_t ta = mulhi_u32((uint32_t)__mul24(ya, ya), P.d2_magic) >> P.d2_sh;
+        const uint32_t tb = mulhi_u32((uint32_t)__mul24(yb, yb), P.d2_magic) >> P.d2_sh;
+        fr = fr + (s16x2){(short)ta, (short)tb};
+    }
     const unsigned short sc = (unsigned short)(1u << P.n_shift), one = (unsigned short)P.i0n;
     const u16x2 base = (u16x2)fr * (u16x2){sc, sc} + (u16x2){one, one};   // Eq. 14, << N
     return base >> q;                                          // Eq. 9 (q <= 15)
@@ -650,8 +659,8 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     const bool any_low = __builtin_amdgcn_ballot_w64(low_row) != 0;
 
     if (P.variant == 0) softmax_slab_math<K, SLOTS, MODE, 0, POSTMODE>(x, w, mx, lower, any_low, lut, P);
-    else if (MODE != 0 || P.variant == 1) softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE>(x, w, mx, lower, any_low, lut, P);
-    else softmax_slab_math<K, SLOTS, MODE, 2, POSTMODE>(x, w, mx, lower, any_low, lut, P);   // 32-bit lanes only
+    else if (P.variant == 1) softmax_slab_math<K, SLOTS, MODE, 1, POSTMODE>(x, w, mx, lower, any_low, lut, P);
+    else softmax_slab_math<K, SLOTS, MODE, 2, POSTMODE>(x, w, mx, lower, any_low, lut, P);
     }
     if (POSTMODE == PM_NONE && P.post_xor != 0) {     // signed output around the zero-point -128
 #pragma unroll
