@@ -473,9 +473,16 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     // the per-window mask: at most two runs of entries (MaskRuns)
     MaskRuns MR = {};
     if (MASK) MR = mask_runs_of_slab<COLS, RPW>(I.mask, (uint32_t)(slab * RPW), P);
-    auto copy_in = [&](auto tag, auto straddle_tag) {
+    // EXACT: the bias is added with the minus-infinity rule per score (four lane-ops).  Otherwise
+    // with the saturating sum alone, which is the same value unless a score or a table entry is
+    // INT32_MIN; the smallest operand is tracked beside it (two lane-ops per score in all), and
+    // the function returns whether any lane of the wavefront met INT32_MIN, in which case the
+    // caller runs the exact form over the slab again.
+    auto copy_in = [&](auto tag, auto straddle_tag, auto exact_tag) -> bool {
         constexpr bool PARTIAL = decltype(tag)::value;
         constexpr bool STRADDLE = decltype(straddle_tag)::value;
+        constexpr bool EXACT = decltype(exact_tag)::value;
+        i32x4 lowest = {0, 0, 0, 0};
         i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
         i32x4 first4 = {0, 0, 0, 0};
         if (BIAS && STRADDLE) first4 = load_i32x4(bias);
@@ -540,15 +547,47 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
                     v = add_table_chunk(v, mv);
                 }
             } else if (BIAS) {
-                v = add_table_chunk(v, bv);
+                if (EXACT) {
+                    v = add_table_chunk(v, bv);
+                } else {
+                    lowest.x = min(min(lowest.x, v.x), bv.x);
+                    lowest.y = min(min(lowest.y, v.y), bv.y);
+                    lowest.z = min(min(lowest.z, v.z), bv.z);
+                    lowest.w = min(min(lowest.w, v.w), bv.w);
+                    v.x = sat_add_i32(v.x, bv.x);
+                    v.y = sat_add_i32(v.y, bv.y);
+                    v.z = sat_add_i32(v.z, bv.z);
+                    v.w = sat_add_i32(v.w, bv.w);
+                }
             }
             lds4[li] = v;
         }
         wave_lds_fence();
+        return !EXACT &&
+               __builtin_amdgcn_ballot_w64(min(min(lowest.x, lowest.y), min(lowest.z, lowest.w)) == kI32Min) != 0;
     };
-    if (partial) copy_in(std::true_type{}, std::integral_constant<bool, BIAS>{});
-    else if (straddle) copy_in(std::false_type{}, std::true_type{});
-    else copy_in(std::false_type{}, std::false_type{});
+    // a partial slab and a per-window table take the exact form at once
+    constexpr bool FAST_ADD = BIAS && !MASK;
+    bool redo = false;                                // wavefront-uniform
+    if (partial) copy_in(std::true_type{}, std::integral_constant<bool, BIAS>{}, std::true_type{});
+    else if (straddle) redo = copy_in(std::false_type{}, std::true_type{}, std::integral_constant<bool, !FAST_ADD>{});
+    else redo = copy_in(std::false_type{}, std::false_type{}, std::integral_constant<bool, !FAST_ADD>{});
+    if (FAST_ADD && redo) {
+        // Some score or table entry of this slab is INT32_MIN: the slab once more with the exact
+        // addition, one chunk at a time (a rare path: it must cost no registers, not no time).
+        i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
+        const i32x4 first4 = load_i32x4(bias);
+#pragma unroll 1
+        for (int i = 0; i < (IN_CHUNKS + 63) / 64; ++i) {
+            const int li = min(i * 64 + lane, IN_CHUNKS - 1);
+            const i32x4 v = stream_load_i32x4(src + 4 * li);
+            uint32_t o = boff + 4u * (uint32_t)li;
+            if (o >= pe) o -= pe;
+            const i32x4 bv = straddle ? bias_chunk_wrapping(bias, o, pe, first4) : load_i32x4(bias + o);
+            lds4[li] = add_table_chunk(v, bv);
+        }
+        wave_lds_fence();
+    }
 
     IPTQ_TL(1, wall_clock64());
     // ---- this lane's blocks; elements outside the row become "minus infinity"

@@ -64,3 +64,29 @@ def test_table_entry_int32_min_masks_positive_scores(cols, period):
         assert want[3 % period].max() > 5
         for algo in (0, 1, 2, 3):
             assert np.array_equal(gpu_softmax(scores, p, bias, period, algo=algo), want), (variant, algo)
+
+
+@pytest.mark.parametrize("heads", [4, 3])
+def test_bias_with_rare_minus_infinity_operands(heads):
+    """Most slabs hold no INT32_MIN at all and a few do (the kernel adds the table with the plain
+    saturating sum and repeats a slab with the minus-infinity rule when one of its operands is
+    INT32_MIN): masked scores under positive table entries, masked table entries under positive
+    scores, sums that saturate at both ends, in a tensor of several thousand slabs."""
+    rng = np.random.default_rng(40 + heads)
+    cols, period = 49, heads * 49
+    rows = 5000 * 32 + 11
+    scores = np.rint(rng.standard_normal((rows, cols)) * 600).astype(np.int32)
+    bias = np.rint(rng.standard_normal((period, cols)) * 30).astype(np.int32)
+    bias[5, 7] = INT32_MIN                                   # one masked table entry: every 32-row slab that holds table row 5
+    bias[6, 3] = 2 ** 31 - 1
+    bias[7, 3] = INT32_MIN + 1
+    hit = rng.random(scores.shape) < 2e-5
+    scores[hit] = INT32_MIN
+    scores[rng.random(scores.shape) < 1e-5] = 2 ** 31 - 1
+    scores[rng.random(scores.shape) < 1e-5] = INT32_MIN + 1
+    scores[6, 3] = 2 ** 31 - 5                                # saturates upward with bias[6, 3]
+    scores[7, 3] = -9                                         # with bias[7, 3] the sum clamps at INT32_MIN, which then counts as minus infinity
+    for variant in (0, 1):
+        p = prepare.softmax_prepare(2.0 ** -7, cols, variant)
+        want = ref.softmax_i32(scores, p, bias, period)
+        assert np.array_equal(gpu_softmax(scores, p, bias, period, algo=4), want), (heads, variant)
