@@ -182,7 +182,7 @@ int iptq_requant(const int32_t *d_in, void *d_out, int64_t n, int32_t out_is_sig
  * 16-byte grid); an additive table of any size is fused (a little faster when
  * bias_period_rows * cols is a multiple of 4, as with 4, 8, 16 or 32 Swin heads), except a
  * table with fewer rows than one wavefront's slab (64 rows divided by the lanes per row: 32 at
- * 49 columns, 8 or 16 at 197), or of 2^31 entries and more, which takes the three-pass kernel
+ * 49 columns, 8 or 16 at 197), or of 2^30 entries and more, which takes the three-pass kernel
  * (about a sixth of the speed).
  */
 int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias, int64_t bias_period_rows,

@@ -44,6 +44,12 @@ __device__ __forceinline__ i32x4 load_i32x4(const int32_t *p)
 {
     return *reinterpret_cast<const i32x4_a4 *>(p);
 }
+// The same at a byte offset below 2^32 from a wavefront-uniform base: compiles to the form with a
+// scalar base and a 32-bit vector offset (no 64-bit address arithmetic per load).
+__device__ __forceinline__ i32x4 load_i32x4_at(const int32_t *base, uint32_t byte_offset)
+{
+    return *reinterpret_cast<const i32x4_a4 *>(reinterpret_cast<const char *>(base) + byte_offset);
+}
 __device__ __forceinline__ void stream_store_bytes16(u32x4 v, uint8_t *p)
 {
     __builtin_nontemporal_store(v, reinterpret_cast<u32x4_a1 *>(p));

@@ -203,9 +203,9 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             // off the 16-byte grid need nothing but their natural alignment
             const bool aligned =
                 ((reinterpret_cast<uintptr_t>(c.scores) | reinterpret_cast<uintptr_t>(c.bias)) & 3) == 0;
-            // the fused bias wraps at most once per slab, and its offsets are 32-bit
+            // the fused bias wraps at most once per slab, and its byte offsets are 32-bit
             const bool bias_ok = !has_bias || ((int64_t)c.P.bias_period_rows * cols >= 4 &&
-                                       (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 31) &&
+                                       (int64_t)c.P.bias_period_rows * cols < ((int64_t)1 << 30) &&
                                                c.P.bias_period_rows >= rpw);
             const bool slab_algo = c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_SLAB;
             const int has_mask = c.mask != nullptr ? 1 : (c.mask_bits != nullptr ? 2 : 0);

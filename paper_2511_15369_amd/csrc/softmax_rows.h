@@ -411,7 +411,9 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     __shared__ uint8_t lut_all[kRowsWpb][POSTMODE == PM_GENERAL ? kPostLutBytes : 4];
 
     const int lane = threadIdx.x & 63;
-    const int wv = threadIdx.x >> 6;
+    // (the wavefront index as a scalar: everything derived from it - the slab, its table offsets,
+    // the runs of mask entries - is then computed on the scalar unit)
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     int it = 0;                                       // which problem this workgroup serves
     for (int i = 1; i < B.n_items; ++i)
         if (blockIdx.x >= B.item[i].first_wg) it = i;
@@ -534,7 +536,7 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
             if (BIAS) {
                 uint32_t o = boff + 4u * (uint32_t)li;
                 if (o >= pe) o -= pe;
-                bv = STRADDLE ? bias_chunk_wrapping(bias, o, pe, first4) : load_i32x4(bias + o);
+                bv = STRADDLE ? bias_chunk_wrapping(bias, o, pe, first4) : load_i32x4_at(bias, 4u * o);   // table below 4 GiB
             }
             if (MASK) {
                 const i32x4 mv = mask_chunk(I.mask, MR, 4u * (uint32_t)li);
