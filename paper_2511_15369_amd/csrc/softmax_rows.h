@@ -258,8 +258,9 @@ IPTQ_DEV u16x2 bit_exp_pair_of_deltas(s16x2 dl, const SoftmaxDev &P)
     const u16x2 n = (u16x2)((s4 - dl) - s1);                   // -Qp of Eq. 7
     u16x2 ns = n;
     if (SHIFTED) ns = n << (unsigned short)P.t16;
-    const uint32_t qa = mulhi_u24((uint32_t)ns.x, P.mg24);     // Eq. 8: n div i0
-    const uint32_t qb = mulhi_u24((uint32_t)ns.y, P.mg24);
+    const uint32_t nw = __builtin_bit_cast(uint32_t, ns);
+    const uint32_t qa = mulhi_u24(nw & 0xffffu, P.mg24);       // Eq. 8: n div i0
+    const uint32_t qb = mulhi_u24(__builtin_amdgcn_ubfe(nw, 16, 16), P.mg24);   // (a field extract folds into the multiply's operand select)
     const u16x2 q = {(unsigned short)qa, (unsigned short)qb};
     const unsigned short i0 = (unsigned short)P.i0;
     const s16x2 nr = (s16x2)(q * (u16x2){i0, i0} - n);         // -r in (-i0, 0]
