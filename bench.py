@@ -155,12 +155,19 @@ def build_units(name, batch=None, seed=0, variant_override=None, sets=1):
     return [Unit(name, u, batch, seed, variant_override, sets) for u in range(workloads.CONFIGS[name]["units"])]
 
 
-def time_steps(fn, reps, before_each=None):
+MARKERS = False      # --markers: a roctx range around every timed region, named by its leg
+
+
+def time_steps(fn, reps, before_each=None, leg=None):
     """reps calls of fn() back to back on the launch stream with an event between them.
-    Returns (mean ms over the whole region, median ms, min ms of the single calls)."""
+    Returns (mean ms over the whole region, median ms, min ms of the single calls).  With
+    --markers the region sits inside a roctx range called `leg`, so that a rocprofv3 run with
+    --kernel-trace --marker-trace can tell which launches belong to which line of the output."""
     import torch
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
     torch.cuda.synchronize()
+    if MARKERS and leg:
+        torch.cuda.nvtx.range_push(leg)
     ev[0].record()
     for i in range(reps):
         if before_each is not None:
@@ -168,6 +175,8 @@ def time_steps(fn, reps, before_each=None):
         fn()
         ev[i + 1].record()
     torch.cuda.synchronize()
+    if MARKERS and leg:
+        torch.cuda.nvtx.range_pop()
     each = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
     return ev[0].elapsed_time(ev[reps]) / reps, each[len(each) // 2], each[0]
 
@@ -186,8 +195,8 @@ def warm(fn, seconds=0.2):
     torch.cuda.synchronize()
 
 
-def time_region(fn, reps):
-    return time_steps(fn, reps)[0]
+def time_region(fn, reps, leg=None):
+    return time_steps(fn, reps, leg=leg)[0]
 
 
 def pct(gbps):
@@ -223,7 +232,7 @@ def measure_fused(steps):
     res = {}
     for name, fn in (("softmax_pre_requant", softmax_pre), ("gelu_i32", gelu_i32)):
         warm(fn)
-        mean, med, mn = time_steps(fn, steps)
+        mean, med, mn = time_steps(fn, steps, leg="fused_requant/" + name)
         el = units[0].softmax_elements
         gb = SOFTMAX_BYTES_PER_EL * el / (mean / len(units) * 1e-3) / 1e9
         res[name] = {"elements": el, "avg_launch_us": mean / len(units) * 1e3,
@@ -268,7 +277,7 @@ def measure_softmax_forms(steps):
                 ip.softmax_i32(u.d_scores, None, 0, o8 if signed else u.d_probs, u.rows, u.cols, p)
 
         warm(fn)
-        mean, med, mn = time_steps(fn, steps)
+        mean, med, mn = time_steps(fn, steps, leg="softmax_forms/" + kind)
         gb = SOFTMAX_BYTES_PER_EL * el / (mean / len(units) * 1e-3) / 1e9
         res[kind] = {"avg_launch_us": mean / len(units) * 1e3, "median_launch_us": med / len(units) * 1e3,
                      "min_launch_us": mn / len(units) * 1e3, "gbps": gb, "pct_of_hbm_peak": pct(gb)}
@@ -297,7 +306,7 @@ def measure_gelu_per_element(steps):
                 ip.gelu_i8(u.d_x, u.d_y, u.gelu_n, gp)
 
         warm(fn)
-        mean, med, mn = time_steps(fn, steps)
+        mean, med, mn = time_steps(fn, steps, leg="gelu_per_element/degree_%d" % (2 if variant == 0 else 4))
         gb = GELU_BYTES_PER_EL * units[0].gelu_n / (mean / len(units) * 1e-3) / 1e9
         res["degree_%d" % (2 if variant == 0 else 4)] = {
             "avg_launch_us": mean / len(units) * 1e3, "median_launch_us": med / len(units) * 1e3,
@@ -344,7 +353,7 @@ def measure_swin_shifted(steps):
         out = {}
         for name, f in (("bias_and_mask", fn), ("bias_and_mask_bits", bits), ("bias_only", plain)):
             warm(f)
-            mean, med, mn = (t / 4 for t in time_steps(f, steps))
+            mean, med, mn = (t / 4 for t in time_steps(f, steps, leg="swin_b_shifted_windows/stage_%d/%s" % (s + 1, name)))
             gb = SOFTMAX_BYTES_PER_EL * u.softmax_elements / (mean * 1e-3) / 1e9
             out[name] = {"avg_launch_us": mean * 1e3, "median_launch_us": med * 1e3, "min_launch_us": mn * 1e3,
                          "gbps": gb, "pct_of_hbm_peak": pct(gb)}
@@ -375,7 +384,7 @@ def measure_row_lengths(steps):
                 ip.softmax_i32(x, None, 0, y, rows, cols, sp)
 
         warm(fn, 0.1)
-        ms = time_region(fn, max(1, steps // 2)) / len(ins)
+        ms = time_region(fn, max(1, steps // 2), leg="row_lengths/%d" % cols) / len(ins)
         el = rows * cols
         res[str(cols)] = {"rows": rows, "kernel": ip.softmax_kernel_family(cols),
                           "avg_launch_us": ms * 1e3,
@@ -442,7 +451,11 @@ def main():
                     choices=["deit_t", "vit_s", "vit_b", "swin_b", "swin_s_det"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the other benchmark configurations")
+    ap.add_argument("--markers", action="store_true",
+                    help="a roctx range around every timed region (for rocprofv3 --marker-trace)")
     args = ap.parse_args()
+    global MARKERS
+    MARKERS = args.markers
     if args.gpus != 1:
         print("bench.py measures one GPU only: softmax rows and GELU elements are independent, so "
               "the path has no multi-GPU form to time (run with --gpus 1)", file=sys.stderr)
@@ -496,10 +509,10 @@ def main():
                 step()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            ms, med, mn = time_steps(step, args.steps, rotate)
+            ms, med, mn = time_steps(step, args.steps, rotate, leg=name + "/step")
             wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-            sm = time_steps(softmax_only, args.steps, rotate)
-            ge = time_steps(gelu_only, args.steps, rotate)
+            sm = time_steps(softmax_only, args.steps, rotate, leg=name + "/softmax")
+            ge = time_steps(gelu_only, args.steps, rotate, leg=name + "/gelu")
             return ms, med, mn, wall_ms, sm, ge
 
         ms, med, mn, wall_ms, sm_t, ge_t = timed()
@@ -528,9 +541,9 @@ def main():
                 for u in units:
                     u.set_variants(v)
                 step()
-                vms, vmed, vmn = time_steps(step, args.steps, rotate)
-                vsm = time_steps(softmax_only, args.steps, rotate)
-                vge = time_steps(gelu_only, args.steps, rotate)
+                vms, vmed, vmn = time_steps(step, args.steps, rotate, leg="%s/variant_%d/step" % (name, v))
+                vsm = time_steps(softmax_only, args.steps, rotate, leg="%s/variant_%d/softmax" % (name, v))
+                vge = time_steps(gelu_only, args.steps, rotate, leg="%s/variant_%d/gelu" % (name, v))
                 res["variants"]["softmax_%d_gelu_%d" % (v, v)] = {
                     "ms_per_step": vms, "median_ms_per_step": vmed, "min_ms_per_step": vmn,
                     "value": (sm_el + ge_el) / (vms * 1e-3),
@@ -556,8 +569,8 @@ def main():
 
             for _ in range(3):
                 step_batched()
-            bms = time_region(step_batched, args.steps)
-            bsm = time_region(lambda: ip.softmax_i32_batch(sm_probs, n, cols), args.steps)
+            bms = time_region(step_batched, args.steps, leg=name + "/batched/step")
+            bsm = time_region(lambda: ip.softmax_i32_batch(sm_probs, n, cols), args.steps, leg=name + "/batched/softmax")
             res["batched"] = {"what": "all units of the workload in one launch per function: a throughput "
                                       "figure, not an inference schedule (the units depend on each other)",
                               "ms_per_step": bms, "value": (sm_el + ge_el) / (bms * 1e-3),
@@ -579,7 +592,7 @@ def main():
             with torch.cuda.graph(graph):
                 step()
             graph.replay()
-            gms = time_region(graph.replay, args.steps)
+            gms = time_region(graph.replay, args.steps, leg=name + "/graph_replay")
             res["graph_replay"] = {"ms_per_step": gms, "value": (sm_el + ge_el) / (gms * 1e-3),
                                    "pct_of_hbm_peak": pct(alg_bytes / (gms * 1e-3) / 1e9)}
             del graph
@@ -596,7 +609,7 @@ def main():
                 ip.requant(u.d_scores.view(-1), u.d_probs.view(-1), u.softmax_elements, 0, dy)
 
         warm(requant_all, 0.05)
-        rq = time_steps(requant_all, max(1, args.steps // 2), rotate)
+        rq = time_steps(requant_all, max(1, args.steps // 2), rotate, leg=name + "/stream_ceiling")
         res["stream_ceiling"] = {"what": "iptq_requant (int32 -> uint8, the softmax's 5 B/element mix) over the "
                                          "same score tensors, one launch per unit",
                                  "gbps": SOFTMAX_BYTES_PER_EL * sm_el / (rq[0] * 1e-3) / 1e9,

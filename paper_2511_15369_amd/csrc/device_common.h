@@ -138,6 +138,15 @@ IPTQ_DEV int32_t clamp_i32(int32_t v, int32_t lo, int32_t hi)
     return r;
 }
 
+// (mask & a) | (~mask & b) in one instruction (written out, the compiler turns a select on a
+// single bit into a test, a compare and a conditional move per element)
+IPTQ_DEV int32_t select_bits_i32(uint32_t mask, int32_t a, int32_t b)
+{
+    int32_t r;
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(r) : "v"(mask), "v"(a), "v"(b));
+    return r;
+}
+
 IPTQ_DEV int32_t sat_add_i32(int32_t a, int32_t b)
 {
     return __builtin_elementwise_add_sat(a, b);

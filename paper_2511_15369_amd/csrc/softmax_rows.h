@@ -629,8 +629,8 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
                 const int pos = 4 * s * K + e;
                 if (pos >= 64) continue;              // beyond the word: keys past the row
                 const uint32_t half = pos < 32 ? lo : hi;
-                const uint32_t m = 0u - ((half >> (pos & 31)) & 1u);           // all ones: masked
-                x[s][e] = (int32_t)(((uint32_t)x[s][e] & ~m) | (0x80000000u & m));
+                const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int32_t)half, pos & 31, 1);   // all ones: masked
+                x[s][e] = select_bits_i32(m, kI32Min, x[s][e]);
             }
     }
 
