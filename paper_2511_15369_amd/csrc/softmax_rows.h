@@ -249,35 +249,65 @@ IPTQ_DEV uint32_t mulhi_u24(uint32_t a, uint32_t b)   // both below 2^24: bits 4
 // SoftmaxDev::p16): D <= 32767, n_max <= 65535 >> t16, i0 << N < 2^15 (so q <= 15 at the
 // clamp), divider multiplier mg24 < 2^24 exact for (n << t16).
 // From the two stabilised scores of Eq. 6 (any value in [-32768, 0]) on.
-template <int VARIANT, bool SHIFTED>
-IPTQ_DEV u16x2 bit_exp_pair_of_deltas(s16x2 dl, const SoftmaxDev &P)
+// N = 2: one pair; N = 4: the two pairs of a 16-byte block side by side, every packed step as two
+// independent instructions back to back (a single pair is one dependent chain, which leaves the
+// vector unit waiting on itself when few wavefronts share it, as at the end of a launch).
+template <int N> struct Packed16;
+template <> struct Packed16<2> {
+    typedef s16x2 S;
+    typedef u16x2 U;
+    typedef uint32_t W __attribute__((ext_vector_type(1)));    // the same bits as 32-bit words
+};
+template <> struct Packed16<4> {
+    typedef short S __attribute__((ext_vector_type(4)));
+    typedef unsigned short U __attribute__((ext_vector_type(4)));
+    typedef uint32_t W __attribute__((ext_vector_type(2)));
+};
+
+template <int VARIANT, bool SHIFTED, int N>
+IPTQ_DEV typename Packed16<N>::U bit_exp_of_deltas(typename Packed16<N>::S dl, const SoftmaxDev &P)
 {
+    typedef typename Packed16<N>::S S;
+    typedef typename Packed16<N>::U U;
     const short nd = (short)(-P.d_clamp);
-    dl = __builtin_elementwise_max(dl, (s16x2){nd, nd});       // Eq. 6 with the clamp at -D
-    const s16x2 s1 = dl >> 1, s4 = dl >> 4;
-    const u16x2 n = (u16x2)((s4 - dl) - s1);                   // -Qp of Eq. 7
-    u16x2 ns = n;
+    dl = __builtin_elementwise_max(dl, (S)nd);                 // Eq. 6 with the clamp at -D
+    const S s1 = dl >> 1, s4 = dl >> 4;
+    const U n = (U)((s4 - dl) - s1);                           // -Qp of Eq. 7
+    U ns = n;
     if (SHIFTED) ns = n << (unsigned short)P.t16;
-    const uint32_t nw = __builtin_bit_cast(uint32_t, ns);
-    const uint32_t qa = mulhi_u24(nw & 0xffffu, P.mg24);       // Eq. 8: n div i0
-    const uint32_t qb = mulhi_u24(__builtin_amdgcn_ubfe(nw, 16, 16), P.mg24);   // (a field extract folds into the multiply's operand select)
-    const u16x2 q = {(unsigned short)qa, (unsigned short)qb};
+    U q;
+#pragma unroll
+    for (int i = 0; i < N / 2; ++i) {                          // Eq. 8: n div i0, per 32-bit word of the vector
+        const uint32_t nw = __builtin_bit_cast(typename Packed16<N>::W, ns)[i];
+        q[2 * i] = (unsigned short)mulhi_u24(nw & 0xffffu, P.mg24);
+        // (a field extract folds into the multiply's operand select)
+        q[2 * i + 1] = (unsigned short)mulhi_u24(__builtin_amdgcn_ubfe(nw, 16, 16), P.mg24);
+    }
     const unsigned short i0 = (unsigned short)P.i0;
-    const s16x2 nr = (s16x2)(q * (u16x2){i0, i0} - n);         // -r in (-i0, 0]
-    s16x2 fr = nr >> 1;                                        // Eq. 10
+    const S nr = (S)(q * (U)i0 - n);                           // -r in (-i0, 0]
+    S fr = nr >> 1;                                            // Eq. 10
     if (VARIANT >= 1) fr = fr + (nr >> 3) + (nr >> 4);         // Eq. 13
     if (VARIANT == 2) {
         // Eq. 11 with D = 2: + floor(y^2 / (2 i0)).  |y| < 0.6875 i0 < 2^15, so the square needs a
         // 32-bit lane per element (24-bit multiply, multiply-high by the reciprocal of 2 i0); the
-        // quotient is below i0 / 4 and goes back into the packed pair.
-        const int32_t ya = fr.x, yb = fr.y;
-        const uint32_t ta = mulhi_u32((uint32_t)__mul24(ya, ya), P.d2_magic) >> P.d2_sh;
-        const uint32_t tb = mulhi_u32((uint32_t)__mul24(yb, yb), P.d2_magic) >> P.d2_sh;
-        fr = fr + (s16x2){(short)ta, (short)tb};
+        // quotient is below i0 / 4 and goes back into the packed vector.
+        S t;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int32_t y = fr[i];
+            t[i] = (short)(mulhi_u32((uint32_t)__mul24(y, y), P.d2_magic) >> P.d2_sh);
+        }
+        fr = fr + t;
     }
     const unsigned short sc = (unsigned short)(1u << P.n_shift), one = (unsigned short)P.i0n;
-    const u16x2 base = (u16x2)fr * (u16x2){sc, sc} + (u16x2){one, one};   // Eq. 14, << N
+    const U base = (U)fr * (U)sc + (U)one;                     // Eq. 14, << N
     return base >> q;                                          // Eq. 9 (q <= 15)
+}
+
+template <int VARIANT, bool SHIFTED>
+IPTQ_DEV u16x2 bit_exp_pair_of_deltas(s16x2 dl, const SoftmaxDev &P)
+{
+    return bit_exp_of_deltas<VARIANT, SHIFTED, 2>(dl, P);
 }
 
 template <int VARIANT, bool SHIFTED>
@@ -288,17 +318,34 @@ IPTQ_DEV u16x2 bit_exp_pair(int32_t xa, int32_t xb, int32_t mx, const SoftmaxDev
     return bit_exp_pair_of_deltas<VARIANT, SHIFTED>(__builtin_amdgcn_cvt_pk_i16(da, db), P);   // saturating pack
 }
 
-// The same with the requantization of the scores folded in (SoftmaxDev::pre_rowconst): xa, xb
-// and mx are raw scores, c_row the row's constant.
+// The four scores of a 16-byte block -> their exponentials as two packed words.
 template <int VARIANT, bool SHIFTED>
-IPTQ_DEV u16x2 bit_exp_pair_requant(int32_t xa, int32_t xb, int32_t mx, uint32_t c_row, const SoftmaxDev &P)
+IPTQ_DEV void bit_exp_block(const int32_t (&x)[4], int32_t mx, const SoftmaxDev &P, uint32_t (&e)[2])
 {
-    const uint32_t da = min((uint32_t)mx - (uint32_t)xa, P.pre_dmax);      // mx >= x: exact as unsigned
-    const uint32_t db = min((uint32_t)mx - (uint32_t)xb, P.pre_dmax);
-    const uint32_t ea = (__umul24(da, (uint32_t)P.pre_m) + c_row) >> P.pre_s;   // r(mx) - r(x), at most D + 1
-    const uint32_t eb = (__umul24(db, (uint32_t)P.pre_m) + c_row) >> P.pre_s;
-    const s16x2 e = {(short)ea, (short)eb};
-    return bit_exp_pair_of_deltas<VARIANT, SHIFTED>((s16x2){0, 0} - e, P);
+    const s16x2 lo = __builtin_amdgcn_cvt_pk_i16(__builtin_elementwise_sub_sat(x[0], mx),
+                                                 __builtin_elementwise_sub_sat(x[1], mx));
+    const s16x2 hi = __builtin_amdgcn_cvt_pk_i16(__builtin_elementwise_sub_sat(x[2], mx),
+                                                 __builtin_elementwise_sub_sat(x[3], mx));
+    const Packed16<4>::U q = bit_exp_of_deltas<VARIANT, SHIFTED, 4>(__builtin_shufflevector(lo, hi, 0, 1, 2, 3), P);
+    e[0] = __builtin_bit_cast(uint32_t, __builtin_shufflevector(q, q, 0, 1));
+    e[1] = __builtin_bit_cast(uint32_t, __builtin_shufflevector(q, q, 2, 3));
+}
+
+// The same with the requantization of the scores folded in (SoftmaxDev::pre_rowconst): the scores
+// and mx are raw, c_row is the row's constant.
+template <int VARIANT, bool SHIFTED>
+IPTQ_DEV void bit_exp_block_requant(const int32_t (&x)[4], int32_t mx, uint32_t c_row, const SoftmaxDev &P,
+                                    uint32_t (&e)[2])
+{
+    Packed16<4>::S d;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t dd = min((uint32_t)mx - (uint32_t)x[i], P.pre_dmax);     // mx >= x: exact as unsigned
+        d[i] = (short)((__umul24(dd, (uint32_t)P.pre_m) + c_row) >> P.pre_s);    // r(mx) - r(x), at most D + 1
+    }
+    const Packed16<4>::U q = bit_exp_of_deltas<VARIANT, SHIFTED, 4>((Packed16<4>::S)0 - d, P);
+    e[0] = __builtin_bit_cast(uint32_t, __builtin_shufflevector(q, q, 0, 1));
+    e[1] = __builtin_bit_cast(uint32_t, __builtin_shufflevector(q, q, 2, 3));
 }
 
 // The arithmetic of one wavefront's slab once its rows sit in registers: exponentials, row
@@ -322,14 +369,12 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
         uint32_t e2[SLOTS][2];
         uint32_t sum = 0;
 #pragma unroll
-        for (int s = 0; s < SLOTS; ++s)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const u16x2 qe = PRE ? bit_exp_pair_requant<VARIANT, MODE == 2>(x[s][2 * h], x[s][2 * h + 1], mx, c_row, P)
-                                     : bit_exp_pair<VARIANT, MODE == 2>(x[s][2 * h], x[s][2 * h + 1], mx, P);
-                sum = __builtin_amdgcn_udot2(qe, (u16x2){1, 1}, sum, false);
-                e2[s][h] = __builtin_bit_cast(uint32_t, qe);
-            }
+        for (int s = 0; s < SLOTS; ++s) {
+            if (PRE) bit_exp_block_requant<VARIANT, MODE == 2>(x[s], mx, c_row, P, e2[s]);
+            else bit_exp_block<VARIANT, MODE == 2>(x[s], mx, P, e2[s]);
+            sum = __builtin_amdgcn_udot2(__builtin_bit_cast(u16x2, e2[s][0]), (u16x2){1, 1}, sum, false);
+            sum = __builtin_amdgcn_udot2(__builtin_bit_cast(u16x2, e2[s][1]), (u16x2){1, 1}, sum, false);
+        }
         sum = row_sum(sum);
         const uint32_t f_top = floor_pow2_div(P.m_bits, sum) << (24 - P.p_shift);   // < 2^24
 #pragma unroll
