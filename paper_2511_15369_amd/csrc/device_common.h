@@ -138,6 +138,24 @@ IPTQ_DEV int32_t clamp_i32(int32_t v, int32_t lo, int32_t hi)
     return r;
 }
 
+// Every launch starts with a cold scalar cache, and a kernel that reads its arguments in dependent
+// steps (which problem of the batch, then that problem's sizes, then its table constants) waits
+// for memory once per step before it can issue its first load.  This touches the first BYTES of
+// the kernel-argument segment at once, one load per 64-byte line, so that one wait covers them
+// all and the steps that follow hit in the cache.
+template <int BYTES>
+IPTQ_DEV void touch_kernel_arguments()
+{
+    typedef const __attribute__((address_space(4))) uint32_t *ArgWords;
+    ArgWords ka = (ArgWords)__builtin_amdgcn_kernarg_segment_ptr();
+    static_assert(BYTES > 0 && BYTES <= 512, "at most eight lines");
+    constexpr int LINES = (BYTES + 63) / 64;
+    uint32_t t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < LINES; ++i) t[i] = ka[16 * i];
+    asm volatile("" ::"s"(t[0]), "s"(t[1]), "s"(t[2]), "s"(t[3]), "s"(t[4]), "s"(t[5]), "s"(t[6]), "s"(t[7]));
+}
+
 // (mask & a) | (~mask & b) in one instruction (written out, the compiler turns a select on a
 // single bit into a test, a compare and a conditional move per element)
 IPTQ_DEV int32_t select_bits_i32(uint32_t mask, int32_t a, int32_t b)

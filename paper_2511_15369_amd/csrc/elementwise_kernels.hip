@@ -95,6 +95,7 @@ static_assert(sizeof(GeluBatch) <= 4096, "kernel arguments are limited to 4 KiB"
 __global__ void __launch_bounds__(256)
 gelu_i8_table_kernel(GeluBatch B)
 {
+    touch_kernel_arguments<8 + sizeof(GeluItem)>();       // the batch header and its first problem
     int it = 0;
     for (int i = 1; i < B.n_items; ++i)
         if (blockIdx.x >= B.item[i].first_wg) it = i;

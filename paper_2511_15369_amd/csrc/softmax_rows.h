@@ -364,7 +364,7 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
                                 int32_t lower, bool any_low, const uint8_t *lut, const SoftmaxDev &P,
                                 const SUM &row_sum = SUM(), uint32_t c_row = 0)
 {
-    if (MODE != 0 && !any_low) {
+    if (MODE != 0 && __builtin_expect(!any_low, 1)) {
         // ---- packed 16-bit path
         uint32_t e2[SLOTS][2];
         uint32_t sum = 0;
@@ -389,7 +389,7 @@ IPTQ_DEV void softmax_slab_math(int32_t (&x)[SLOTS][4], uint32_t (&w)[SLOTS], in
     } else {
         // ---- 32-bit path
         uint32_t sum = 0;
-        if (!any_low) {
+        if (__builtin_expect(!any_low, 1)) {
 #pragma unroll
             for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
@@ -456,6 +456,7 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[kRowsWpb][SLAB * 4];
     __shared__ uint8_t lut_all[kRowsWpb][POSTMODE == PM_GENERAL ? kPostLutBytes : 4];
 
+    touch_kernel_arguments<8 + sizeof(SoftmaxItem)>();   // the batch header and its first problem
     const int lane = threadIdx.x & 63;
     // (the wavefront index as a scalar: everything derived from it - the slab, its table offsets,
     // the runs of mask entries - is then computed on the scalar unit)
@@ -617,10 +618,12 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     // a partial slab and a per-window table take the exact form at once
     constexpr bool FAST_ADD = BIAS && !MASK;
     bool redo = false;                                // wavefront-uniform
-    if (partial) copy_in(std::true_type{}, std::integral_constant<bool, BIAS>{}, std::true_type{});
-    else if (straddle) redo = copy_in(std::false_type{}, std::true_type{}, std::integral_constant<bool, !FAST_ADD>{});
+    // (the rare forms are marked so that the compiler lays the common path out contiguously: every
+    // launch starts with a cold instruction cache)
+    if (__builtin_expect(partial, 0)) copy_in(std::true_type{}, std::integral_constant<bool, BIAS>{}, std::true_type{});
+    else if (__builtin_expect(straddle, 0)) redo = copy_in(std::false_type{}, std::true_type{}, std::integral_constant<bool, !FAST_ADD>{});
     else redo = copy_in(std::false_type{}, std::false_type{}, std::integral_constant<bool, !FAST_ADD>{});
-    if (FAST_ADD && redo) {
+    if (FAST_ADD && __builtin_expect(redo, 0)) {
         // Some score or table entry of this slab is INT32_MIN: the slab once more with the exact
         // addition, one chunk at a time (a rare path: it must cost no registers, not no time).
         i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
@@ -694,7 +697,7 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
             for (int e = 0; e < 4; ++e) mr = max(mr, x[s][e]);
         mr = group_max_i32<K>(mr);
         const bool low = ((uint32_t)mr ^ 0x80000000u) < P.pre_dmax;        // mr - INT32_MIN as unsigned
-        if (__builtin_amdgcn_ballot_w64(low) == 0) {
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(low) == 0, 1)) {
             const int64_t t = (int64_t)mr * (int64_t)P.pre_m + ((int64_t)1 << (P.pre_s - 1));
             const uint32_t smask = (1u << P.pre_s) - 1u;                   // pre_s <= 31 here
             const uint32_t c_row = smask - ((uint32_t)t & smask);
@@ -798,7 +801,7 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
             }
         }
     };
-    if (partial) copy_out(std::true_type{});
+    if (__builtin_expect(partial, 0)) copy_out(std::true_type{});
     else copy_out(std::false_type{});
 #ifdef IPTQ_TIMELINE
     IPTQ_TL(3, wall_clock64());
