@@ -47,9 +47,11 @@ softmax_rowsdyn_kernel(DynArgs A)
 {
     constexpr int RPW = 64 / K;                       // rows per wavefront, a multiple of 4
     extern __shared__ __attribute__((aligned(16))) uint8_t dyn_lds[];
+    touch_kernel_arguments<sizeof(DynArgs)>();
     const SoftmaxDev &P = A.P;
     const int lane = threadIdx.x & 63;
-    const int wv = threadIdx.x >> 6;
+    // (a scalar: the slab, its table offsets and every test on them then run on the scalar unit)
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const uint32_t wpb = blockDim.x >> 6;
     int64_t slab = (int64_t)blockIdx.x * wpb + wv;
     if (A.share_q != 0) {
@@ -80,8 +82,13 @@ softmax_rowsdyn_kernel(DynArgs A)
         v = add_table_chunk(v, bv);
         return v;
     };
-    auto copy_in = [&](auto bias_tag, auto straddle_tag) {
+    // With a table the scores are added with the saturating sum alone, which is the exact value
+    // unless a score or an entry is INT32_MIN, and the smallest operand is tracked beside it (two
+    // lane-ops per score instead of four); returns whether any lane met INT32_MIN, in which case
+    // the caller copies the slab in again with the exact rule.
+    auto copy_in = [&](auto bias_tag, auto straddle_tag) -> bool {
         constexpr bool BIAS = decltype(bias_tag)::value;
+        i32x4 lowest = {0, 0, 0, 0};
         // the additive table's size is not a multiple of four scores and its end falls inside
         // this slab: one chunk takes entries from both ends of the table
         constexpr bool STRADDLE = decltype(straddle_tag)::value;
@@ -113,13 +120,26 @@ softmax_rowsdyn_kernel(DynArgs A)
         }
 #pragma unroll
         for (int i = 0; i < SLOTS; ++i) {
-            const i32x4 t = BIAS ? add_bias(v[i], bv[BIAS ? i % kAhead : 0]) : v[i];
+            i32x4 t = v[i];
+            if (BIAS) {
+                const i32x4 b = bv[i % kAhead];
+                lowest.x = min(min(lowest.x, t.x), b.x);
+                lowest.y = min(min(lowest.y, t.y), b.y);
+                lowest.z = min(min(lowest.z, t.z), b.z);
+                lowest.w = min(min(lowest.w, t.w), b.w);
+                t.x = sat_add_i32(t.x, b.x);
+                t.y = sat_add_i32(t.y, b.y);
+                t.z = sat_add_i32(t.z, b.z);
+                t.w = sat_add_i32(t.w, b.w);
+            }
             if (BIAS && i + kAhead < SLOTS) bv[i % kAhead] = bias_chunk(i + kAhead);
             lds4[chunk_of(i)] = t;
         }
         wave_lds_fence();
+        return BIAS && __builtin_amdgcn_ballot_w64(min(min(lowest.x, lowest.y), min(lowest.z, lowest.w)) == kI32Min) != 0;
     };
-    // the one partial slab of a launch: guarded loads, chunk by chunk
+    // the one partial slab of a launch, and a slab that holds an INT32_MIN operand: guarded loads
+    // and the exact addition, chunk by chunk
     auto copy_in_partial = [&]() {
         i32x4 *lds4 = reinterpret_cast<i32x4 *>(lds);
         uint32_t boff = 0;
@@ -144,13 +164,15 @@ softmax_rowsdyn_kernel(DynArgs A)
         }
         wave_lds_fence();
     };
-    if (partial) copy_in_partial();
+    if (__builtin_expect(partial, 0)) copy_in_partial();
     else if (bias == nullptr) copy_in(std::false_type{}, std::false_type{});
     else {
         const uint32_t pe = (uint32_t)P.bias_period_rows * (uint32_t)cols;
         const uint32_t boff = row_mod_period((uint32_t)(slab * RPW), P) * (uint32_t)cols;
-        if ((pe & 3u) != 0 && boff + (uint32_t)slab_el > pe) copy_in(std::true_type{}, std::true_type{});
-        else copy_in(std::true_type{}, std::false_type{});
+        bool redo;
+        if ((pe & 3u) != 0 && boff + (uint32_t)slab_el > pe) redo = copy_in(std::true_type{}, std::true_type{});
+        else redo = copy_in(std::true_type{}, std::false_type{});
+        if (__builtin_expect(redo, 0)) copy_in_partial();
     }
 
     // ---- this lane's blocks; elements outside the row become "minus infinity"

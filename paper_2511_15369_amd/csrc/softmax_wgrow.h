@@ -44,6 +44,7 @@ softmax_wgrow_kernel(WideArgs A)
     __shared__ uint8_t lut[kPostLutBytes];
     __shared__ int32_t part_max[WAVES];
     __shared__ uint32_t part_sum[WAVES];
+    touch_kernel_arguments<sizeof(WideArgs)>();
     const SoftmaxDev P = A.P;
     const int tid = threadIdx.x;
     const int lane = tid & 63;

@@ -42,9 +42,10 @@ __global__ void __launch_bounds__(256)
 softmax_wide_kernel(WideArgs A)
 {
     __shared__ uint8_t lut_all[4][kPostLutBytes];
+    touch_kernel_arguments<sizeof(WideArgs)>();
     const SoftmaxDev P = A.P;
     const int lane = threadIdx.x & 63;
-    const int wv = threadIdx.x >> 6;
+    const int wv = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // the row index as a scalar
     const int64_t row = (int64_t)blockIdx.x * 4 + wv;
     if (row >= A.rows) return;                        // no workgroup barrier below
 
