@@ -201,8 +201,8 @@ int iptq_softmax_i32(const int32_t *d_scores, const int32_t *d_bias, int64_t bia
  * is materialised: both tables are read beside the scores.  n_windows >= 1, heads >= 1,
  * n_windows * heads * cols < 2^31 (else IPTQ_ERR_SHAPE).
  * Speed: windows of 49 or 144 tokens with a bias run in the slab kernels (the extra table costs
- * about a tenth of the time); any other shape, or a mask without a bias, takes the slow
- * three-pass kernel.
+ * about a sixth of the time; the packed form below costs almost nothing); any other shape, or a
+ * mask without a bias, takes the slow three-pass kernel.
  */
 int iptq_softmax_i32_windowed(const int32_t *d_scores, const int32_t *d_bias,
                               int64_t bias_period_rows, const int32_t *d_mask, int32_t n_windows,
@@ -215,7 +215,9 @@ int iptq_softmax_i32_windowed(const int32_t *d_scores, const int32_t *d_bias,
  * words (device, 8-byte aligned); bit (k mod 64) of word (k div 64) of row [w, q] set means key k
  * is masked for query q of window w; bits beyond `cols` are ignored.  Identical results to
  * iptq_softmax_i32_windowed with the int32 mask those bits stand for; the mask then costs one
- * 8-byte load per row instead of a third table read beside the scores.
+ * 8-byte load per row and two instructions per score instead of a third table read beside the
+ * scores (Swin-B stage 1 at batch 64: 35 us against 34 us without a mask and 40 us with the int32
+ * mask).
  * Speed: windows of 49 tokens with a bias run in the slab kernel; any other shape takes the slow
  * three-pass kernel.
  */
