@@ -279,3 +279,61 @@ def test_windowed_argument_checks():
         assert rc == -2, (n_w, heads)
     torch.cuda.synchronize()
     assert not d_o.any()                                     # nothing was launched
+
+
+def test_windowed_calls_in_a_hip_graph_and_on_views_off_the_16_byte_grid():
+    """The packing call and both windowed softmax forms captured once in a HIP graph and replayed
+    with fresh scores and a fresh mask each time (eager copies and synchronisations between the
+    replays); the score and output tensors are views that start one element off the 16-byte grid."""
+    import torch
+    import paper_2511_15369_amd as ip
+    rng = np.random.default_rng(21)
+    heads, t, side = 4, 49, 14
+    mask0 = workloads.shifted_window_mask(side, side)
+    n_w = mask0.shape[0]
+    rows = 6 * n_w * heads * t - 9
+    bias = np.rint(rng.standard_normal((heads * t, t)) * 8).astype(np.int32)
+    p = prepare.softmax_prepare(2.0 ** -6.5, t, 1)
+    lp = lib_softmax(p)
+    buf_s = torch.zeros(rows * t + 8, dtype=torch.int32, device="cuda")
+    d_s = buf_s[1:1 + rows * t].view(rows, t)              # 4 bytes off the 16-byte grid
+    d_b = torch.from_numpy(bias).cuda()
+    d_m = torch.from_numpy(mask0.copy()).cuda()
+    d_w = torch.zeros((n_w, t, 1), dtype=torch.int64, device="cuda")
+    buf_a = torch.zeros(rows * t + 32, dtype=torch.uint8, device="cuda")
+    buf_b = torch.zeros(rows * t + 32, dtype=torch.uint8, device="cuda")
+    d_a = buf_a[1:1 + rows * t].view(rows, t)               # one byte off
+    d_o = buf_b[3:3 + rows * t].view(rows, t)
+
+    def work():
+        ip.pack_window_mask(d_m, n_w, t, d_w)
+        ip.softmax_i32_windowed_bits(d_s, d_b, heads * t, d_w, n_w, heads, d_a, rows, t, lp)
+        ip.softmax_i32_windowed(d_s, d_b, heads * t, d_m, n_w, heads, d_o, rows, t, lp)
+
+    side_stream = torch.cuda.Stream()
+    side_stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side_stream):
+        work()
+    torch.cuda.current_stream().wait_stream(side_stream)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        work()
+    for rep in range(4):
+        scores = np.rint(rng.standard_normal((rows, t)) * (200 + 400 * rep)).astype(np.int32)
+        mask = np.where(rng.random((n_w, t, t)) < 0.1 * (rep + 1), INT32_MIN, 0).astype(np.int32)
+        d_s.copy_(torch.from_numpy(scores))
+        d_m.copy_(torch.from_numpy(mask))
+        buf_a.fill_(0x5A)
+        buf_b.fill_(0x5A)
+        d_w.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = ref.softmax_i32_windowed(scores, p, bias, heads * t, mask, heads)
+        assert np.array_equal(d_w.cpu().numpy().view(np.uint64), ref.pack_window_mask(mask)), rep
+        assert np.array_equal(d_a.cpu().numpy(), want), rep
+        assert np.array_equal(d_o.cpu().numpy(), want), rep
+        for buf, off in ((buf_a, 1), (buf_b, 3)):          # nothing written around the views
+            host = buf.cpu().numpy()
+            assert (host[:off] == 0x5A).all() and (host[off + rows * t:] == 0x5A).all(), rep
