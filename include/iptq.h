@@ -218,8 +218,8 @@ int iptq_softmax_i32_windowed(const int32_t *d_scores, const int32_t *d_bias,
  * 8-byte load per row and two instructions per score instead of a third table read beside the
  * scores (Swin-B stage 1 at batch 64: 35 us against 34 us without a mask and 40 us with the int32
  * mask).
- * Speed: windows of 49 tokens with a bias run in the slab kernel; any other shape takes the slow
- * three-pass kernel.
+ * Speed: windows of 49 or 144 tokens with a bias run in the slab kernels; any other shape takes
+ * the slow three-pass kernel.
  */
 int iptq_softmax_i32_windowed_bits(const int32_t *d_scores, const int32_t *d_bias,
                                    int64_t bias_period_rows, const uint64_t *d_mask_bits,

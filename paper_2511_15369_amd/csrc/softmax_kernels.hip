@@ -210,7 +210,7 @@ hipError_t softmax_dispatch(const SoftmaxCall *calls, int n_calls, int32_t cols,
             const bool slab_algo = c.algo == IPTQ_ALGO_AUTO || c.algo == IPTQ_ALGO_SLAB;
             const int has_mask = c.mask != nullptr ? 1 : (c.mask_bits != nullptr ? 2 : 0);
             // the mask is compiled in beside a bias, for window sizes whose slab has no more rows
-            // than a window has queries (one bit per key: windows of 49 tokens)
+            // than a window has queries (49 and 144 tokens, in either form of the mask)
             bool mask_ok = true;
             if (has_mask == 1)
                 mask_ok = has_bias && rows_mask_compiled(cols) && rpw <= cols &&

@@ -470,7 +470,7 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     const int32_t *__restrict__ bias = I.bias;
     uint8_t *__restrict__ out = I.out;
     static_assert(!MASK || RPW <= COLS, "a slab may cross one wrap of the query index at most");
-    static_assert(MASKKIND != 2 || COLS <= 64, "one 64-bit word per query");
+    constexpr int MW = MASKKIND == 2 ? (COLS + 63) / 64 : 1;   // 64-bit words of packed mask per query
     const uint32_t lw = blockIdx.x - I.first_wg;
     int64_t slab = (int64_t)lw * kRowsWpb + wv;
     if (BIAS && I.share_q != 0) {
@@ -495,9 +495,9 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     const int b_r = e_r >> 2;                         // its 16-byte block
     const int phi = e_r & 3;                          // and its offset inside that block
 
-    // ---- the packed mask: this lane's row takes word [window, query]; loaded now, used after
-    // the slab has been read back from LDS
-    uint64_t mask_word = 0;
+    // ---- the packed mask: this lane's row takes the words of [window, query]; loaded now, used
+    // after the slab has been read back from LDS
+    uint64_t mask_words[MW] = {};
     if (MASKKIND == 2) {
         const uint32_t row = (uint32_t)(slab * RPW) + (uint32_t)lr;
         uint32_t rm = 0;
@@ -505,7 +505,9 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
             rm = row - (mulhi_u32(row, P.mperiod_magic) >> P.mperiod_sh) * (uint32_t)P.mask_period_rows;
         const uint32_t w = P.group_rows >= 2 ? mulhi_u32(rm, P.group_magic) >> P.group_sh : rm;
         const uint32_t q = (rm - w * (uint32_t)P.group_rows) % (uint32_t)COLS;
-        mask_word = I.mask_bits[w * (uint32_t)COLS + q];
+        const uint64_t *mw = I.mask_bits + (uint64_t)(w * (uint32_t)COLS + q) * MW;
+#pragma unroll
+        for (int i = 0; i < MW; ++i) mask_words[i] = mw[i];
     }
 
     // ---- flat copy of the slab into LDS, bias added on the way.  A partial last slab (the
@@ -664,19 +666,29 @@ IPTQ_DEV void softmax_rows_body(const SoftmaxBatch &B)
     wave_lds_fence();                                 // the slab area is reused for the output
 
     if (MASKKIND == 2) {
-        // element e of slot s is key 4 (s K + j) + e - phi: shift the word once so that its bit
-        // sits at the compile-time position 4 s K + e (keys below 0 and beyond the row read zeros;
-        // those elements are minus infinity already)
+        // element e of slot s is key 4 (s K + j) + e - phi: shift the row's bits once, by
+        // sh = 4 j - phi in [-3, 4 K - 1], so that this bit sits at the compile-time position
+        // 4 s K + e (keys below 0 and beyond the row read zeros; those elements are minus infinity
+        // already).  Word i of the shifted string is bits [sh', sh' + 63] of two neighbouring words.
         const int sh = 4 * j - phi;
-        const uint64_t aligned = sh >= 0 ? mask_word >> sh : mask_word << (-sh);
-        const uint32_t lo = (uint32_t)aligned, hi = (uint32_t)(aligned >> 32);
+        const bool back = sh < 0;
+        const int sh6 = sh & 63;
+        uint64_t aligned[MW];
+#pragma unroll
+        for (int i = 0; i < MW; ++i) {
+            const uint64_t prev = i > 0 ? mask_words[i - 1] : 0, cur = mask_words[i];
+            const uint64_t next = i + 1 < MW ? mask_words[i + 1] : 0;
+            const uint64_t lo64 = back ? prev : cur, hi64 = back ? cur : next;
+            aligned[i] = sh6 == 0 ? lo64 : (lo64 >> sh6) | (hi64 << (64 - sh6));
+        }
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int pos = 4 * s * K + e;
-                if (pos >= 64) continue;              // beyond the word: keys past the row
-                const uint32_t half = pos < 32 ? lo : hi;
+                if (pos >= 64 * MW) continue;         // beyond the words: keys past the row
+                const uint64_t wd = aligned[pos >> 6];
+                const uint32_t half = (pos & 32) ? (uint32_t)(wd >> 32) : (uint32_t)wd;
                 const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int32_t)half, pos & 31, 1);   // all ones: masked
                 x[s][e] = select_bits_i32(m, kI32Min, x[s][e]);
             }
@@ -827,8 +839,8 @@ softmax_rows_masked_kernel(SoftmaxBatch B)
     softmax_rows_body<COLS, K, MODE, true, POSTMODE, 1>(B);
 }
 
-// The mask one bit per key (windows of at most 64 tokens): one 8-byte load per lane and two
-// instructions per score instead of a third table.
+// The mask one bit per key: one to three 8-byte loads per lane (49- and 144-token windows) and
+// two instructions per score instead of a third table.
 template <int COLS, int K, int MODE, int POSTMODE>
 __global__ void __launch_bounds__(64 * kRowsWpb)
 softmax_rows_maskbits_kernel(SoftmaxBatch B)
@@ -865,7 +877,7 @@ constexpr int64_t kRowsAltMaxElements = 90 * 1000 * 1000;
 // The per-window mask is compiled in for the window sizes of shifted-window attention only
 // (7 x 7 and 12 x 12 tokens), with the bias table beside it.
 constexpr bool rows_mask_compiled(int cols) { return cols == 49 || cols == 144; }
-constexpr bool rows_maskbits_compiled(int cols) { return cols == 49; }
+constexpr bool rows_maskbits_compiled(int cols) { return cols == 49 || cols == 144; }
 #define IPTQ_DECLARE_ROWS_LAUNCHER(COLS, K)                                                       \
     template <>                                                                                   \
     hipError_t launch_softmax_rows<COLS, K>(const SoftmaxBatch &, unsigned, bool, int, bool, int, int, hipStream_t);

@@ -94,6 +94,35 @@ def test_windowed_12x12_windows():
     p = prepare.softmax_prepare(2.0 ** -6, 144, 1)
     want = ref.softmax_i32_windowed(scores, p, bias, heads * 144, mask, heads)
     assert np.array_equal(gpu_softmax_windowed(scores, p, bias, heads * 144, mask, heads), want)
+    # the same mask one bit per key: three words per query, in the slab kernel and the three-pass one
+    bits = ref.pack_window_mask(mask)
+    assert bits.shape == (16, 144, 3)
+    for algo in (0, 1):
+        assert np.array_equal(gpu_softmax_windowed_bits(scores, p, bias, heads * 144, bits, heads, algo=algo), want), algo
+
+
+@pytest.mark.parametrize("heads", [4, 3])
+def test_windowed_bits_12x12_dense_masks(heads):
+    """144-token windows with random masks (bits in all three words at every lane offset), masked
+    scores, a fully masked query, both variants and output types, a ragged row count."""
+    rng = np.random.default_rng(80 + heads)
+    t, n_w = 144, 3
+    rows = 3 * n_w * heads * t - 5
+    scores = np.rint(rng.standard_normal((rows, t)) * 300).astype(np.int32)
+    scores[rng.random(scores.shape) < 0.01] = INT32_MIN
+    bias = np.rint(rng.standard_normal((heads * t, t)) * 8).astype(np.int32)
+    mask = np.where(rng.random((n_w, t, t)) < 0.4, INT32_MIN, 0).astype(np.int32)
+    mask[1, 7, :] = INT32_MIN
+    mask[2, :, :] = 0
+    mask[2, np.arange(t), (np.arange(t) * 5) % t] = INT32_MIN
+    bits = ref.pack_window_mask(mask)
+    dirty = bits.copy()
+    dirty[:, :, 2] |= np.uint64(0xFFFFFFFFFFFF0000)          # bits 144..191: no such keys
+    for variant, signed in ((1, 0), (0, 1), (2, 0)):
+        p = prepare.softmax_prepare(2.0 ** -6.5, t, variant, signed)
+        want = ref.softmax_i32_windowed(scores, p, bias, heads * t, mask, heads)
+        for b in (bits, dirty):
+            assert np.array_equal(gpu_softmax_windowed_bits(scores, p, bias, heads * t, b, heads), want), (variant, signed)
 
 
 def test_windowed_other_row_length_takes_the_three_pass_kernel():
