@@ -165,15 +165,26 @@ MARKERS = False      # --markers: a roctx range around every timed region, named
 
 
 def time_steps(fn, reps, before_each=None, leg=None):
-    """reps calls of fn() back to back on the launch stream with an event between them.
-    Returns (mean ms over the whole region, median ms, min ms of the single calls).  With
-    --markers the region sits inside a roctx range called `leg`, so that a rocprofv3 run with
-    --kernel-trace --marker-trace can tell which launches belong to which line of the output."""
+    """reps calls of fn() back to back on the launch stream, twice: once between two events (the
+    mean: nothing but the calls' own launches sits in the timed region), once with an event after
+    every call (median and minimum of the single calls; an event record is a packet of its own on
+    the stream and costs a workload of one or two launches per call several per cent).
+    Returns (mean ms per call, median ms, min ms).  With --markers both passes sit inside a roctx
+    range called `leg`, so that a rocprofv3 run with --kernel-trace --marker-trace can tell which
+    launches belong to which line of the output."""
     import torch
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     if MARKERS and leg:
         torch.cuda.nvtx.range_push(leg)
+    first.record()
+    for i in range(reps):
+        if before_each is not None:
+            before_each(i)
+        fn()
+    last.record()
+    torch.cuda.synchronize()
     ev[0].record()
     for i in range(reps):
         if before_each is not None:
@@ -184,7 +195,7 @@ def time_steps(fn, reps, before_each=None, leg=None):
     if MARKERS and leg:
         torch.cuda.nvtx.range_pop()
     each = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(reps))
-    return ev[0].elapsed_time(ev[reps]) / reps, each[len(each) // 2], each[0]
+    return first.elapsed_time(last) / reps, each[len(each) // 2], each[0]
 
 
 def warm(fn, seconds=0.2):
