@@ -42,7 +42,7 @@ struct SoftmaxItem {
     const int32_t *scores;
     const int32_t *bias;
     const int32_t *mask;  // per-window mask [n_windows, cols, cols] or nullptr
-    const uint64_t *mask_bits;   // the same mask one bit per key, [n_windows, cols] words (cols <= 64), or nullptr
+    const uint64_t *mask_bits;   // the same mask one bit per key, [n_windows, cols, ceil(cols / 64)] words, or nullptr
     uint8_t *out;
     int64_t n_slabs;      // the last one may be partial
     uint32_t first_wg;
