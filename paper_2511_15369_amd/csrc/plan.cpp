@@ -248,7 +248,7 @@ int plan_gelu(const iptq_gelu_params_t *p, int is_i8_entry, GeluDev *out)
 
 // ------------------------------------------------------------------ C ABI: host helpers
 
-extern "C" int iptq_version(void) { return 100; }
+extern "C" int iptq_version(void) { return 200; }   // 0.2.0: window masks, second-degree exponential, Unified Metric
 
 extern "C" const char *iptq_strerror(int code)
 {
