@@ -219,7 +219,9 @@ int iptq_softmax_i32_windowed(const int32_t *d_scores, const int32_t *d_bias,
  * scores (Swin-B stage 1 at batch 64: 35 us against 34 us without a mask and 40 us with the int32
  * mask).
  * Speed: windows of 49 or 144 tokens with a bias run in the slab kernels; any other shape takes
- * the slow three-pass kernel.
+ * the slow three-pass kernel.  Errors as for iptq_softmax_i32_windowed; IPTQ_ERR_ALIGN if
+ * d_mask_bits is not 8-byte aligned; a batched problem that carries both forms of the mask is
+ * refused with IPTQ_ERR_PARAM.
  */
 int iptq_softmax_i32_windowed_bits(const int32_t *d_scores, const int32_t *d_bias,
                                    int64_t bias_period_rows, const uint64_t *d_mask_bits,
